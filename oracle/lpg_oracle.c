@@ -1,0 +1,193 @@
+/*
+ * CPU oracle for layout-propagating GEMM chains.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain reference the GPU library is judged against.  It
+ * shares no code, header, table or constant with the HIP path and must never be
+ * linked or called from it; only tests, the smoke check and the benchmark's
+ * CPU-baseline leg may use it.
+ *
+ * What it holds
+ *   orc_gemm        C = alpha*A*B + beta*C      (paper Eq. 1), fp64, row-major
+ *   orc_gemm_alg1   the paper's Algorithm 1 written out literally (i-j-l loops,
+ *                   alpha applied to every term); used as a brute-force pin
+ *   orc_round_f32 / orc_round_bf16   storage rounding of an fp64 array
+ *   orc_bf16_bits   fp32 bit pattern -> bf16 bit pattern, round-nearest-even
+ *   orc_silu_mul    g*sigmoid(g)*u in fp64 (the activation F_i of Eq. 2 used by
+ *                   the Llama-shaped workload)
+ *   orc_pack / orc_unpack            canonical <-> packed layout, by walking the
+ *                   layout's nested dimensions outermost to innermost (the GPU
+ *                   re-design of the dimension order of Eq. 3)
+ *
+ * The packed layout P(X; F, K) of a matrix with free dimension F (index f) and
+ * contraction dimension K (index k), element size es in {4, 2} bytes:
+ *   KV = 16/es            elements one lane holds in a 128-bit register
+ *   KF = 2*KV             k-extent of one fragment (32 f  x KF k  = 1 KiB)
+ *   KB = 4*KF             k-extent of one block    (32 f  x KB k  = 4 KiB)
+ *   Fp = F rounded up to 32,  Kp = K rounded up to KB  (padding holds zeros)
+ * nested dimensions, outermost to innermost:
+ *   [kb : Kp/KB] [g : Fp/32] [c : 4] [h : 2] [fl : 32] [v : KV]
+ * with  f = 32*g + fl  and  k = KB*kb + KF*c + 8*(v/4) + 4*h + (v%4).
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <stdlib.h>
+#include <math.h>
+
+/* ------------------------------------------------------------------ GEMM */
+
+/* Eq. 1 on row-major fp64 arrays.  For each output row the k-sum is taken in
+ * ascending l with a plain multiply and add per term; alpha multiplies the
+ * finished sum once; beta == 0 means C_in is never read (it may be NULL or
+ * hold NaN).  Rows are independent, so they are spread over OpenMP threads. */
+void orc_gemm(int64_t m, int64_t n, int64_t k, double alpha,
+              const double *A, int64_t lda, const double *B, int64_t ldb,
+              double beta, const double *Cin, int64_t ldcin,
+              double *Cout, int64_t ldc)
+{
+#pragma omp parallel
+    {
+        double *acc = (double *)malloc((size_t)(n > 0 ? n : 1) * sizeof(double));
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < m; ++i) {
+            for (int64_t j = 0; j < n; ++j) acc[j] = 0.0;
+            for (int64_t l = 0; l < k; ++l) {
+                const double a = A[i * lda + l];
+                const double *brow = B + l * ldb;
+                for (int64_t j = 0; j < n; ++j) acc[j] += a * brow[j];
+            }
+            for (int64_t j = 0; j < n; ++j) {
+                double v = alpha * acc[j];
+                if (beta != 0.0) v += beta * Cin[i * ldcin + j];
+                Cout[i * ldc + j] = v;
+            }
+        }
+        free(acc);
+    }
+}
+
+/* Algorithm 1 as printed: scale C by beta, then add alpha*A[i][l]*B[l][j] term
+ * by term.  In place on C.  Single-threaded, small shapes only.  (Unlike
+ * orc_gemm it reads C even when beta == 0, exactly as the listing does.) */
+void orc_gemm_alg1(int64_t m, int64_t n, int64_t k, double alpha,
+                   const double *A, const double *B, double beta, double *C)
+{
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            C[i * n + j] = beta * C[i * n + j];
+            for (int64_t l = 0; l < k; ++l)
+                C[i * n + j] = C[i * n + j] + alpha * A[i * k + l] * B[l * n + j];
+        }
+}
+
+/* ------------------------------------------------------- storage rounding */
+
+/* bf16 = upper 16 bits of an fp32, rounded to nearest, ties to even; NaN stays
+ * NaN (quiet bit forced so that truncation cannot turn it into infinity). */
+uint16_t orc_bf16_bits(uint32_t u)
+{
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu) != 0u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+void orc_bf16_bits_array(const uint32_t *u, uint16_t *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = orc_bf16_bits(u[i]);
+}
+
+void orc_round_f32(double *x, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) x[i] = (double)(float)x[i];
+}
+
+void orc_round_bf16(double *x, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        float f = (float)x[i];
+        uint32_t u;
+        memcpy(&u, &f, 4);
+        u = (uint32_t)orc_bf16_bits(u) << 16;
+        memcpy(&f, &u, 4);
+        x[i] = (double)f;
+    }
+}
+
+/* --------------------------------------------------------------- activation */
+
+void orc_silu_mul(const double *g, const double *u, double *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = g[i] / (1.0 + exp(-g[i])) * u[i];
+}
+
+/* ----------------------------------------------------------- packed layout */
+
+/* Canonical element (f, k) of the matrix being packed.  `k_contig` != 0 means
+ * the canonical array is contiguous along k (address f*ld + k), else along f
+ * (address k*ld + f).  A left operand (free = rows) stored row-major, or a
+ * right operand (free = columns) stored column-major, is k-contiguous. */
+static inline size_t canon_index(int64_t f, int64_t k, int64_t ld, int k_contig)
+{
+    return k_contig ? (size_t)(f * ld + k) : (size_t)(k * ld + f);
+}
+
+/* Pack the view [f0, f0+F) x [k0, k0+K) of a packed parent with extents
+ * (PF, PK).  `canon` points at canonical element (f=0,k=0) OF THE VIEW.
+ * Every block the view touches is written whole: positions whose (f,k) falls
+ * outside the view's logical extent receive zero bytes.  f0 must be a multiple
+ * of 32 and k0 of KB.  Elements are moved as raw es-byte patterns. */
+void orc_pack(const void *canon, int64_t ld, int k_contig, int es,
+              void *packed, int64_t PF, int64_t PK,
+              int64_t f0, int64_t k0, int64_t F, int64_t K)
+{
+    const int64_t KV = 16 / es, KF = 2 * KV, KB = 4 * KF;
+    const int64_t PFp = (PF + 31) / 32 * 32;
+    (void)PK;
+    const int64_t Fp = (F + 31) / 32 * 32, Kp = (K + KB - 1) / KB * KB;
+    const unsigned char *src = (const unsigned char *)canon;
+    unsigned char *dst = (unsigned char *)packed;
+    for (int64_t kb = 0; kb < Kp / KB; ++kb)
+        for (int64_t g = 0; g < Fp / 32; ++g) {
+            /* position of block (kb, g) of the view inside the parent buffer */
+            size_t pos = (size_t)((k0 / KB + kb) * (PFp * KB) + (f0 / 32 + g) * (32 * KB));
+            for (int64_t c = 0; c < 4; ++c)
+                for (int64_t h = 0; h < 2; ++h)
+                    for (int64_t fl = 0; fl < 32; ++fl)
+                        for (int64_t v = 0; v < KV; ++v, ++pos) {
+                            const int64_t f = 32 * g + fl;
+                            const int64_t k = KB * kb + KF * c + 8 * (v / 4) + 4 * h + (v % 4);
+                            if (f < F && k < K)
+                                memcpy(dst + pos * es, src + canon_index(f, k, ld, k_contig) * es, es);
+                            else
+                                memset(dst + pos * es, 0, es);
+                        }
+        }
+}
+
+/* Inverse of orc_pack: copies the view's logical elements back to canonical
+ * order and ignores padding. */
+void orc_unpack(void *canon, int64_t ld, int k_contig, int es,
+                const void *packed, int64_t PF, int64_t PK,
+                int64_t f0, int64_t k0, int64_t F, int64_t K)
+{
+    const int64_t KV = 16 / es, KF = 2 * KV, KB = 4 * KF;
+    const int64_t PFp = (PF + 31) / 32 * 32;
+    (void)PK;
+    const int64_t Fp = (F + 31) / 32 * 32, Kp = (K + KB - 1) / KB * KB;
+    unsigned char *dst = (unsigned char *)canon;
+    const unsigned char *src = (const unsigned char *)packed;
+    for (int64_t kb = 0; kb < Kp / KB; ++kb)
+        for (int64_t g = 0; g < Fp / 32; ++g) {
+            size_t pos = (size_t)((k0 / KB + kb) * (PFp * KB) + (f0 / 32 + g) * (32 * KB));
+            for (int64_t c = 0; c < 4; ++c)
+                for (int64_t h = 0; h < 2; ++h)
+                    for (int64_t fl = 0; fl < 32; ++fl)
+                        for (int64_t v = 0; v < KV; ++v, ++pos) {
+                            const int64_t f = 32 * g + fl;
+                            const int64_t k = KB * kb + KF * c + 8 * (v / 4) + 4 * h + (v % 4);
+                            if (f < F && k < K)
+                                memcpy(dst + canon_index(f, k, ld, k_contig) * es, src + pos * es, es);
+                        }
+        }
+}

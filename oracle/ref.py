@@ -1,0 +1,205 @@
+"""Python face of the CPU oracle.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrappers over oracle/lpg_oracle.c plus a closed-form index function
+for the packed layout, written independently of the C loop nest so that the two
+can be checked against each other.  Nothing here is imported by the product
+package; only tests, the smoke check and the benchmark's CPU-baseline leg use it.
+
+Conventions: matrices are numpy float64, C-contiguous, row-major.  Bit-pattern
+functions take and return unsigned integer arrays.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            path = _build.build()
+        L = ctypes.CDLL(path)
+        i64, dbl, vp, i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_int
+        L.orc_gemm.argtypes = [i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, vp, i64]
+        L.orc_gemm.restype = None
+        L.orc_gemm_alg1.argtypes = [i64, i64, i64, dbl, vp, vp, dbl, vp]
+        L.orc_gemm_alg1.restype = None
+        L.orc_round_f32.argtypes = [vp, i64]
+        L.orc_round_bf16.argtypes = [vp, i64]
+        L.orc_bf16_bits.argtypes = [ctypes.c_uint32]
+        L.orc_bf16_bits.restype = ctypes.c_uint16
+        L.orc_bf16_bits_array.argtypes = [vp, vp, i64]
+        L.orc_silu_mul.argtypes = [vp, vp, vp, i64]
+        L.orc_pack.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64]
+        L.orc_unpack.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64]
+        _lib = L
+    return _lib
+
+
+def _f64(x):
+    return np.ascontiguousarray(x, dtype=np.float64)
+
+
+# ------------------------------------------------------------------ GEMM (Eq. 1)
+
+def gemm(A, B, alpha=1.0, beta=0.0, C=None):
+    """alpha*A@B + beta*C on fp64 row-major arrays (Eq. 1).  beta == 0 never reads C."""
+    A = _f64(A)
+    B = _f64(B)
+    m, k = A.shape
+    k2, n = B.shape
+    if k != k2:
+        raise ValueError("inner dimensions differ")
+    out = np.empty((m, n), dtype=np.float64)
+    if beta != 0.0:
+        if C is None:
+            raise ValueError("beta != 0 needs C")
+        C = _f64(C)
+        if C.shape != (m, n):
+            raise ValueError("C has the wrong shape")
+        cptr, ldc_in = C.ctypes.data, n
+    else:
+        cptr, ldc_in = None, 0
+    lib().orc_gemm(m, n, k, float(alpha), A.ctypes.data, k, B.ctypes.data, n,
+                   float(beta), cptr, ldc_in, out.ctypes.data, n)
+    return out
+
+
+def gemm_alg1(A, B, alpha=1.0, beta=0.0, C=None):
+    """Algorithm 1 literally (brute-force pin); C defaults to zeros."""
+    A = _f64(A)
+    B = _f64(B)
+    m, k = A.shape
+    _, n = B.shape
+    out = np.zeros((m, n), dtype=np.float64) if C is None else _f64(C).copy()
+    lib().orc_gemm_alg1(m, n, k, float(alpha), A.ctypes.data, B.ctypes.data, float(beta),
+                        out.ctypes.data)
+    return out
+
+
+def chain(X, Bs, alphas=None):
+    """Right-multiplication chain X*B_1*...*B_S (Eq. 2 with identity activations)."""
+    C = _f64(X)
+    for i, B in enumerate(Bs):
+        C = gemm(C, B, alpha=1.0 if alphas is None else alphas[i])
+    return C
+
+
+# ------------------------------------------------------------- storage rounding
+
+def round_f32(x):
+    y = _f64(x).copy()
+    lib().orc_round_f32(y.ctypes.data, y.size)
+    return y
+
+
+def round_bf16(x):
+    y = _f64(x).copy()
+    lib().orc_round_bf16(y.ctypes.data, y.size)
+    return y
+
+
+def bf16_bits(u32):
+    """fp32 bit patterns (uint32 array) -> bf16 bit patterns (uint16), RNE."""
+    u32 = np.ascontiguousarray(u32, dtype=np.uint32)
+    out = np.empty(u32.shape, dtype=np.uint16)
+    lib().orc_bf16_bits_array(u32.ctypes.data, out.ctypes.data, u32.size)
+    return out
+
+
+def silu_mul(g, u):
+    g = _f64(g)
+    u = _f64(u)
+    out = np.empty_like(g)
+    lib().orc_silu_mul(g.ctypes.data, u.ctypes.data, out.ctypes.data, g.size)
+    return out
+
+
+# ------------------------------------------------------------------ packed layout
+
+def layout_consts(es):
+    """(KV, KF, KB) for element size es in bytes."""
+    kv = 16 // es
+    return kv, 2 * kv, 8 * kv
+
+
+def padded_extents(F, K, es):
+    _, _, kb = layout_consts(es)
+    return (F + 31) // 32 * 32, (K + kb - 1) // kb * kb
+
+
+def packed_elems(F, K, es):
+    fp, kp = padded_extents(F, K, es)
+    return fp * kp
+
+
+def packed_offset(f, k, PF, es):
+    """Closed-form element offset of logical (f, k) inside a packed parent whose
+    free extent is PF.  Derived from the nested-dimension order by summing
+    index * stride for each dimension; works on numpy integer arrays."""
+    kv, kf, kb = layout_consts(es)
+    f = np.asarray(f, dtype=np.int64)
+    k = np.asarray(k, dtype=np.int64)
+    pfp = (PF + 31) // 32 * 32
+    blk = (k // kb) * (pfp * kb) + (f // 32) * (32 * kb)
+    kin = k % kb
+    c = kin // kf
+    r = kin % kf              # position inside the fragment's k range
+    h = (r // 4) % 2
+    v = 4 * (r // 8) + r % 4
+    return blk + c * (32 * kf) + h * (32 * kv) + (f % 32) * kv + v
+
+
+def _raw(a, es):
+    dt = {4: np.uint32, 2: np.uint16}[es]
+    a = np.ascontiguousarray(a)
+    if a.dtype.itemsize != es:
+        raise ValueError("element size mismatch")
+    return a.view(dt)
+
+
+def pack(canon, free_is_rows, es, parent=None, origin=(0, 0), out=None):
+    """Pack a 2-D canonical row-major array of raw elements.
+
+    free_is_rows=True gives the left-operand layout P(X; rows, cols); False
+    gives the right-operand layout P(X; cols, rows).  `parent` = (PF, PK)
+    extents of the packed parent, `origin` = (f0, k0) of this view inside it.
+    Returns (or fills `out`, a flat raw array of the parent's padded size).
+    """
+    a = _raw(canon, es)
+    rows, cols = a.shape
+    F, K = (rows, cols) if free_is_rows else (cols, rows)
+    PF, PK = parent if parent is not None else (F, K)
+    if out is None:
+        out = np.zeros(packed_elems(PF, PK, es), dtype=a.dtype)
+    lib().orc_pack(a.ctypes.data, cols, 1 if free_is_rows else 0, es, out.ctypes.data,
+                   PF, PK, origin[0], origin[1], F, K)
+    return out
+
+
+def unpack(packed, rows, cols, free_is_rows, es, parent=None, origin=(0, 0)):
+    """Inverse of pack(): returns a (rows, cols) raw array."""
+    p = _raw(packed, es)
+    F, K = (rows, cols) if free_is_rows else (cols, rows)
+    PF, PK = parent if parent is not None else (F, K)
+    out = np.zeros((rows, cols), dtype=p.dtype)
+    lib().orc_unpack(out.ctypes.data, cols, 1 if free_is_rows else 0, es, p.ctypes.data,
+                     PF, PK, origin[0], origin[1], F, K)
+    return out
+
+
+# ------------------------------------------------------------------ error metric
+
+def rel_frobenius(got, ref):
+    """||got - ref||_F / ||ref||_F in fp64."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref.ravel())
+    num = np.linalg.norm((got - ref).ravel())
+    return float(num / den) if den > 0 else float(num)
