@@ -1,0 +1,224 @@
+/*
+ * lpg.h - layout-propagating GEMM chains on one MI355X (gfx950).  C ABI.
+ *
+ * A chain of dependent GEMMs  C_i = alpha_i * A_i * B_i + beta_i * C_i  (paper
+ * Eq. 1, chained as in Eq. 2) in which every intermediate stays in the packed,
+ * MFMA-fragment-ordered layout that the next GEMM's loads consume: matrices are
+ * packed once at the chain's entry and unpacked once at its exit (the paper's
+ * Initial / Intermediate / Ending decomposition, section III-A), so row/column
+ * major semantics hold only at the boundaries.
+ *
+ * General rules for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; descriptors and
+ *     stage arrays are HOST memory read during the call only.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued asynchronously; no call synchronises or allocates.
+ *   - Return value: LPG_OK (0) or a negative lpg_status.  Errors are detected on
+ *     the host before anything is launched; lpg_last_error() gives a message.
+ *   - Packed buffers must be 16-byte aligned (LPG_EALIGN otherwise).
+ *
+ * The packed layout P(X; F, K) (this library's re-design, for 64-lane MFMA
+ * operand registers, of the tile order of Eq. 3).  X has a free dimension F and
+ * a contraction dimension K.  With es = element size, KV = 16/es, KF = 2*KV,
+ * KB = 4*KF (fp32: 4, 8, 32; bf16: 8, 16, 64), F padded to 32 and K to KB with
+ * zeros, the nested dimensions are, outermost to innermost,
+ *        [K/KB] [F/32] [4 fragments] [2 lane halves h] [32 lanes fl] [KV v]
+ * and  k = KB*kb + KF*c + 8*(v/4) + 4*h + v%4,  f = 32*g + fl.
+ * One fragment (1 KiB) is exactly one 128-bit-per-lane wave load and is the
+ * operand register image of v_mfma_f32_32x32x2_f32 (four of them per fragment)
+ * or v_mfma_f32_32x32x16_bf16 (one).  A 32x32 accumulator tile, as the MFMA
+ * leaves it in registers, is already a run of fragments of the output's packed
+ * layout, so the epilogue stores it with plain 128-bit stores.
+ *   LPG_PACKED_A = P(X; F = rows, K = cols): X will be a LEFT operand.
+ *   LPG_PACKED_B = P(X; F = cols, K = rows): X will be a RIGHT operand.
+ * PACKED_A of X and PACKED_B of X^T are the same bytes.
+ */
+#ifndef LPG_H
+#define LPG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LPG_OK = 0,
+    LPG_EINVAL = -1,       /* bad argument (NULL, negative size, shape mismatch)        */
+    LPG_ELAYOUT = -2,      /* descriptor kinds / packed geometry do not fit together    */
+    LPG_EUNSUPPORTED = -3, /* dtype combination or option not implemented               */
+    LPG_EALIGN = -4,       /* pointer or view origin not aligned as the layout needs    */
+    LPG_EHIP = -5,         /* a HIP runtime call failed                                 */
+    LPG_EWORKSPACE = -6    /* lpg_chain: workspace too small                            */
+} lpg_status;
+
+typedef enum { LPG_F32 = 0, LPG_BF16 = 1 } lpg_dtype;
+
+typedef enum {
+    LPG_ROW_MAJOR = 0, /* canonical, boundaries only */
+    LPG_COL_MAJOR = 1, /* canonical, boundaries only */
+    LPG_PACKED_A = 2,
+    LPG_PACKED_B = 3
+} lpg_kind;
+
+/*
+ * Descriptor of a (batched) matrix or of a view into a larger parent.
+ *
+ * rows, cols          logical extent of one matrix.
+ * ld                  canonical kinds: leading dimension in elements (0 = tight:
+ *                     parent_cols for row-major, parent_rows for column-major).
+ * parent_rows/cols    extent of the parent this view lives in (0,0 = the view is
+ *                     the whole parent).  For packed kinds the parent fixes the
+ *                     padded geometry (block strides).
+ * row0, col0          origin of the view inside the parent.  Packed kinds: the
+ *                     free-dimension origin must be a multiple of 32 and the
+ *                     contraction-dimension origin a multiple of KB, and a view
+ *                     extent that is not such a multiple must end at the parent's
+ *                     edge.  This is the restricted form of the paper's "store
+ *                     stride / block order" parameters (section III-C) that
+ *                     per-head slices of Q, K, V, O need (section IV-A).
+ * batch               number of matrices (0 is read as 1).
+ * batch_div           matrix b uses slot b / batch_div (0 is read as 1); lets
+ *                     several query heads share one key/value head instead of
+ *                     replicating it (Alg. 2, head-wise replication step).
+ * batch_stride        elements between the parents of consecutive slots (0 = all
+ *                     slots share one parent).
+ * batch_row_step,
+ * batch_col_step      shift of the view origin per slot inside the parent.
+ */
+typedef struct lpg_desc {
+    int32_t kind;
+    int32_t dtype;
+    int64_t rows, cols;
+    int64_t ld;
+    int64_t parent_rows, parent_cols;
+    int64_t row0, col0;
+    int32_t batch;
+    int32_t batch_div;
+    int64_t batch_stride;
+    int64_t batch_row_step, batch_col_step;
+} lpg_desc;
+
+/* Elementwise operations on packed buffers (layout-oblivious; paper II-C, IV-A). */
+typedef enum {
+    LPG_EW_SCALE = 0,   /* out = s * x0            (x1 ignored)                          */
+    LPG_EW_ADD = 1,     /* out = x0 + s * x1                                             */
+    LPG_EW_SILU_MUL = 2 /* out = x0 * sigmoid(x0) * x1   (SiLU(gate) * up)               */
+} lpg_ew_op;
+
+/* Operations fused into the GEMM epilogue, applied to v = alpha*acc + beta*C_in. */
+typedef enum {
+    LPG_EPI_NONE = 0,      /* out = v                                                    */
+    LPG_EPI_SILU = 1,      /* out = v * sigmoid(v)                                       */
+    LPG_EPI_GATE_SILU = 2  /* out = g * sigmoid(g) * v, g = epi_arg at the same position
+                              (epi_arg: device buffer laid out and typed exactly as C_out) */
+} lpg_epilogue_op;
+
+/* Bytes of the allocation a descriptor addresses (all slots, padding included
+ * for packed kinds).  Returns 0 if the descriptor is invalid. */
+size_t lpg_packed_bytes(const lpg_desc *d);
+
+/* Host-side index function of the layout: element offset (in elements, from the
+ * buffer start) of logical element (row, col) of matrix b.  Works for canonical
+ * and packed kinds.  Returns LPG_OK or LPG_EINVAL. */
+int lpg_layout_offset(const lpg_desc *d, int64_t b, int64_t row, int64_t col, int64_t *offset);
+
+/*
+ * lpg_pack - canonical -> packed, once at the chain's entry (the packing step of
+ * the GotoBLAS loop nest, Fig. 2c, done for the whole matrix; paper II-A).
+ * src_d: ROW_MAJOR or COL_MAJOR; dst_d: PACKED_A or PACKED_B, same rows/cols/batch.
+ * Writes every block the view touches, zero-filling padding.  dtype pairs:
+ * f32->f32, bf16->bf16 (bit-exact copies), f32->bf16 (round to nearest even).
+ */
+int lpg_pack(const void *src, const lpg_desc *src_d, void *dst, const lpg_desc *dst_d,
+             void *stream);
+
+/*
+ * lpg_unpack - packed -> canonical, once at the chain's exit (the reordering the
+ * paper's Default micro-kernel performs, III-B).  Padding is dropped.  dtype
+ * pairs: f32->f32, bf16->bf16 (bit-exact), bf16->f32 (exact widening).
+ */
+int lpg_unpack(const void *src, const lpg_desc *src_d, void *dst, const lpg_desc *dst_d,
+               void *stream);
+
+/*
+ * lpg_gemm_packed - the Intermediate kernel (III-A.2) with the Propagate-Layout
+ * micro-kernel (III-B):  C_out = epilogue(alpha * A * B + beta * C_in), all
+ * operands packed, C written directly as operand fragments of the next GEMM.
+ *   a_d.kind == LPG_PACKED_A, b_d.kind == LPG_PACKED_B, a_d.cols == b_d.rows.
+ *   c_d.kind == LPG_PACKED_A (C will be a left operand) or LPG_PACKED_B (right).
+ *   dtypes: (f32, f32 -> f32), (bf16, bf16 -> bf16 or f32); accumulation is fp32.
+ *   C_in: laid out and typed as c_d; may be NULL iff beta == 0, and is never read
+ *   when beta == 0 (the packed-C requirement of III-B, which this library
+ *   supports).  C_in == C_out (in place) is allowed; C_out must not alias A or B.
+ *   Batches: c_d.batch matrices; A, B use slot b / batch_div of their descriptors.
+ *   Padding of C_out is written as zeros.
+ */
+int lpg_gemm_packed(float alpha, const void *A, const lpg_desc *a_d, const void *B,
+                    const lpg_desc *b_d, float beta, const void *C_in, void *C_out,
+                    const lpg_desc *c_d, int epilogue_op, const void *epi_arg, void *stream);
+
+/*
+ * lpg_elementwise_packed - layout-oblivious elementwise op over whole packed (or
+ * canonical, tightly stored) buffers sharing one descriptor `d` (no sub-views).
+ * Every supported op maps zero padding to zero.  Math in fp32; bf16 results are
+ * rounded to nearest even.  x1 may be NULL for LPG_EW_SCALE.  In place is allowed.
+ */
+int lpg_elementwise_packed(int op, const void *x0, const void *x1, float s, void *out,
+                           const lpg_desc *d, void *stream);
+
+/* One stage of a chain. */
+typedef enum {
+    LPG_STAGE_PACK = 0,
+    LPG_STAGE_GEMM = 1,
+    LPG_STAGE_ELEMENTWISE = 2,
+    LPG_STAGE_UNPACK = 3
+} lpg_stage_type;
+
+typedef struct lpg_stage {
+    int32_t type;       /* lpg_stage_type                                               */
+    int32_t op;         /* GEMM: lpg_epilogue_op; ELEMENTWISE: lpg_ew_op                */
+    float alpha, beta;  /* GEMM                                                         */
+    float scalar;       /* ELEMENTWISE: s                                               */
+    int32_t reserved;
+    const void *in0;    /* PACK/UNPACK: src; GEMM: A; ELEMENTWISE: x0                   */
+    const void *in1;    /* GEMM: B; ELEMENTWISE: x1                                     */
+    const void *in2;    /* GEMM: C_in (or NULL)                                         */
+    const void *epi_arg;/* GEMM: epilogue argument (or NULL)                            */
+    void *out;
+    lpg_desc in0_d;     /* descriptor of in0                                            */
+    lpg_desc in1_d;     /* GEMM: descriptor of B                                        */
+    lpg_desc out_d;     /* descriptor of out (and of in2, epi_arg, ELEMENTWISE inputs)  */
+} lpg_stage;
+
+typedef enum {
+    LPG_CHAIN_PROPAGATED = 0, /* intermediates stay packed (LP-GEMM, Fig. 1b)           */
+    LPG_CHAIN_CANONICAL = 1   /* control: every intermediate is unpacked to row-major
+                                 by its producer and re-packed for its consumer, as a
+                                 BLAS-API chain does (Fig. 1a); same kernels, same result */
+} lpg_chain_mode;
+
+/* Workspace bytes lpg_chain needs (0 in propagated mode).  SIZE_MAX on error. */
+size_t lpg_chain_workspace_bytes(const lpg_stage *stages, int n, int mode);
+
+/*
+ * lpg_chain - enqueue a whole chain (Eq. 2) on one stream.  Checks that each
+ * packed input that an earlier stage produced is read with the packed geometry
+ * it was written in (LPG_ELAYOUT otherwise), then launches the stages in order.
+ * In LPG_CHAIN_CANONICAL mode `workspace` (device, 256-byte aligned, at least
+ * lpg_chain_workspace_bytes) holds the row-major copies of the intermediates.
+ */
+int lpg_chain(const lpg_stage *stages, int n, int mode, void *workspace,
+              size_t workspace_bytes, void *stream);
+
+/* Message for the last error on this thread ("" if none). */
+const char *lpg_last_error(void);
+
+/* Library version string. */
+const char *lpg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LPG_H */

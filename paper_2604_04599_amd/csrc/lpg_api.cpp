@@ -1,0 +1,672 @@
+// Host side of the C ABI: descriptor validation, view arithmetic, kernel argument
+// marshalling, and the chain executor (propagated and canonical-control modes).
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "lpg_internal.h"
+
+namespace lpg {
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+static inline bool is_packed(int kind) { return kind == LPG_PACKED_A || kind == LPG_PACKED_B; }
+static inline bool is_canon(int kind) { return kind == LPG_ROW_MAJOR || kind == LPG_COL_MAJOR; }
+
+static int check_common(const lpg_desc *d, const char *what)
+{
+    if (!d) return fail(LPG_EINVAL, "%s: descriptor is NULL", what);
+    if (d->kind < LPG_ROW_MAJOR || d->kind > LPG_PACKED_B) return fail(LPG_EINVAL, "%s: bad kind %d", what, d->kind);
+    if (d->dtype != LPG_F32 && d->dtype != LPG_BF16) return fail(LPG_EUNSUPPORTED, "%s: bad dtype %d", what, d->dtype);
+    if (d->rows < 0 || d->cols < 0) return fail(LPG_EINVAL, "%s: negative extent", what);
+    if (d->rows > 0x7fffffff || d->cols > 0x7fffffff) return fail(LPG_EINVAL, "%s: extent over 2^31-1", what);
+    if (d->batch < 0 || d->batch_div < 0) return fail(LPG_EINVAL, "%s: negative batch", what);
+    if (d->row0 < 0 || d->col0 < 0 || d->batch_stride < 0 || d->batch_row_step < 0 || d->batch_col_step < 0)
+        return fail(LPG_EINVAL, "%s: negative origin, step or stride", what);
+    if ((d->parent_rows == 0) != (d->parent_cols == 0))
+        return fail(LPG_EINVAL, "%s: parent_rows and parent_cols must both be set or both be 0", what);
+    return LPG_OK;
+}
+
+static inline int nbatch(const lpg_desc *d) { return d->batch > 0 ? d->batch : 1; }
+static inline int bdiv(const lpg_desc *d) { return d->batch_div > 0 ? d->batch_div : 1; }
+static inline int nslots(const lpg_desc *d) { return (nbatch(d) + bdiv(d) - 1) / bdiv(d); }
+
+// Reduce a packed descriptor to a PView and validate its geometry.
+static int make_pview(const lpg_desc *d, const char *what, PView *v)
+{
+    int rc = check_common(d, what);
+    if (rc) return rc;
+    if (!is_packed(d->kind)) return fail(LPG_ELAYOUT, "%s: expected a packed kind, got %d", what, d->kind);
+    const bool tr = d->kind == LPG_PACKED_B;
+    v->dtype = d->dtype;
+    v->es = elem_size(d->dtype);
+    const int64_t KB = kb_of(d->dtype);
+    const int64_t prow = d->parent_rows ? d->parent_rows : d->rows;
+    const int64_t pcol = d->parent_cols ? d->parent_cols : d->cols;
+    v->transposed = tr;
+    v->F = tr ? d->cols : d->rows;
+    v->K = tr ? d->rows : d->cols;
+    v->PF = tr ? pcol : prow;
+    v->PK = tr ? prow : pcol;
+    v->f0 = tr ? d->col0 : d->row0;
+    v->k0 = tr ? d->row0 : d->col0;
+    v->fstep = tr ? d->batch_col_step : d->batch_row_step;
+    v->kstep = tr ? d->batch_row_step : d->batch_col_step;
+    v->batch = nbatch(d);
+    v->bdiv = bdiv(d);
+    v->bstride = d->batch_stride;
+    v->PFp = round_up(v->PF, 32);
+    v->PKp = round_up(v->PK, KB);
+    const int ns = nslots(d);
+    if (v->f0 % 32 || v->fstep % 32)
+        return fail(LPG_EALIGN, "%s: free-dimension origin/step must be a multiple of 32", what);
+    if (v->k0 % KB || v->kstep % KB)
+        return fail(LPG_EALIGN, "%s: contraction-dimension origin/step must be a multiple of %d", what, (int)KB);
+    const int64_t f_last = v->f0 + (ns - 1) * v->fstep, k_last = v->k0 + (ns - 1) * v->kstep;
+    if (f_last + v->F > v->PF || k_last + v->K > v->PK)
+        return fail(LPG_EINVAL, "%s: view exceeds its parent", what);
+    // a ragged extent may only sit at the parent's edge, where its padding is the parent's
+    if (v->F % 32 && (ns > 1 ? v->fstep != 0 : false))
+        return fail(LPG_EALIGN, "%s: stepped views need a free extent that is a multiple of 32", what);
+    if (v->K % KB && (ns > 1 ? v->kstep != 0 : false))
+        return fail(LPG_EALIGN, "%s: stepped views need a contraction extent that is a multiple of %d", what, (int)KB);
+    if (v->F % 32 && v->f0 + v->F != v->PF)
+        return fail(LPG_EALIGN, "%s: a free extent that is not a multiple of 32 must end at the parent's edge", what);
+    if (v->K % KB && v->k0 + v->K != v->PK)
+        return fail(LPG_EALIGN, "%s: a contraction extent that is not a multiple of %d must end at the parent's edge", what, (int)KB);
+    if (ns > 1 && v->bstride != 0 && v->bstride < v->PFp * v->PKp)
+        return fail(LPG_EINVAL, "%s: batch_stride smaller than one packed parent", what);
+    if ((v->bstride * v->es) % 16)
+        return fail(LPG_EALIGN, "%s: batch_stride must keep 16-byte alignment", what);
+    v->kb_stride = v->PFp * KB * v->es;
+    v->origin = (v->k0 / KB) * v->kb_stride + (v->f0 / 32) * (int64_t)kBlockBytes;
+    v->slot_step = v->bstride * v->es + (v->kstep / KB) * v->kb_stride + (v->fstep / 32) * (int64_t)kBlockBytes;
+    return LPG_OK;
+}
+
+static int make_cview(const lpg_desc *d, const char *what, CView *v)
+{
+    int rc = check_common(d, what);
+    if (rc) return rc;
+    if (!is_canon(d->kind)) return fail(LPG_ELAYOUT, "%s: expected ROW_MAJOR or COL_MAJOR, got kind %d", what, d->kind);
+    const int64_t prow = d->parent_rows ? d->parent_rows : d->rows;
+    const int64_t pcol = d->parent_cols ? d->parent_cols : d->cols;
+    const bool rm = d->kind == LPG_ROW_MAJOR;
+    const int64_t tight = rm ? pcol : prow;
+    const int64_t ld = d->ld ? d->ld : tight;
+    if (ld < tight) return fail(LPG_EINVAL, "%s: ld %lld smaller than the parent's extent %lld", what, (long long)ld, (long long)tight);
+    v->dtype = d->dtype;
+    v->es = elem_size(d->dtype);
+    v->rows = d->rows;
+    v->cols = d->cols;
+    v->row_stride = rm ? ld : 1;
+    v->col_stride = rm ? 1 : ld;
+    v->batch = nbatch(d);
+    v->bdiv = bdiv(d);
+    const int ns = nslots(d);
+    if (d->row0 + (ns - 1) * d->batch_row_step + d->rows > prow ||
+        d->col0 + (ns - 1) * d->batch_col_step + d->cols > pcol)
+        return fail(LPG_EINVAL, "%s: view exceeds its parent", what);
+    v->origin = d->row0 * v->row_stride + d->col0 * v->col_stride;
+    v->slot_step = d->batch_stride + d->batch_row_step * v->row_stride + d->batch_col_step * v->col_stride;
+    return LPG_OK;
+}
+
+static size_t desc_bytes(const lpg_desc *d)
+{
+    if (check_common(d, "desc")) return 0;
+    const int ns = nslots(d);
+    const int es = elem_size(d->dtype);
+    const int64_t prow = d->parent_rows ? d->parent_rows : d->rows;
+    const int64_t pcol = d->parent_cols ? d->parent_cols : d->cols;
+    int64_t one;
+    if (is_packed(d->kind)) {
+        const bool tr = d->kind == LPG_PACKED_B;
+        const int64_t PF = tr ? pcol : prow, PK = tr ? prow : pcol;
+        one = round_up(PF, 32) * round_up(PK, kb_of(d->dtype));
+    } else {
+        const bool rm = d->kind == LPG_ROW_MAJOR;
+        const int64_t tight = rm ? pcol : prow;
+        const int64_t ld = d->ld ? d->ld : tight;
+        one = ld * (rm ? prow : pcol);
+    }
+    const int64_t total = (d->batch_stride ? (int64_t)(ns - 1) * d->batch_stride : 0) + one;
+    return (size_t)total * es;
+}
+
+static int check_ptr16(const void *p, const char *what)
+{
+    if (!p) return fail(LPG_EINVAL, "%s: NULL pointer", what);
+    if ((uintptr_t)p % 16) return fail(LPG_EALIGN, "%s: packed buffers must be 16-byte aligned", what);
+    return LPG_OK;
+}
+
+// ------------------------------------------------------------------------ pack / unpack
+
+static int do_pack_unpack(bool pack, const void *canon, const lpg_desc *cd, const void *packed,
+                          const lpg_desc *pd, hipStream_t st)
+{
+    const char *name = pack ? "lpg_pack" : "lpg_unpack";
+    PView pv;
+    CView cv;
+    int rc = make_pview(pd, pack ? "lpg_pack dst" : "lpg_unpack src", &pv);
+    if (rc) return rc;
+    rc = make_cview(cd, pack ? "lpg_pack src" : "lpg_unpack dst", &cv);
+    if (rc) return rc;
+    if (cd->rows != pd->rows || cd->cols != pd->cols)
+        return fail(LPG_EINVAL, "%s: source and destination extents differ", name);
+    if (nbatch(cd) != nbatch(pd)) return fail(LPG_EINVAL, "%s: batch counts differ", name);
+    const bool conv_ok = pack ? (cv.dtype == pv.dtype || (cv.dtype == LPG_F32 && pv.dtype == LPG_BF16))
+                              : (cv.dtype == pv.dtype || (pv.dtype == LPG_BF16 && cv.dtype == LPG_F32));
+    if (!conv_ok) return fail(LPG_EUNSUPPORTED, "%s: dtype conversion not supported", name);
+    if (!canon) return fail(LPG_EINVAL, "%s: NULL canonical pointer", name);
+    rc = check_ptr16(packed, name);
+    if (rc) return rc;
+    if ((uintptr_t)canon % cv.es) return fail(LPG_EALIGN, "%s: canonical pointer not element aligned", name);
+    if (pv.F == 0 || pv.K == 0) return LPG_OK;
+
+    PackArgs a;
+    a.canon = (const char *)canon + cv.origin * cv.es;
+    a.packed = (char *)packed + pv.origin;
+    a.sf = pv.transposed ? cv.col_stride : cv.row_stride;
+    a.sk = pv.transposed ? cv.row_stride : cv.col_stride;
+    a.c_slot = cv.slot_step * cv.es;
+    a.p_kbs = pv.kb_stride;
+    a.p_slot = pv.slot_step;
+    a.c_div = cv.bdiv;
+    a.p_div = pv.bdiv;
+    a.F = (int32_t)pv.F;
+    a.K = (int32_t)pv.K;
+    a.ngroups = (int32_t)((pv.F + 31) / 32);
+    a.nkb = (int32_t)((pv.K + kb_of(pv.dtype) - 1) / kb_of(pv.dtype));
+    a.batch = pv.batch;
+    if (a.nkb > 65535 || a.batch > 65535) return fail(LPG_EUNSUPPORTED, "%s: more than 65535 K blocks or batches", name);
+    hipError_t e = pack ? launch_pack(a, cv.dtype, pv.dtype, st) : launch_unpack(a, pv.dtype, cv.dtype, st);
+    if (e != hipSuccess) return fail(LPG_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LPG_OK;
+}
+
+// ------------------------------------------------------------------------------- GEMM
+
+static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *B, const lpg_desc *b_d,
+                   float beta, const void *C_in, void *C_out, const lpg_desc *c_d, int epi,
+                   const void *epi_arg, hipStream_t st, bool launch)
+{
+    PView av, bv, cv;
+    int rc = make_pview(a_d, "lpg_gemm_packed A", &av);
+    if (rc) return rc;
+    rc = make_pview(b_d, "lpg_gemm_packed B", &bv);
+    if (rc) return rc;
+    rc = make_pview(c_d, "lpg_gemm_packed C", &cv);
+    if (rc) return rc;
+    if (a_d->kind != LPG_PACKED_A) return fail(LPG_ELAYOUT, "lpg_gemm_packed: A must be LPG_PACKED_A");
+    if (b_d->kind != LPG_PACKED_B) return fail(LPG_ELAYOUT, "lpg_gemm_packed: B must be LPG_PACKED_B");
+    if (a_d->cols != b_d->rows)
+        return fail(LPG_EINVAL, "lpg_gemm_packed: inner dimensions differ (A cols %lld, B rows %lld)",
+                    (long long)a_d->cols, (long long)b_d->rows);
+    if (c_d->rows != a_d->rows || c_d->cols != b_d->cols)
+        return fail(LPG_EINVAL, "lpg_gemm_packed: C is %lldx%lld but A*B is %lldx%lld", (long long)c_d->rows,
+                    (long long)c_d->cols, (long long)a_d->rows, (long long)b_d->cols);
+    if (av.dtype != bv.dtype) return fail(LPG_EUNSUPPORTED, "lpg_gemm_packed: A and B dtypes differ");
+    if (av.dtype == LPG_F32 && cv.dtype != LPG_F32)
+        return fail(LPG_EUNSUPPORTED, "lpg_gemm_packed: f32 inputs need an f32 output");
+    if (epi < LPG_EPI_NONE || epi > LPG_EPI_GATE_SILU) return fail(LPG_EINVAL, "lpg_gemm_packed: bad epilogue op %d", epi);
+    if (epi == LPG_EPI_GATE_SILU && !epi_arg) return fail(LPG_EINVAL, "lpg_gemm_packed: LPG_EPI_GATE_SILU needs epi_arg");
+    if (beta != 0.0f && !C_in) return fail(LPG_EINVAL, "lpg_gemm_packed: beta != 0 needs C_in");
+    if (cv.bdiv != 1) return fail(LPG_EINVAL, "lpg_gemm_packed: C batch_div must be 1");
+    const int nb = cv.batch;
+    if ((nb + av.bdiv - 1) / av.bdiv > (av.batch + av.bdiv - 1) / av.bdiv && av.batch != 1)
+        return fail(LPG_EINVAL, "lpg_gemm_packed: A has too few batch slots");
+    if ((nb + bv.bdiv - 1) / bv.bdiv > (bv.batch + bv.bdiv - 1) / bv.bdiv && bv.batch != 1)
+        return fail(LPG_EINVAL, "lpg_gemm_packed: B has too few batch slots");
+    rc = check_ptr16(A, "lpg_gemm_packed A");
+    if (rc) return rc;
+    rc = check_ptr16(B, "lpg_gemm_packed B");
+    if (rc) return rc;
+    rc = check_ptr16(C_out, "lpg_gemm_packed C_out");
+    if (rc) return rc;
+    if (C_in && (uintptr_t)C_in % 16) return fail(LPG_EALIGN, "lpg_gemm_packed: C_in not 16-byte aligned");
+    if (epi_arg && (uintptr_t)epi_arg % 16) return fail(LPG_EALIGN, "lpg_gemm_packed: epi_arg not 16-byte aligned");
+    if (C_out == A || C_out == B) return fail(LPG_EINVAL, "lpg_gemm_packed: C_out must not alias A or B");
+    if (!launch) return LPG_OK;
+
+    // Which operand rides on lanes decides the role C is written in.
+    const bool c_is_left = c_d->kind == LPG_PACKED_A;  // out free = rows(M): L = A, R = B
+    const PView &L = c_is_left ? av : bv;
+    const PView &R = c_is_left ? bv : av;
+    GemmArgs g;
+    g.L = (const char *)(c_is_left ? A : B) + L.origin;
+    g.R = (const char *)(c_is_left ? B : A) + R.origin;
+    g.Cin = (beta != 0.0f) ? (const char *)C_in + cv.origin : nullptr;
+    g.Epi = epi_arg ? (const char *)epi_arg + cv.origin : nullptr;
+    g.Out = (char *)C_out + cv.origin;
+    g.l_kbs = L.kb_stride;
+    g.r_kbs = R.kb_stride;
+    g.o_kbs = cv.kb_stride;
+    g.l_slot = L.batch == 1 ? 0 : L.slot_step;
+    g.r_slot = R.batch == 1 ? 0 : R.slot_step;
+    g.o_slot = cv.slot_step;
+    g.l_div = L.bdiv;
+    g.r_div = R.bdiv;
+    g.FL = (int32_t)L.F;
+    g.FR = (int32_t)R.F;
+    g.FLg = (int32_t)((L.F + 31) / 32);
+    g.FRg = (int32_t)((R.F + 31) / 32);
+    g.FRg_out = (int32_t)(round_up(R.F, kb_of(cv.dtype)) / 32);
+    g.nkb = (int32_t)((av.K + kb_of(av.dtype) - 1) / kb_of(av.dtype));
+    g.tiles_l = g.tiles_r = 0;
+    g.batch = nb;
+    g.epi = epi;
+    g.alpha = alpha;
+    g.beta = beta;
+    if (g.FL == 0 || g.FR == 0) return LPG_OK;
+    hipError_t e = launch_gemm(g, av.dtype, cv.dtype, st);
+    if (e != hipSuccess) return fail(LPG_EHIP, "lpg_gemm_packed: %s", hipGetErrorString(e));
+    return LPG_OK;
+}
+
+// ------------------------------------------------------------------------ elementwise
+
+static int do_elementwise(int op, const void *x0, const void *x1, float s, void *out, const lpg_desc *d,
+                          hipStream_t st, bool launch)
+{
+    int rc = check_common(d, "lpg_elementwise_packed");
+    if (rc) return rc;
+    if (op < LPG_EW_SCALE || op > LPG_EW_SILU_MUL) return fail(LPG_EINVAL, "lpg_elementwise_packed: bad op %d", op);
+    if (d->row0 || d->col0 || d->batch_row_step || d->batch_col_step ||
+        (d->parent_rows && (d->parent_rows != d->rows || d->parent_cols != d->cols)))
+        return fail(LPG_EUNSUPPORTED, "lpg_elementwise_packed: sub-views are not supported");
+    if (is_canon(d->kind)) {
+        const int64_t tight = d->kind == LPG_ROW_MAJOR ? d->cols : d->rows;
+        if (d->ld && d->ld != tight) return fail(LPG_EUNSUPPORTED, "lpg_elementwise_packed: canonical buffers must be tight");
+    }
+    if (!x0 || !out) return fail(LPG_EINVAL, "lpg_elementwise_packed: NULL pointer");
+    if (op != LPG_EW_SCALE && !x1) return fail(LPG_EINVAL, "lpg_elementwise_packed: op needs x1");
+    const size_t bytes = desc_bytes(d);
+    if (bytes % 16) return fail(LPG_EALIGN, "lpg_elementwise_packed: buffer size must be a multiple of 16 bytes");
+    if ((uintptr_t)x0 % 16 || (uintptr_t)out % 16 || (x1 && (uintptr_t)x1 % 16))
+        return fail(LPG_EALIGN, "lpg_elementwise_packed: buffers must be 16-byte aligned");
+    if (!launch) return LPG_OK;
+    EwArgs a;
+    a.x0 = (const char *)x0;
+    a.x1 = (op == LPG_EW_SCALE) ? nullptr : (const char *)x1;
+    a.out = (char *)out;
+    a.n16 = (int64_t)(bytes / 16);
+    a.op = op;
+    a.s = s;
+    hipError_t e = launch_elementwise(a, d->dtype, st);
+    if (e != hipSuccess) return fail(LPG_EHIP, "lpg_elementwise_packed: %s", hipGetErrorString(e));
+    return LPG_OK;
+}
+
+// ------------------------------------------------------------------------------ chain
+
+// Packed geometry two descriptors must share to address the same bytes the same way.
+struct Geometry {
+    int dtype;
+    int64_t PF, PK, bstride;
+};
+static bool geometry_of(const lpg_desc *d, Geometry *g)
+{
+    if (!is_packed(d->kind)) return false;
+    const bool tr = d->kind == LPG_PACKED_B;
+    const int64_t prow = d->parent_rows ? d->parent_rows : d->rows;
+    const int64_t pcol = d->parent_cols ? d->parent_cols : d->cols;
+    g->dtype = d->dtype;
+    g->PF = tr ? pcol : prow;
+    g->PK = tr ? prow : pcol;
+    g->bstride = d->batch_stride;
+    return true;
+}
+
+// Row-major twin of a packed descriptor: the same logical views (rows, cols, origin,
+// per-slot steps) over a tight row-major parent.
+static lpg_desc canonical_twin(const lpg_desc *p)
+{
+    lpg_desc c = *p;
+    const int64_t prow = p->parent_rows ? p->parent_rows : p->rows;
+    const int64_t pcol = p->parent_cols ? p->parent_cols : p->cols;
+    c.kind = LPG_ROW_MAJOR;
+    c.ld = pcol;
+    c.parent_rows = prow;
+    c.parent_cols = pcol;
+    c.batch_stride = p->batch_stride ? prow * pcol : 0;
+    return c;
+}
+
+struct Slot {
+    const void *packed;   // packed buffer this slot mirrors
+    char *canon;          // row-major copy in the workspace
+    size_t bytes;
+    bool canonical_live;  // the up-to-date copy is the canonical one
+};
+
+static size_t twin_bytes(const lpg_desc *p)
+{
+    lpg_desc c = canonical_twin(p);
+    return (desc_bytes(&c) + 255) / 256 * 256;
+}
+
+static bool later_reads(const lpg_stage *st, int n, int from, const void *buf, bool *by_compute)
+{
+    bool any = false;
+    *by_compute = false;
+    for (int i = from; i < n; ++i) {
+        const lpg_stage &s = st[i];
+        const bool reads = s.in0 == buf || (s.type == LPG_STAGE_GEMM && (s.in1 == buf || s.in2 == buf || s.epi_arg == buf)) ||
+                           (s.type == LPG_STAGE_ELEMENTWISE && s.in1 == buf);
+        if (reads) {
+            any = true;
+            if (s.type == LPG_STAGE_GEMM || s.type == LPG_STAGE_ELEMENTWISE) *by_compute = true;
+        }
+        if (s.out == buf) break;  // overwritten from here on
+    }
+    return any;
+}
+
+static int validate_stage(const lpg_stage &s, int i)
+{
+    switch (s.type) {
+        case LPG_STAGE_PACK:
+        case LPG_STAGE_UNPACK: {
+            PView pv;
+            CView cv;
+            const bool pk = s.type == LPG_STAGE_PACK;
+            int rc = make_pview(pk ? &s.out_d : &s.in0_d, "lpg_chain pack/unpack", &pv);
+            if (rc) return rc;
+            rc = make_cview(pk ? &s.in0_d : &s.out_d, "lpg_chain pack/unpack", &cv);
+            if (rc) return rc;
+            if (!s.in0 || !s.out) return fail(LPG_EINVAL, "lpg_chain: stage %d has a NULL buffer", i);
+            return LPG_OK;
+        }
+        case LPG_STAGE_GEMM:
+            return do_gemm(s.alpha, s.in0, &s.in0_d, s.in1, &s.in1_d, s.beta, s.in2, s.out, &s.out_d, s.op,
+                           s.epi_arg, nullptr, false);
+        case LPG_STAGE_ELEMENTWISE:
+            return do_elementwise(s.op, s.in0, s.in1, s.scalar, s.out, &s.out_d, nullptr, false);
+        default:
+            return fail(LPG_EINVAL, "lpg_chain: stage %d has unknown type %d", i, s.type);
+    }
+}
+
+// Every packed input that an earlier stage wrote must be read with the geometry it
+// was written in (the consumer's loads assume the producer's block strides).
+static int check_links(const lpg_stage *st, int n)
+{
+    for (int i = 0; i < n; ++i) {
+        const lpg_stage &s = st[i];
+        struct In { const void *p; const lpg_desc *d; } ins[4];
+        int ni = 0;
+        if (s.type == LPG_STAGE_GEMM) {
+            ins[ni++] = {s.in0, &s.in0_d};
+            ins[ni++] = {s.in1, &s.in1_d};
+            if (s.in2) ins[ni++] = {s.in2, &s.out_d};
+            if (s.epi_arg) ins[ni++] = {s.epi_arg, &s.out_d};
+        } else if (s.type == LPG_STAGE_ELEMENTWISE) {
+            ins[ni++] = {s.in0, &s.out_d};
+            if (s.in1) ins[ni++] = {s.in1, &s.out_d};
+        } else if (s.type == LPG_STAGE_UNPACK) {
+            ins[ni++] = {s.in0, &s.in0_d};
+        }
+        for (int k = 0; k < ni; ++k) {
+            Geometry gi;
+            if (!geometry_of(ins[k].d, &gi)) continue;
+            for (int j = i - 1; j >= 0; --j) {
+                if (st[j].out != ins[k].p) continue;
+                Geometry gj;
+                if (!geometry_of(&st[j].out_d, &gj))
+                    return fail(LPG_ELAYOUT, "lpg_chain: stage %d reads as packed a buffer stage %d wrote canonical", i, j);
+                if (gi.dtype != gj.dtype || gi.PF != gj.PF || gi.PK != gj.PK || gi.bstride != gj.bstride)
+                    return fail(LPG_ELAYOUT,
+                                "lpg_chain: stage %d reads a buffer with packed geometry (free %lld, k %lld, dtype %d) "
+                                "but stage %d wrote it as (free %lld, k %lld, dtype %d)",
+                                i, (long long)gi.PF, (long long)gi.PK, gi.dtype, j, (long long)gj.PF,
+                                (long long)gj.PK, gj.dtype);
+                break;
+            }
+        }
+    }
+    return LPG_OK;
+}
+
+static int run_stage(const lpg_stage &s, hipStream_t hs)
+{
+    switch (s.type) {
+        case LPG_STAGE_PACK: return do_pack_unpack(true, s.in0, &s.in0_d, s.out, &s.out_d, hs);
+        case LPG_STAGE_UNPACK: return do_pack_unpack(false, s.out, &s.out_d, s.in0, &s.in0_d, hs);
+        case LPG_STAGE_GEMM:
+            return do_gemm(s.alpha, s.in0, &s.in0_d, s.in1, &s.in1_d, s.beta, s.in2, s.out, &s.out_d, s.op, s.epi_arg,
+                           hs, true);
+        default: return do_elementwise(s.op, s.in0, s.in1, s.scalar, s.out, &s.out_d, hs, true);
+    }
+}
+
+// Canonical control.  After each computing stage whose packed result a later computing
+// stage reads, the result is unpacked to a row-major copy in the workspace; before a
+// GEMM reads such a buffer it is packed again from that copy (once).  An elementwise
+// stage whose inputs are all held canonically runs on the row-major copies and leaves a
+// row-major result, as a BLAS-API program would.  Outputs are bit-identical to the
+// propagated mode because pack and unpack are permutations.
+static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes, hipStream_t hs, bool dry,
+                           size_t *need)
+{
+    std::vector<Slot> slots;
+    size_t used = 0;
+    auto find = [&](const void *p) -> Slot * {
+        for (auto &s : slots)
+            if (s.packed == p) return &s;
+        return nullptr;
+    };
+    // descriptors under which stages wrote a buffer since it was last re-packed
+    struct Wrote { const void *p; lpg_desc d; bool pending; };
+    std::vector<Wrote> wrote;
+    auto get_slot = [&](const void *p, const lpg_desc *pd) -> Slot * {
+        Slot *s = find(p);
+        const size_t bytes = twin_bytes(pd);
+        if (s && s->bytes >= bytes) return s;
+        Slot ns{p, ws ? ws + used : nullptr, bytes, false};
+        used += bytes;
+        if (s) { *s = ns; return s; }
+        slots.push_back(ns);
+        return &slots.back();
+    };
+    // Pack again, from the row-major copy, everything stages wrote into `p`.
+    auto repack = [&](const void *p) -> int {
+        Slot *s = find(p);
+        if (!s || !s->canonical_live) return LPG_OK;
+        for (auto &w : wrote) {
+            if (w.p != p || !w.pending) continue;
+            if (!dry) {
+                lpg_desc c = canonical_twin(&w.d);
+                int rc = do_pack_unpack(true, s->canon, &c, p, &w.d, hs);
+                if (rc) return rc;
+            }
+            w.pending = false;
+        }
+        s->canonical_live = false;
+        return LPG_OK;
+    };
+
+    for (int i = 0; i < n; ++i) {
+        const lpg_stage &s = st[i];
+        if (s.type == LPG_STAGE_ELEMENTWISE) {
+            Slot *s0 = find(s.in0), *s1 = s.in1 ? find(s.in1) : nullptr;
+            const size_t tb = is_packed(s.out_d.kind) ? twin_bytes(&s.out_d) : 0;
+            const bool canon_in = s0 && s0->canonical_live && s0->bytes == tb &&
+                                  (!s.in1 || (s1 && s1->canonical_live && s1->bytes == tb));
+            bool by_compute = false;
+            later_reads(st, n, i + 1, s.out, &by_compute);
+            if (canon_in && is_packed(s.out_d.kind)) {
+                // run on the row-major copies; result stays row-major in the workspace
+                lpg_desc c = canonical_twin(&s.out_d);
+                c.ld = 0;
+                Slot *so = get_slot(s.out, &s.out_d);
+                // get_slot may have moved the vector: look the inputs up again
+                s0 = find(s.in0);
+                s1 = s.in1 ? find(s.in1) : nullptr;
+                if (!dry) {
+                    int rc = do_elementwise(s.op, s0->canon, s1 ? s1->canon : nullptr, s.scalar, so->canon, &c, hs, true);
+                    if (rc) return rc;
+                }
+                so->canonical_live = true;
+                wrote.push_back({s.out, s.out_d, true});
+                continue;
+            }
+            int rc = repack(s.in0);
+            if (rc) return rc;
+            if (s.in1) { rc = repack(s.in1); if (rc) return rc; }
+        } else if (s.type == LPG_STAGE_GEMM) {
+            int rc = repack(s.in0);
+            if (rc) return rc;
+            rc = repack(s.in1);
+            if (rc) return rc;
+            if (s.in2) { rc = repack(s.in2); if (rc) return rc; }
+            if (s.epi_arg) { rc = repack(s.epi_arg); if (rc) return rc; }
+        } else if (s.type == LPG_STAGE_UNPACK) {
+            int rc = repack(s.in0);
+            if (rc) return rc;
+        }
+        if (!dry) {
+            int rc = run_stage(s, hs);
+            if (rc) return rc;
+        }
+        if ((s.type == LPG_STAGE_GEMM || s.type == LPG_STAGE_ELEMENTWISE) && is_packed(s.out_d.kind)) {
+            bool by_compute = false;
+            later_reads(st, n, i + 1, s.out, &by_compute);
+            if (by_compute) {
+                wrote.push_back({s.out, s.out_d, true});
+                Slot *so = get_slot(s.out, &s.out_d);
+                if (!dry) {
+                    lpg_desc c = canonical_twin(&s.out_d);
+                    int rc = do_pack_unpack(false, so->canon, &c, s.out, &s.out_d, hs);
+                    if (rc) return rc;
+                }
+                so->canonical_live = true;
+            }
+        } else if (s.type == LPG_STAGE_PACK) {
+            Slot *so = find(s.out);
+            if (so) so->canonical_live = false;
+        }
+        if (!dry && used > ws_bytes) return fail(LPG_EWORKSPACE, "lpg_chain: workspace too small (%zu needed so far, %zu given)", used, ws_bytes);
+    }
+    if (need) *need = used;
+    return LPG_OK;
+}
+
+}  // namespace lpg
+
+// ================================================================================ C ABI
+
+using namespace lpg;
+
+extern "C" {
+
+size_t lpg_packed_bytes(const lpg_desc *d) { return desc_bytes(d); }
+
+int lpg_layout_offset(const lpg_desc *d, int64_t b, int64_t row, int64_t col, int64_t *offset)
+{
+    int rc = check_common(d, "lpg_layout_offset");
+    if (rc) return rc;
+    if (!offset) return fail(LPG_EINVAL, "lpg_layout_offset: NULL offset");
+    if (b < 0 || b >= nbatch(d) || row < 0 || row >= d->rows || col < 0 || col >= d->cols)
+        return fail(LPG_EINVAL, "lpg_layout_offset: index out of range");
+    const int64_t slot = b / bdiv(d);
+    if (is_canon(d->kind)) {
+        CView v;
+        rc = make_cview(d, "lpg_layout_offset", &v);
+        if (rc) return rc;
+        *offset = v.origin + slot * v.slot_step + row * v.row_stride + col * v.col_stride;
+        return LPG_OK;
+    }
+    PView v;
+    rc = make_pview(d, "lpg_layout_offset", &v);
+    if (rc) return rc;
+    const int64_t f = v.transposed ? col : row, k = v.transposed ? row : col;
+    const int64_t KB = kb_of(v.dtype), KV = 16 / v.es, KF = 2 * KV;
+    const int64_t kin = k % KB, c = kin / KF, r = kin % KF;
+    const int64_t h = (r >> 2) & 1, vv = 4 * (r >> 3) + (r & 3);
+    const int64_t bytes = v.origin + slot * v.slot_step + (k / KB) * v.kb_stride + (f / 32) * (int64_t)kBlockBytes +
+                          c * kFragBytes + h * 512 + (f % 32) * 16 + vv * v.es;
+    *offset = bytes / v.es;
+    return LPG_OK;
+}
+
+int lpg_pack(const void *src, const lpg_desc *src_d, void *dst, const lpg_desc *dst_d, void *stream)
+{
+    return do_pack_unpack(true, src, src_d, dst, dst_d, (hipStream_t)stream);
+}
+
+int lpg_unpack(const void *src, const lpg_desc *src_d, void *dst, const lpg_desc *dst_d, void *stream)
+{
+    return do_pack_unpack(false, dst, dst_d, src, src_d, (hipStream_t)stream);
+}
+
+int lpg_gemm_packed(float alpha, const void *A, const lpg_desc *a_d, const void *B, const lpg_desc *b_d, float beta,
+                    const void *C_in, void *C_out, const lpg_desc *c_d, int epilogue_op, const void *epi_arg,
+                    void *stream)
+{
+    return do_gemm(alpha, A, a_d, B, b_d, beta, C_in, C_out, c_d, epilogue_op, epi_arg, (hipStream_t)stream, true);
+}
+
+int lpg_elementwise_packed(int op, const void *x0, const void *x1, float s, void *out, const lpg_desc *d,
+                           void *stream)
+{
+    return do_elementwise(op, x0, x1, s, out, d, (hipStream_t)stream, true);
+}
+
+size_t lpg_chain_workspace_bytes(const lpg_stage *stages, int n, int mode)
+{
+    if (!stages || n < 0) return (size_t)-1;
+    if (mode == LPG_CHAIN_PROPAGATED) return 0;
+    if (mode != LPG_CHAIN_CANONICAL) return (size_t)-1;
+    for (int i = 0; i < n; ++i)
+        if (validate_stage(stages[i], i)) return (size_t)-1;
+    size_t need = 0;
+    if (chain_canonical(stages, n, nullptr, 0, nullptr, true, &need)) return (size_t)-1;
+    return need;
+}
+
+int lpg_chain(const lpg_stage *stages, int n, int mode, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (n < 0 || (n > 0 && !stages)) return fail(LPG_EINVAL, "lpg_chain: bad stage array");
+    if (mode != LPG_CHAIN_PROPAGATED && mode != LPG_CHAIN_CANONICAL) return fail(LPG_EINVAL, "lpg_chain: bad mode %d", mode);
+    for (int i = 0; i < n; ++i) {
+        int rc = validate_stage(stages[i], i);
+        if (rc) return rc;
+    }
+    int rc = check_links(stages, n);
+    if (rc) return rc;
+    hipStream_t hs = (hipStream_t)stream;
+    if (mode == LPG_CHAIN_PROPAGATED) {
+        for (int i = 0; i < n; ++i) {
+            rc = run_stage(stages[i], hs);
+            if (rc) return rc;
+        }
+        return LPG_OK;
+    }
+    size_t need = 0;
+    rc = chain_canonical(stages, n, nullptr, 0, nullptr, true, &need);
+    if (rc) return rc;
+    if (need > workspace_bytes || (need && !workspace))
+        return fail(LPG_EWORKSPACE, "lpg_chain: workspace too small (%zu needed, %zu given)", need, workspace_bytes);
+    if (need && (uintptr_t)workspace % 256) return fail(LPG_EALIGN, "lpg_chain: workspace must be 256-byte aligned");
+    return chain_canonical(stages, n, (char *)workspace, workspace_bytes, hs, false, nullptr);
+}
+
+const char *lpg_last_error(void) { return g_err; }
+
+const char *lpg_version(void) { return "lpg 0.1 (gfx950)"; }
+
+}  // extern "C"

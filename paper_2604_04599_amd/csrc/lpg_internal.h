@@ -1,0 +1,94 @@
+// Internal declarations shared by the host API (lpg_api.cpp) and the device
+// code (lpg_kernels.hip) of the GPU path.  Nothing here is used by the CPU checker.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/lpg.h"
+
+namespace lpg {
+
+// Packed-layout constants.  A fragment is 64 lanes x 16 bytes = 1 KiB, a block is
+// four fragments = 32 free indices x KB contraction indices = 4 KiB, for both dtypes.
+constexpr int kFragBytes = 1024;
+constexpr int kBlockBytes = 4096;
+constexpr int kFragsPerBlock = 4;
+
+inline int elem_size(int dtype) { return dtype == LPG_F32 ? 4 : 2; }
+inline int kb_of(int dtype) { return dtype == LPG_F32 ? 32 : 64; }  // K extent of a block
+
+// A packed descriptor reduced to what kernels need (all in bytes unless noted).
+struct PView {
+    int dtype, es;
+    int64_t F, K;          // logical extents of one view (free, contraction)
+    int64_t PF, PK;        // logical extents of the parent
+    int64_t PFp, PKp;      // padded extents of the parent
+    int64_t f0, k0;        // origin of slot 0's view (elements)
+    int64_t fstep, kstep;  // origin shift per slot (elements)
+    int batch, bdiv;
+    int64_t bstride;       // elements between parents of consecutive slots
+    int64_t kb_stride;     // bytes between consecutive K blocks of the parent
+    int64_t origin;        // bytes from buffer start to slot 0's first block
+    int64_t slot_step;     // bytes added per slot
+    bool transposed;       // kind == PACKED_B (free = cols)
+};
+
+// A canonical descriptor reduced to strides over (free, contraction) indices.
+struct CView {
+    int dtype, es;
+    int64_t rows, cols;
+    int64_t row_stride, col_stride;  // elements
+    int64_t origin;                  // elements
+    int64_t slot_step;               // elements
+    int batch, bdiv;
+};
+
+struct PackArgs {
+    const char *canon;   // canonical buffer + origin (bytes applied)
+    char *packed;        // packed buffer + origin
+    int64_t sf, sk;      // canonical strides (elements) along free / contraction index
+    int64_t c_slot;      // canonical bytes per slot
+    int64_t p_kbs;       // packed bytes between K blocks
+    int64_t p_slot;      // packed bytes per slot
+    int32_t c_div, p_div;
+    int32_t F, K;        // logical extents
+    int32_t ngroups;     // ceil(F/32)
+    int32_t nkb;         // ceil(K/KB)
+    int32_t batch;
+};
+
+struct GemmArgs {
+    const char *L;       // operand whose free index lands on lanes (out's free dimension)
+    const char *R;       // operand whose free index lands on registers (out's contraction dim)
+    const char *Cin;     // may be null (beta == 0)
+    const char *Epi;     // may be null
+    char *Out;
+    int64_t l_kbs, r_kbs, o_kbs;     // bytes between K blocks
+    int64_t l_slot, r_slot, o_slot;  // bytes per slot
+    int32_t l_div, r_div;
+    int32_t FL, FR;                  // logical extents of out: free dim, contraction dim
+    int32_t FLg, FRg;                // 32-groups present in L and R
+    int32_t FRg_out;                 // 32-groups of out's contraction dim incl. block padding
+    int32_t nkb;                     // contraction blocks of the product
+    int32_t tiles_l, tiles_r, batch;
+    int32_t epi;
+    float alpha, beta;
+};
+
+struct EwArgs {
+    const char *x0, *x1;
+    char *out;
+    int64_t n16;  // number of 16-byte chunks
+    int32_t op;
+    float s;
+};
+
+// Launchers (lpg_kernels.hip).  Return hipError_t of the launch.
+hipError_t launch_pack(const PackArgs &a, int src_dtype, int dst_dtype, hipStream_t st);
+hipError_t launch_unpack(const PackArgs &a, int src_dtype, int dst_dtype, hipStream_t st);
+hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, hipStream_t st);
+hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st);
+
+}  // namespace lpg
