@@ -38,8 +38,14 @@ def lib():
         L.orc_silu_mul.argtypes = [vp, vp, vp, i64]
         L.orc_pack.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64]
         L.orc_unpack.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64]
+        L.orc_threads.restype = ctypes.c_int
         _lib = L
     return _lib
+
+
+def threads():
+    """OpenMP threads the oracle GEMM uses."""
+    return int(lib().orc_threads())
 
 
 def _f64(x):
