@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--workloads", default="all",
                     help="comma list of extra workloads to report beside the headline, 'all' or 'none'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default=None,
+                    help="profiling aid: time just this workload (both modes) and print its line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1",
@@ -122,6 +124,11 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     from paper_2604_04599_amd import inputs
+
+    if args.only:
+        res, _, _, _ = measure(args.only, args.steps, args.warmup)
+        print(json.dumps({"workload": args.only, **res}))
+        return
 
     head, ch, inp, shape = measure(HEADLINE, args.steps, args.warmup)
     t_gemm, gemm_flops = time_gemm_launches(ch, args.steps)

@@ -8,7 +8,8 @@ LIB = os.path.join(HERE, "liblpg.so")
 SOURCES = ["lpg_api.cpp", "lpg_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function"]
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+         "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 
 def build(verbose: bool = False) -> str:

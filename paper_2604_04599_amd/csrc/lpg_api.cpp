@@ -2,6 +2,7 @@
 // marshalling, and the chain executor (propagated and canonical-control modes).
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -272,7 +273,10 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     g.alpha = alpha;
     g.beta = beta;
     if (g.FL == 0 || g.FR == 0) return LPG_OK;
-    hipError_t e = launch_gemm(g, av.dtype, cv.dtype, st);
+    // LPG_FORCE_TILE=<index> pins the tile configuration (a tuning aid; unset = automatic)
+    int cfg = -1;
+    if (const char *f = getenv("LPG_FORCE_TILE")) cfg = atoi(f);
+    hipError_t e = launch_gemm(g, av.dtype, cv.dtype, cfg, st);
     if (e != hipSuccess) return fail(LPG_EHIP, "lpg_gemm_packed: %s", hipGetErrorString(e));
     return LPG_OK;
 }

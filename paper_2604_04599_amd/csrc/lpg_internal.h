@@ -88,7 +88,9 @@ struct EwArgs {
 // Launchers (lpg_kernels.hip).  Return hipError_t of the launch.
 hipError_t launch_pack(const PackArgs &a, int src_dtype, int dst_dtype, hipStream_t st);
 hipError_t launch_unpack(const PackArgs &a, int src_dtype, int dst_dtype, hipStream_t st);
-hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, hipStream_t st);
+// cfg < 0 lets the library choose the tile configuration.
+hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, int cfg, hipStream_t st);
+int choose_gemm_config(const GemmArgs &a, int in_dtype);
 hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st);
 
 }  // namespace lpg

@@ -11,6 +11,8 @@ namespace lpg {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct F32 {
     typedef uint32_t raw;
@@ -30,6 +32,13 @@ __device__ __forceinline__ uint32_t bf16_rne(float f)
     return u >> 16;
 }
 __device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+// two fp32 -> packed bf16 pair with the hardware converter (round to nearest even); used
+// where results are judged by tolerance, the bit-pattern routine above where bytes are
+__device__ __forceinline__ uint32_t bf16_pack2(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 template <typename S, typename D>
 __device__ __forceinline__ typename D::raw convert_raw(typename S::raw x)
@@ -219,7 +228,7 @@ __global__ __launch_bounds__(256) void ew_kernel(EwArgs a)
             } else {
                 const float lo = ew_apply(a.op, bf16_to_f32(pw[j] & 0xffff), bf16_to_f32(qw[j] & 0xffff), a.s);
                 const float hi = ew_apply(a.op, bf16_to_f32(pw[j] >> 16), bf16_to_f32(qw[j] >> 16), a.s);
-                r[j] = bf16_rne(lo) | (bf16_rne(hi) << 16);
+                r[j] = bf16_pack2(lo, hi);
             }
         }
         ((uint4 *)a.out)[i] = make_uint4(r[0], r[1], r[2], r[3]);
@@ -250,9 +259,28 @@ hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st)
 // accumulators already are fragments of P(out; FL, FR) and are stored as they stand.
 //
 // Workgroup tile: TLG x TRG 32-groups; WL x WR waves, each owning (TLG/WL) x (TRG/WR)
-// 32x32 tiles.  One K block (4 fragments per group) is staged per step through a
-// double-buffered LDS copy of the packed blocks; since the packed block is already in
-// register-image order the LDS copy is verbatim and every ds_read_b128 is conflict free.
+// 32x32 tiles.  A step stages FS fragments per group (FS = 4: a whole K block, FS = 2:
+// half of one) into one of NS LDS stages used as a ring; NS-1 steps are in flight ahead of
+// the one being multiplied.  The packed block already is the register image, so the copy
+// is verbatim: each wave moves whole 1 KiB fragments with the direct global->LDS load (no
+// VGPR round trip), and every ds_read_b128 at lane*16 is conflict free.
+//
+// Workgroups are persistent: workgroup j walks the virtual tile ids j, j + G, j + 2G, ...
+// (G = grid size) and the staging ring runs across tile boundaries, so the next tile's
+// first steps are in flight while the current tile's epilogue stores drain.  Every
+// workgroup runs a fixed, finite number of steps; there is no queue and no atomics.
+
+// 16 bytes per lane, global -> LDS at lds_addr + lane*16 (lds_addr wave-uniform).  Written
+// as inline asm so that the compiler does not serialise later LDS reads of the OTHER stage
+// behind this transfer; completion is awaited explicitly (vmcnt) before the stage is read.
+#ifndef LPG_DBG
+#define LPG_DBG 0  // timing experiments only: 1 = no copies, 2 = no multiplies, 4 = no stores
+#endif
+__device__ __forceinline__ void lds_dma16(const void *g, uint32_t lds_addr)
+{
+    if (LPG_DBG & 1) return;
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
+}
 
 template <typename IN>
 __device__ __forceinline__ void mma_frag(f32x16 &acc, const uint4 &r, const uint4 &l)
@@ -275,227 +303,467 @@ __device__ __forceinline__ float epi_apply(int epi, float v, float g)
     return v;
 }
 
-template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR>
+struct TileInfo {
+    const char *Lp, *Rp;  // first block of the tile's L / R slab at K block 0
+    int gl0, gr0;         // first 32-group of the tile in out's free / contraction dimension
+    int nlg, nrg;         // groups of the tile that exist in L / R
+    int b;                // batch index
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int MASK, int N>
+__device__ __forceinline__ void sched_group()
+{
+    if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
+}
+
+// registers -> fragments of P(out; FL, FR) for one 32x32 accumulator tile
+template <typename OUT>
+__device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane,
+                                           char *Ob, const char *Cb, const char *Eb, bool use_c, bool use_e)
+{
+    const int h = lane >> 5;
+    const int fl = grL * 32 + (lane & 31);
+    const bool have = grR < p.FRg;
+    float v[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) v[e] = have ? acc[e] : 0.0f;
+    if (p.alpha != 1.0f) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] *= p.alpha;
+    }
+    int64_t obase;  // byte offset of this tile's first fragment inside out
+    if constexpr (OUT::ES == 4)
+        obase = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
+    else
+        obase = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes + (grR & 1) * 2 * kFragBytes + lane * 16;
+    constexpr int NF = (OUT::ES == 4) ? 4 : 2;  // fragments this tile spans
+    constexpr int PER = 16 / NF;
+    if (use_c || use_e) {
+#pragma unroll
+        for (int fgi = 0; fgi < NF; ++fgi) {
+            float cv[PER], ev[PER];
+            if (use_c) {
+                const uint4 t4 = *(const uint4 *)(Cb + obase + fgi * kFragBytes);
+                const uint32_t w[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    if constexpr (OUT::ES == 4) cv[j] = __uint_as_float(w[j]);
+                    else cv[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
+                }
+            }
+            if (use_e) {
+                const uint4 t4 = *(const uint4 *)(Eb + obase + fgi * kFragBytes);
+                const uint32_t w[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    if constexpr (OUT::ES == 4) ev[j] = __uint_as_float(w[j]);
+                    else ev[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                float x = v[fgi * PER + j];
+                if (use_c) x += p.beta * cv[j];
+                v[fgi * PER + j] = epi_apply(p.epi, x, use_e ? ev[j] : 0.0f);
+            }
+        }
+    } else if (p.epi == LPG_EPI_SILU) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = silu_f(v[e]);
+    }
+    // zero the padding of ragged edge tiles
+    if (grL * 32 + 32 > p.FL || grR * 32 + 32 > p.FR) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+            if (fl >= p.FL || fr >= p.FR) v[e] = 0.0f;
+        }
+    }
+    if constexpr (OUT::ES == 4) {
+#pragma unroll
+        for (int fgi = 0; fgi < 4; ++fgi)
+            *(uint4 *)(Ob + obase + fgi * kFragBytes) =
+                make_uint4(__float_as_uint(v[4 * fgi]), __float_as_uint(v[4 * fgi + 1]),
+                           __float_as_uint(v[4 * fgi + 2]), __float_as_uint(v[4 * fgi + 3]));
+    } else {
+#pragma unroll
+        for (int fgi = 0; fgi < 2; ++fgi) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = bf16_pack2(v[8 * fgi + 2 * j], v[8 * fgi + 2 * j + 1]);
+            *(uint4 *)(Ob + obase + fgi * kFragBytes) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
+// XPF (needs NS >= 3): the first fragment of the NEXT step is read into registers while the
+// last fragment of the current step is multiplied, so no LDS latency is exposed after the
+// barrier; the barrier of a step then also publishes the step after it.
+template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR, int FS, int NS, bool XPF>
 __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
 {
-    constexpr int NT = WL * WR * 64;
+    static_assert(!XPF || NS >= 3, "cross-step prefetch needs a landed stage beyond the current one");
+    constexpr int NW = WL * WR;
     constexpr int WTL = TLG / WL, WTR = TRG / WR;
-    constexpr int NCH = (TLG + TRG) * 256 / NT;  // 16-byte chunks per thread per stage
-    constexpr int STAGE = (TLG + TRG) * kBlockBytes;
-    static_assert((TLG + TRG) * 256 % NT == 0, "stage must divide over the threads");
+    constexpr int NFRAG = (TLG + TRG) * FS;  // fragments per stage
+    constexpr int FPW = NFRAG / NW;          // fragments each wave copies per stage
+    constexpr int FPW_L = TLG * FS / NW;     // ... of which the first FPW_L come from L
+    constexpr int STAGE = NFRAG * kFragBytes;
+    constexpr int SPB = kFragsPerBlock / FS;  // steps per K block
+    static_assert(NFRAG % NW == 0 && (TLG * FS) % NW == 0, "stage must divide over the waves");
+    static_assert(TLG % WL == 0 && TRG % WR == 0, "tile must divide over the waves");
+    static_assert(FS == 2 || FS == 4, "a step is a whole or half K block");
+    static_assert(NS >= 2 && NS <= 5 && (NS - 2) * FPW <= 63, "ring depth limited by the vmcnt field");
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wl = wave % WL, wr = wave / WL;
 
-    // ---- workgroup -> (batch, tile) with an XCD-aware remap: hardware deals workgroups
-    // round-robin to the 8 XCDs, so give each XCD a contiguous range of tile ids, then
-    // walk tiles in bands of GM tile-rows so that neighbours share L and R panels in L2.
-    const int ntile = p.tiles_l * p.tiles_r;
-    const int64_t total = (int64_t)ntile * p.batch;
-    int64_t pid;
-    {
-        const int64_t bid = blockIdx.x;
-        const int64_t per = total / 8, rem = total % 8, x = bid % 8, idx = bid / 8;
-        pid = (x < rem) ? x * (per + 1) + idx : rem * (per + 1) + (x - rem) * per + idx;
-    }
-    const int b = (int)(pid / ntile);
-    const int tp = (int)(pid % ntile);
-    constexpr int GM = 8;
-    const int width = GM * p.tiles_r;
-    const int band = tp / width, first_l = band * GM;
-    const int gsz = min(p.tiles_l - first_l, GM);
-    const int tl = first_l + (tp % width) % gsz;
-    const int tr = (tp % width) / gsz;
+    const uint32_t ntile = (uint32_t)(p.tiles_l * p.tiles_r);
+    const uint32_t total = ntile * (uint32_t)p.batch;
+    const uint32_t G = gridDim.x;
+    const int spt = p.nkb * SPB;  // steps per tile
+    if (blockIdx.x >= total) return;
+    const uint32_t my_tiles = (total - blockIdx.x + G - 1) / G;
 
-    const int gl0 = tl * TLG, gr0 = tr * TRG;
-    const int nlg = min(TLG, p.FLg - gl0);
-    const int nrg = max(0, min(TRG, p.FRg - gr0));
-    const char *Lp = p.L + (int64_t)(b / p.l_div) * p.l_slot + (int64_t)gl0 * kBlockBytes;
-    const char *Rp = p.R + (int64_t)(b / p.r_div) * p.r_slot + (int64_t)gr0 * kBlockBytes;
+    // virtual block id -> (batch, tile).  Hardware deals consecutive workgroups round-robin
+    // to the 8 XCDs; ids congruent mod 8 get one contiguous range of tile ids, walked in
+    // bands of GM tile-rows, so the tiles an XCD works on share L and R panels in its L2.
+    auto decode = [&](uint32_t vb) -> TileInfo {
+        const uint32_t per = total / 8, rem = total % 8, x = vb % 8, idx = vb / 8;
+        const uint32_t pid = (x < rem) ? x * (per + 1) + idx : rem * (per + 1) + (x - rem) * per + idx;
+        TileInfo t;
+        t.b = (int)(pid / ntile);
+        const int tp = (int)(pid % ntile);
+        constexpr int GM = 8;
+        const int width = GM * p.tiles_r;
+        const int first_l = (tp / width) * GM;
+        const int gsz = min(p.tiles_l - first_l, GM);
+        const int tl = first_l + (tp % width) % gsz;
+        const int tr = (tp % width) / gsz;
+        t.gl0 = tl * TLG;
+        t.gr0 = tr * TRG;
+        t.nlg = min(TLG, p.FLg - t.gl0);
+        t.nrg = max(0, min(TRG, p.FRg - t.gr0));
+        t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (int64_t)t.gl0 * kBlockBytes;
+        t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (int64_t)t.gr0 * kBlockBytes;
+        return t;
+    };
 
-    uint4 pre[NCH];
-    auto gload = [&](int kb) {
+    // ---- copy side.  Wave w copies fragments w, w + NW, ... of a stage; src[i] is this
+    // lane's address of its i-th fragment at the step the copy cursor stands on.  Every wave
+    // always issues exactly FPW transfers per step, so outstanding-transfer counts agree
+    // across waves: a group the tile does not have is replaced by the tile's last existing
+    // group (its data is never used), which keeps every address inside the operand.
+    const char *src[FPW];
+    auto aim = [&](const TileInfo &t) {
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            const int c = i * NT + tid;      // chunk id within the stage
-            const int grp = c >> 8;          // block (32-group) the chunk belongs to
-            const int off = (c & 255) * 16;
-            if (grp < TLG) {
-                if (grp < nlg)
-                    pre[i] = *(const uint4 *)(Lp + (int64_t)kb * p.l_kbs + grp * kBlockBytes + off);
-            } else {
-                if (grp - TLG < nrg)
-                    pre[i] = *(const uint4 *)(Rp + (int64_t)kb * p.r_kbs + (grp - TLG) * kBlockBytes + off);
+        for (int i = 0; i < FPW; ++i) {
+            const int fid = i * NW + wave;
+            const int grp = fid / FS, c = fid % FS;
+            const char *base = (i < FPW_L) ? t.Lp + min(grp, t.nlg - 1) * kBlockBytes
+                                           : t.Rp + max(0, min(grp - TLG, t.nrg - 1)) * kBlockBytes;
+            src[i] = base + c * kFragBytes + lane * 16;
+        }
+    };
+    uint32_t c_tiles_left = my_tiles;  // tiles the copy cursor still has to start or finish
+    uint32_t c_vb = blockIdx.x;
+    int c_s = 0;                       // step of its tile the copy cursor stands on
+    int c_st = 0;                      // ring stage it fills next
+    int pending = 0;                   // steps copied (or in flight) and not yet multiplied
+    bool c_live = spt > 0;
+    auto copy_step = [&]() {
+        const uint32_t dst = sbase + c_st * STAGE + wave * kFragBytes;
+#pragma unroll
+        for (int i = 0; i < FPW; ++i) lds_dma16(src[i], dst + i * NW * kFragBytes);
+        c_st = (c_st + 1 == NS) ? 0 : c_st + 1;
+        ++pending;
+        if (++c_s == spt) {  // next tile
+            c_s = 0;
+            c_vb += G;
+            if (--c_tiles_left == 0) c_live = false;
+            else aim(decode(c_vb));
+        } else {             // next step of the same tile
+            int64_t dl, dr;
+            if (FS == 4 || (c_s & 1) == 0) {  // first fragments of the next K block
+                dl = p.l_kbs - (kFragsPerBlock - FS) * kFragBytes;
+                dr = p.r_kbs - (kFragsPerBlock - FS) * kFragBytes;
+            } else {                          // second half of the same K block
+                dl = dr = FS * kFragBytes;
             }
+#pragma unroll
+            for (int i = 0; i < FPW; ++i) src[i] += (i < FPW_L) ? dl : dr;
         }
     };
-    auto sstore = [&](int st) {
+    aim(decode(c_vb));
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            const int c = i * NT + tid;
-            *(uint4 *)(smem + st * STAGE + c * 16) = pre[i];
-        }
-    };
+    for (int j = 0; j < NS - 1; ++j)
+        if (c_live) copy_step();
 
-    f32x16 acc[WTL][WTR];
-#pragma unroll
-    for (int a = 0; a < WTL; ++a)
-#pragma unroll
-        for (int q = 0; q < WTR; ++q)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[a][q][e] = 0.0f;
+    const bool use_c = (p.beta != 0.0f) && p.Cin;
+    const bool use_e = (p.epi == LPG_EPI_GATE_SILU) && p.Epi;
 
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) pre[i] = make_uint4(0, 0, 0, 0);
-
-    if (p.nkb > 0) {
-        gload(0);
-        sstore(0);
-    }
-    __syncthreads();
-    for (int kb = 0; kb < p.nkb; ++kb) {
-        const int cur = kb & 1;
-        if (kb + 1 < p.nkb) gload(kb + 1);
-        const char *sL = smem + cur * STAGE + (wl * WTL) * kBlockBytes + lane * 16;
-        const char *sR = smem + cur * STAGE + (TLG + wr * WTR) * kBlockBytes + lane * 16;
-#pragma unroll
-        for (int c = 0; c < kFragsPerBlock; ++c) {
-            uint4 lf[WTL], rf[WTR];
-#pragma unroll
-            for (int a = 0; a < WTL; ++a) lf[a] = *(const uint4 *)(sL + a * kBlockBytes + c * kFragBytes);
-#pragma unroll
-            for (int q = 0; q < WTR; ++q) rf[q] = *(const uint4 *)(sR + q * kBlockBytes + c * kFragBytes);
-#pragma unroll
-            for (int a = 0; a < WTL; ++a)
-#pragma unroll
-                for (int q = 0; q < WTR; ++q) mma_frag<IN>(acc[a][q], rf[q], lf[a]);
-        }
-        if (kb + 1 < p.nkb) sstore(cur ^ 1);
+    // ---- multiply side
+    int st = 0;
+    const char *sLw = smem + (wl * WTL) * (FS * kFragBytes) + lane * 16;
+    const char *sRw = smem + (TLG + wr * WTR) * (FS * kFragBytes) + lane * 16;
+    uint4 lf[2][WTL], rf[2][WTR];
+    if constexpr (XPF) {
+        // prime: fragment 0 of the very first step
+        if (pending == NS - 1) wait_vmcnt<(NS - 2) * FPW>();
+        else wait_vmcnt<0>();
         __syncthreads();
+#pragma unroll
+        for (int a = 0; a < WTL; ++a) lf[0][a] = *(const uint4 *)(sLw + a * (FS * kFragBytes));
+#pragma unroll
+        for (int q = 0; q < WTR; ++q) rf[0][q] = *(const uint4 *)(sRw + q * (FS * kFragBytes));
     }
+    uint32_t vb = blockIdx.x;
+    for (uint32_t ti = 0; ti < my_tiles; ++ti, vb += G) {
+        f32x16 acc[WTL][WTR];
+#pragma unroll
+        for (int a = 0; a < WTL; ++a)
+#pragma unroll
+            for (int q = 0; q < WTR; ++q)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[a][q][e] = 0.0f;
 
-    // ---- epilogue: registers -> fragments of P(out; FL, FR)
-    const int h = lane >> 5;
-    const int64_t oslot = (int64_t)b * p.o_slot;
-    char *Ob = p.Out + oslot;
-    const char *Cb = p.Cin ? p.Cin + oslot : nullptr;
-    const char *Eb = p.Epi ? p.Epi + oslot : nullptr;
-    const bool use_c = (p.beta != 0.0f) && Cb;
-    const bool use_e = (p.epi == LPG_EPI_GATE_SILU) && Eb;
+        for (int s = 0; s < spt; ++s) {
+            // Wait until this wave's transfers of the step that must be readable have landed
+            // (XPF: the step after the current one; otherwise the current one); later steps
+            // stay in flight (transfers complete in issue order).
+            constexpr int KEEP = XPF ? NS - 3 : NS - 2;
+            if (pending == NS - 1) wait_vmcnt<KEEP * FPW>();
+            else wait_vmcnt<0>();
+            __syncthreads();  // everyone's transfers landed; the stage multiplied last step is free
+            if (c_live) copy_step();
+
+            const char *sL = sLw + st * STAGE;
+            const char *sR = sRw + st * STAGE;
+            const int stn = (st + 1 == NS) ? 0 : st + 1;
+            if (LPG_DBG & 2) { st = stn; --pending; continue; }
+            if constexpr (!XPF) {
 #pragma unroll
-    for (int a = 0; a < WTL; ++a) {
-        const int grL = gl0 + wl * WTL + a;
-        if (grL >= p.FLg) continue;
-        const int fl = grL * 32 + (lane & 31);
+                for (int a = 0; a < WTL; ++a) lf[0][a] = *(const uint4 *)(sL + a * (FS * kFragBytes));
 #pragma unroll
-        for (int q = 0; q < WTR; ++q) {
-            const int grR = gr0 + wr * WTR + q;
-            if (grR >= p.FRg_out) continue;
-            const bool have = grR < p.FRg;
-            float v[16];
+                for (int q = 0; q < WTR; ++q) rf[0][q] = *(const uint4 *)(sR + q * (FS * kFragBytes));
+            }
 #pragma unroll
-            for (int e = 0; e < 16; ++e) v[e] = have ? p.alpha * acc[a][q][e] : 0.0f;
-            // byte offset of this tile's first fragment inside out
-            int64_t obase;
-            if constexpr (OUT::ES == 4)
-                obase = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
-            else
-                obase = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes +
-                        (grR & 1) * 2 * kFragBytes + lane * 16;
-            constexpr int NF = (OUT::ES == 4) ? 4 : 2;  // fragments this tile spans
-            if (use_c || use_e) {
+            for (int c = 0; c < FS; ++c) {
+                if (c + 1 < FS) {
 #pragma unroll
-                for (int fgi = 0; fgi < NF; ++fgi) {
-                    float cv[16 / NF], ev[16 / NF];
-                    if constexpr (OUT::ES == 4) {
-                        if (use_c) {
-                            const uint4 t4 = *(const uint4 *)(Cb + obase + fgi * kFragBytes);
-                            cv[0] = __uint_as_float(t4.x); cv[1] = __uint_as_float(t4.y);
-                            cv[2] = __uint_as_float(t4.z); cv[3] = __uint_as_float(t4.w);
+                    for (int a = 0; a < WTL; ++a)
+                        lf[(c + 1) & 1][a] = *(const uint4 *)(sL + a * (FS * kFragBytes) + (c + 1) * kFragBytes);
+#pragma unroll
+                    for (int q = 0; q < WTR; ++q)
+                        rf[(c + 1) & 1][q] = *(const uint4 *)(sR + q * (FS * kFragBytes) + (c + 1) * kFragBytes);
+                } else if constexpr (XPF) {
+                    // fragment 0 of the next step (after the very last step this reads a stage
+                    // nobody uses; the address stays inside the ring)
+#pragma unroll
+                    for (int a = 0; a < WTL; ++a)
+                        lf[0][a] = *(const uint4 *)(sLw + stn * STAGE + a * (FS * kFragBytes));
+#pragma unroll
+                    for (int q = 0; q < WTR; ++q)
+                        rf[0][q] = *(const uint4 *)(sRw + stn * STAGE + q * (FS * kFragBytes));
+                }
+#pragma unroll
+                for (int a = 0; a < WTL; ++a)
+#pragma unroll
+                    for (int q = 0; q < WTR; ++q) mma_frag<IN>(acc[a][q], rf[c & 1][q], lf[c & 1][a]);
+            }
+            // Scheduling recipe for the block above: the reads of the next fragment are spread
+            // one by one between the MFMAs of the current one, so LDS latency hides behind
+            // matrix work instead of being waited for in front of every MFMA.
+            {
+                constexpr int NR = WTL + WTR;
+                constexpr int NM = WTL * WTR * (IN::ES == 4 ? 4 : 1);
+                constexpr int PAIRS = NM < NR ? NM : NR;
+                if constexpr (!XPF) sched_group<0x100, NR>();
+#pragma unroll
+                for (int c = 0; c < FS; ++c) {
+                    if (c + 1 < FS || XPF) {
+#pragma unroll
+                        for (int i = 0; i < PAIRS - 1; ++i) {
+                            sched_group<0x008, 1>();
+                            sched_group<0x100, 1>();
                         }
-                        if (use_e) {
-                            const uint4 t4 = *(const uint4 *)(Eb + obase + fgi * kFragBytes);
-                            ev[0] = __uint_as_float(t4.x); ev[1] = __uint_as_float(t4.y);
-                            ev[2] = __uint_as_float(t4.z); ev[3] = __uint_as_float(t4.w);
-                        }
+                        sched_group<0x008, 1>();
+                        sched_group<0x100, NR - (PAIRS - 1)>();
+                        sched_group<0x008, NM - PAIRS>();
                     } else {
-                        if (use_c) {
-                            const uint4 t4 = *(const uint4 *)(Cb + obase + fgi * kFragBytes);
-                            const uint32_t w[4] = {t4.x, t4.y, t4.z, t4.w};
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) cv[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
-                        }
-                        if (use_e) {
-                            const uint4 t4 = *(const uint4 *)(Eb + obase + fgi * kFragBytes);
-                            const uint32_t w[4] = {t4.x, t4.y, t4.z, t4.w};
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) ev[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
-                        }
-                    }
-#pragma unroll
-                    for (int j = 0; j < 16 / NF; ++j) {
-                        float x = v[fgi * (16 / NF) + j];
-                        if (use_c) x += p.beta * cv[j];
-                        v[fgi * (16 / NF) + j] = epi_apply(p.epi, x, use_e ? ev[j] : 0.0f);
+                        sched_group<0x008, NM>();
                     }
                 }
-            } else if (p.epi == LPG_EPI_SILU) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) v[e] = silu_f(v[e]);
             }
-            // zero the padding of ragged edge tiles
-            if (grL * 32 + 32 > p.FL || grR * 32 + 32 > p.FR) {
+            st = stn;
+            --pending;
+        }
+
+        // ---- epilogue
+        if (LPG_DBG & 4) continue;
+        const TileInfo cur = decode(vb);
+        const int64_t oslot = (int64_t)cur.b * p.o_slot;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-                    if (fl >= p.FL || fr >= p.FR) v[e] = 0.0f;
-                }
-            }
-            if constexpr (OUT::ES == 4) {
+        for (int a = 0; a < WTL; ++a) {
+            const int grL = cur.gl0 + wl * WTL + a;
+            if (grL >= p.FLg) continue;
 #pragma unroll
-                for (int fgi = 0; fgi < 4; ++fgi)
-                    *(uint4 *)(Ob + obase + fgi * kFragBytes) =
-                        make_uint4(__float_as_uint(v[4 * fgi]), __float_as_uint(v[4 * fgi + 1]),
-                                   __float_as_uint(v[4 * fgi + 2]), __float_as_uint(v[4 * fgi + 3]));
-            } else {
-#pragma unroll
-                for (int fgi = 0; fgi < 2; ++fgi) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        w[j] = bf16_rne(v[8 * fgi + 2 * j]) | (bf16_rne(v[8 * fgi + 2 * j + 1]) << 16);
-                    *(uint4 *)(Ob + obase + fgi * kFragBytes) = make_uint4(w[0], w[1], w[2], w[3]);
-                }
+            for (int q = 0; q < WTR; ++q) {
+                const int grR = cur.gr0 + wr * WTR + q;
+                if (grR >= p.FRg_out) continue;
+                store_tile<OUT>(p, acc[a][q], grL, grR, lane, p.Out + oslot, p.Cin + oslot, p.Epi + oslot, use_c,
+                                use_e);
             }
         }
     }
+}
+
+// Tile configurations (TLG, TRG, WL, WR) in 32-groups; index = position in this list.
+struct TileCfg {
+    int tlg, trg, wl, wr;
+};
+static const TileCfg kCfgs[] = {
+    {2, 2, 2, 2},  // 0:  64 x  64, 4 waves of 1x1
+    {4, 2, 2, 2},  // 1: 128 x  64, 4 waves of 2x1
+    {2, 4, 2, 2},  // 2:  64 x 128, 4 waves of 1x2
+    {4, 4, 2, 2},  // 3: 128 x 128, 4 waves of 2x2
+    {8, 4, 2, 2},  // 4: 256 x 128, 4 waves of 4x2
+    {4, 8, 2, 2},  // 5: 128 x 256, 4 waves of 2x4
+    {8, 8, 2, 4},  // 6: 256 x 256, 8 waves of 4x2
+    {8, 2, 4, 1},  // 7: 256 x  64, 4 waves of 2x2
+};
+constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
+
+// Staging ring per input type and tile: fp32 moves whole K blocks through two stages (its
+// MFMAs are slow enough to cover memory latency); bf16 moves half blocks through a ring of
+// four stages (three where four would keep a second workgroup off the compute unit) and
+// reads the next step's first fragment ahead.
+constexpr int ring_fs(bool bf16) { return bf16 ? 2 : 4; }
+constexpr int ring_ns(bool bf16, int tlg, int trg, int nw)
+{
+    if (!bf16) return 2;
+    const int stage = (tlg + trg) * 2 * kFragBytes;
+    if (nw == 8) return 5 * stage <= 160 * 1024 ? 5 : 4;  // one workgroup per compute unit: use all the LDS
+    return 4 * stage <= 80 * 1024 ? 4 : 3;
+}
+
+static int lds_bytes(const TileCfg &c, bool bf16)
+{
+    return ring_ns(bf16, c.tlg, c.trg, c.wl * c.wr) * (c.tlg + c.trg) * ring_fs(bf16) * kFragBytes;
+}
+
+static int workgroups_per_cu(const TileCfg &c, bool bf16)
+{
+    int occ = (160 * 1024) / lds_bytes(c, bf16);
+    const int waves = c.wl * c.wr;
+    // accumulators + operand registers per lane decide how many waves fit a SIMD
+    const int regs = (c.tlg / c.wl) * (c.trg / c.wr) * 16 + 64;
+    const int waves_per_simd = regs > 256 ? 1 : (regs > 128 ? 2 : 4);
+    const int by_regs = waves_per_simd * 4 / waves;
+    if (occ > by_regs) occ = by_regs;
+    if (occ > 4) occ = 4;
+    return occ < 1 ? 1 : occ;
+}
+
+// Estimated run time (arbitrary units) of one GEMM with a tile configuration: the MFMA
+// work of the busiest compute unit, derated when few waves share a SIMD (less latency
+// hiding) or when a wave's tile is so small that LDS reads per MFMA dominate.
+static double estimate_cost(const GemmArgs &a, const TileCfg &c, bool bf16)
+{
+    const int64_t tl = (a.FLg + c.tlg - 1) / c.tlg, tr = (a.FRg_out + c.trg - 1) / c.trg;
+    const int64_t tiles = tl * tr * a.batch;
+    const int ncu = 256;
+    const int occ = workgroups_per_cu(c, bf16);
+    const int64_t per_cu = (tiles + ncu - 1) / ncu;  // tiles the busiest CU runs
+    const int wtl = c.tlg / c.wl, wtr = c.trg / c.wr;
+    const double waves_per_simd = (double)(c.wl * c.wr) / 4.0;
+    double tile_time = (double)wtl * wtr * waves_per_simd * (a.nkb > 0 ? a.nkb : 1) + 0.35 * wtl * wtr;
+    const int resident = (int)((per_cu < occ ? per_cu : occ) * waves_per_simd);  // waves per SIMD
+    double eff = resident >= 2 ? 1.0 : 0.8;
+    if (bf16) {
+        const double reads_per_mma = (double)(wtl + wtr) / (wtl * wtr);
+        eff /= (1.0 + 0.35 * reads_per_mma);
+    } else {
+        eff /= (1.0 + 0.03 * (double)(wtl + wtr) / (wtl * wtr));
+    }
+    return per_cu * tile_time / eff;
 }
 
 template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR>
 static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
 {
     constexpr int NT = WL * WR * 64;
-    constexpr size_t lds = 2 * (size_t)(TLG + TRG) * kBlockBytes;
+    constexpr bool BF = IN::ES == 2;
+    constexpr int FS = ring_fs(BF), NS = ring_ns(BF, TLG, TRG, WL * WR);
+    constexpr size_t lds = (size_t)NS * (TLG + TRG) * FS * kFragBytes;
+    static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
     a.tiles_l = (a.FLg + TLG - 1) / TLG;
     a.tiles_r = (a.FRg_out + TRG - 1) / TRG;
     const int64_t total = (int64_t)a.tiles_l * a.tiles_r * a.batch;
     if (total <= 0) return hipSuccess;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
-    auto kern = gemm_kernel<IN, OUT, TLG, TRG, WL, WR>;
+    const TileCfg c = {TLG, TRG, WL, WR};
+    int64_t grid = (int64_t)256 * workgroups_per_cu(c, IN::ES == 2);
+    if (grid > total) grid = total;
+    auto kern = gemm_kernel<IN, OUT, TLG, TRG, WL, WR, FS, NS, BF>;
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+        static bool done = false;  // per instantiation
+        if (!done) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            done = true;
+        }
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(NT), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, st, a);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, hipStream_t st)
+template <typename IN, typename OUT>
+static hipError_t launch_gemm_dtype(const GemmArgs &a, int cfg, hipStream_t st)
 {
-    if (in_dtype == LPG_F32 && out_dtype == LPG_F32) return launch_gemm_cfg<F32, F32, 4, 4, 2, 2>(a, st);
-    if (in_dtype == LPG_BF16 && out_dtype == LPG_BF16) return launch_gemm_cfg<BF16, BF16, 4, 4, 2, 2>(a, st);
-    if (in_dtype == LPG_BF16 && out_dtype == LPG_F32) return launch_gemm_cfg<BF16, F32, 4, 4, 2, 2>(a, st);
+    switch (cfg) {
+        case 0: return launch_gemm_cfg<IN, OUT, 2, 2, 2, 2>(a, st);
+        case 1: return launch_gemm_cfg<IN, OUT, 4, 2, 2, 2>(a, st);
+        case 2: return launch_gemm_cfg<IN, OUT, 2, 4, 2, 2>(a, st);
+        case 3: return launch_gemm_cfg<IN, OUT, 4, 4, 2, 2>(a, st);
+        case 4: return launch_gemm_cfg<IN, OUT, 8, 4, 2, 2>(a, st);
+        case 5: return launch_gemm_cfg<IN, OUT, 4, 8, 2, 2>(a, st);
+        case 6: return launch_gemm_cfg<IN, OUT, 8, 8, 2, 4>(a, st);
+        case 7: return launch_gemm_cfg<IN, OUT, 8, 2, 4, 1>(a, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+int choose_gemm_config(const GemmArgs &a, int in_dtype)
+{
+    const bool bf16 = in_dtype == LPG_BF16;
+    int best = 3;
+    double best_cost = 1e300;
+    for (int i = 0; i < kNumCfgs; ++i) {
+        const double c = estimate_cost(a, kCfgs[i], bf16);
+        if (c < best_cost * 0.999) {  // later (larger) configurations must win clearly
+            best_cost = c;
+            best = i;
+        }
+    }
+    return best;
+}
+
+hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, int cfg, hipStream_t st)
+{
+    if (cfg < 0 || cfg >= kNumCfgs) cfg = choose_gemm_config(a, in_dtype);
+    if (in_dtype == LPG_F32 && out_dtype == LPG_F32) return launch_gemm_dtype<F32, F32>(a, cfg, st);
+    if (in_dtype == LPG_BF16 && out_dtype == LPG_BF16) return launch_gemm_dtype<BF16, BF16>(a, cfg, st);
+    if (in_dtype == LPG_BF16 && out_dtype == LPG_F32) return launch_gemm_dtype<BF16, F32>(a, cfg, st);
     return hipErrorInvalidValue;
 }
 

@@ -200,3 +200,29 @@ def test_elementwise_ops(dtype):
         back = got.astype(np.float32).view(np.uint32)
         back = (back >> 16).astype(np.uint16) if dtype == LPG_BF16 else back
         assert np.array_equal(raw, ref.pack(back, True, ES[dtype]))            # padding stays zero
+
+
+@pytest.mark.parametrize("cfg", range(8))
+def test_every_tile_configuration(cfg, monkeypatch):
+    """Each tile configuration of the GEMM kernel, forced through LPG_FORCE_TILE, on shapes
+    that span several tiles, a ragged tail and several tiles per persistent workgroup."""
+    monkeypatch.setenv("LPG_FORCE_TILE", str(cfg))
+    rng = np.random.default_rng(100 + cfg)
+    for (m, n, k) in [(300, 520, 200), (70, 40, 33), (1200, 2100, 96)]:
+        A = rng.uniform(-1, 1, (m, k)).astype(np.float32)
+        B = rng.uniform(-1, 1, (k, n)).astype(np.float32)
+        C = rng.uniform(-1, 1, (m, n)).astype(np.float32)
+        for c_kind in (LPG_PACKED_A, LPG_PACKED_B):
+            got, raw, _ = run_gemm(A, B, LPG_F32, LPG_F32, c_kind, alpha=1.5, beta=0.5, C=C)
+            assert ref.rel_frobenius(got, ref.gemm(A, B, 1.5, 0.5, C)) <= F32_TOL, (cfg, m, n, k)
+            assert np.array_equal(raw, ref.pack(got.astype(np.float32), c_kind == LPG_PACKED_A, 4))
+        Ab, Bb = bf16_exact(A), bf16_exact(B)
+        got, _, _ = run_gemm(Ab, Bb, LPG_BF16, LPG_BF16, LPG_PACKED_A)
+        assert ref.rel_frobenius(got, ref.gemm(Ab, Bb)) <= BF16_TOL, (cfg, m, n, k)
+        got, _, _ = run_gemm(Ab, Bb, LPG_BF16, LPG_F32, LPG_PACKED_B)
+        assert ref.rel_frobenius(got, ref.gemm(Ab, Bb)) <= 1e-5, (cfg, m, n, k)
+    # integer inputs: exact, many tiles per workgroup (batched)
+    A = rng.integers(-2, 3, (96, 64)).astype(np.float32)
+    B = rng.integers(-2, 3, (64, 96)).astype(np.float32)
+    got, _, _ = run_gemm(A, B, LPG_F32, LPG_F32, LPG_PACKED_A)
+    assert np.array_equal(got, ref.gemm(A, B))
