@@ -65,20 +65,24 @@ def time_gemm_launches(ch, steps):
     return total_ms * 1e-3 / len(pairs), nflops / ngemm
 
 
-def measure(name, steps, warmup, shape_over=None):
+def measure(name, steps, warmup, shape_over=None, modes="both"):
     from paper_2604_04599_amd import api, chains, inputs
     inp, shape = inputs.make(name, **(shape_over or {}))
     ch = chains.build(name, inp, shape)
     flops = inputs.gemm_flops(name, shape)
-    t_prop = time_chain(ch, api.LPG_CHAIN_PROPAGATED, steps, warmup)
-    t_canon = time_chain(ch, api.LPG_CHAIN_CANONICAL, steps, warmup)
     dt = inputs.DTYPES[name]
-    tf = flops / t_prop / 1e12
-    res = {"dtype": dt, "shape": shape, "gemm_gflop": round(flops / 1e9, 3),
-           "ms_per_step": round(t_prop * 1e3, 4), "tflops": round(tf, 2),
-           "pct_mfma_peak": round(100 * tf / PEAK_TFLOPS[dt], 2),
-           "canonical_ms_per_step": round(t_canon * 1e3, 4),
-           "speedup_vs_canonical": round(t_canon / t_prop, 3)}
+    res = {"dtype": dt, "shape": shape, "gemm_gflop": round(flops / 1e9, 3)}
+    t_prop = t_canon = None
+    if modes in ("both", "propagated"):
+        t_prop = time_chain(ch, api.LPG_CHAIN_PROPAGATED, steps, warmup)
+        tf = flops / t_prop / 1e12
+        res.update({"ms_per_step": round(t_prop * 1e3, 4), "tflops": round(tf, 2),
+                    "pct_mfma_peak": round(100 * tf / PEAK_TFLOPS[dt], 2)})
+    if modes in ("both", "canonical"):
+        t_canon = time_chain(ch, api.LPG_CHAIN_CANONICAL, steps, warmup)
+        res["canonical_ms_per_step"] = round(t_canon * 1e3, 4)
+    if t_prop and t_canon:
+        res["speedup_vs_canonical"] = round(t_canon / t_prop, 3)
     return res, ch, inp, shape
 
 
@@ -111,7 +115,12 @@ def main():
                     help="comma list of extra workloads to report beside the headline, 'all' or 'none'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default=None,
-                    help="profiling aid: time just this workload (both modes) and print its line")
+                    help="profiling aid: time just this workload and print its line")
+    ap.add_argument("--mode", default="both", choices=["both", "propagated", "canonical"],
+                    help="with --only: which chain mode(s) to run")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="profiling aid: run the elementwise SCALE kernel over a buffer of MIB MiB "
+                         "(reads MIB, writes MIB per launch) --steps times, to scale HBM counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1",
@@ -125,8 +134,20 @@ def main():
     torch.cuda.set_device(0)
     from paper_2604_04599_amd import inputs
 
+    if args.copy_calibration:
+        from paper_2604_04599_amd import api
+        n = args.copy_calibration << 20
+        x = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        d = api.desc(api.LPG_ROW_MAJOR, api.LPG_F32, n // 4096, 1024)
+        for _ in range(args.steps):
+            api.lpg_elementwise_packed(api.LPG_EW_SCALE, x, None, 1.0, y, d, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_mib": args.copy_calibration, "launches": args.steps}))
+        return
+
     if args.only:
-        res, _, _, _ = measure(args.only, args.steps, args.warmup)
+        res, _, _, _ = measure(args.only, args.steps, args.warmup, modes=args.mode)
         print(json.dumps({"workload": args.only, **res}))
         return
 

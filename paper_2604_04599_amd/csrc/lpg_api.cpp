@@ -193,6 +193,7 @@ static int do_pack_unpack(bool pack, const void *canon, const lpg_desc *cd, cons
     a.ngroups = (int32_t)((pv.F + 31) / 32);
     a.nkb = (int32_t)((pv.K + kb_of(pv.dtype) - 1) / kb_of(pv.dtype));
     a.batch = pv.batch;
+    a.kpw = 1;
     if (a.nkb > 65535 || a.batch > 65535) return fail(LPG_EUNSUPPORTED, "%s: more than 65535 K blocks or batches", name);
     hipError_t e = pack ? launch_pack(a, cv.dtype, pv.dtype, st) : launch_unpack(a, pv.dtype, cv.dtype, st);
     if (e != hipSuccess) return fail(LPG_EHIP, "%s: %s", name, hipGetErrorString(e));

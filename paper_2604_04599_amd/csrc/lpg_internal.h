@@ -57,6 +57,7 @@ struct PackArgs {
     int32_t ngroups;     // ceil(F/32)
     int32_t nkb;         // ceil(K/KB)
     int32_t batch;
+    int32_t kpw;         // K blocks per workgroup (set by the launcher)
 };
 
 struct GemmArgs {

@@ -53,131 +53,167 @@ __device__ __forceinline__ typename D::raw convert_raw(typename S::raw x)
 }
 
 // ---------------------------------------------------------------------------------
-// pack / unpack.  One workgroup of 256 threads moves one block (32 f x KB k).
+// pack / unpack.  A workgroup of 256 threads moves whole blocks (32 f x KB k), KPW
+// consecutive K blocks of one 32-group per workgroup.
 // PACK = true: canonical -> packed (zero padding written); false: packed -> canonical.
 // C = canonical element type, P = packed element type.
 // KC = true: canonical is contiguous along k (sk == 1); thread t handles free index
-//   t/8 and the (t%8)-th eighth of the block's k range, so 8 neighbouring lanes touch
-//   one contiguous run of the canonical row and one contiguous 128-byte run of a
-//   fragment half.
+//   t/8 and the (t%8)-th eighth of the block's k range: PER = KB/8 consecutive canonical
+//   elements, moved as 16- or 32-byte vectors when VEC says every such run is 16-byte
+//   aligned, so 8 neighbouring lanes touch one contiguous run of the canonical row and one
+//   contiguous 128-byte run of a fragment half.
 // KC = false: canonical is contiguous along f (sf == 1); thread t owns the 16 packed
 //   bytes at t*16 and touches KV canonical elements, lanes running along f.
-template <bool PACK, typename C, typename P, bool KC>
+template <typename T, int N>
+__device__ __forceinline__ void load_run(T (&dst)[N], const T *src, bool vec)
+{
+    constexpr int BYTES = N * (int)sizeof(T);
+    static_assert(BYTES % 16 == 0, "runs are whole 16-byte vectors");
+    if (vec) {
+        uint4 q[BYTES / 16];
+#pragma unroll
+        for (int i = 0; i < BYTES / 16; ++i) q[i] = ((const uint4 *)src)[i];
+        __builtin_memcpy(dst, q, BYTES);
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) dst[i] = src[i];
+    }
+}
+template <typename T, int N>
+__device__ __forceinline__ void store_run(T *dst, const T (&src)[N])
+{
+    constexpr int BYTES = N * (int)sizeof(T);
+    uint4 q[BYTES / 16];
+    __builtin_memcpy(q, src, BYTES);
+#pragma unroll
+    for (int i = 0; i < BYTES / 16; ++i) ((uint4 *)dst)[i] = q[i];
+}
+
+template <bool PACK, typename C, typename P, bool KC, bool VEC>
 __global__ __launch_bounds__(256) void pack_kernel(PackArgs a)
 {
     typedef typename C::raw craw;
     typedef typename P::raw praw;
     constexpr int KV = P::KV, KF = P::KF, KB = P::KB;
-    const int g = blockIdx.x, kb = blockIdx.y, b = blockIdx.z;
+    const int g = blockIdx.x, b = blockIdx.z;
     const int t = threadIdx.x;
-    const char *cbase = a.canon + (int64_t)(b / a.c_div) * a.c_slot;
-    char *pblock = a.packed + (int64_t)(b / a.p_div) * a.p_slot + (int64_t)kb * a.p_kbs +
-                   (int64_t)g * kBlockBytes;
-    craw *canon = (craw *)cbase;
+    craw *canon = (craw *)(a.canon + (int64_t)(b / a.c_div) * a.c_slot);
+    char *pgroup = a.packed + (int64_t)(b / a.p_div) * a.p_slot + (int64_t)g * kBlockBytes;
+    const int kb_end = min(a.nkb, (int)(blockIdx.y + 1) * a.kpw);
 
-    if constexpr (KC) {
-        const int fl = t >> 3, piece = t & 7;
-        const int64_t f = (int64_t)g * 32 + fl;
-        constexpr int PER = KB / 8;  // consecutive k per thread: 4 (fp32) or 8 (bf16)
-        const int64_t kbase = (int64_t)kb * KB + piece * PER;
-        // k = KF*c + 8*u + 4*h + j for j < 4:   fp32: piece = 2c + h (u = 0);
-        // bf16: piece = 2c + u, the eight k split into h = 0 (first four) and h = 1.
-        if constexpr (P::ES == 4) {
-            const int c = piece >> 1, h = piece & 1;
-            praw *dst = (praw *)(pblock + c * kFragBytes + h * 512 + fl * 16);
+    for (int kb = blockIdx.y * a.kpw; kb < kb_end; ++kb) {
+        char *pblock = pgroup + (int64_t)kb * a.p_kbs;
+        if constexpr (KC) {
+            const int fl = t >> 3, piece = t & 7;
+            const int64_t f = (int64_t)g * 32 + fl;
+            constexpr int PER = KB / 8;  // consecutive k per thread: 4 (fp32) or 8 (bf16)
+            const int64_t kbase = (int64_t)kb * KB + piece * PER;
+            craw *run = canon + f * a.sf + kbase;
+            const bool row_in = f < a.F;
+            const bool whole = row_in && kbase + PER <= a.K;
+            craw cv[PER];
+            praw pv[PER];
+            // packed position of the run: k = KF*c + 8*u + 4*h + j (j < 4).
+            //   fp32: piece = 2c + h, one 16-byte vector.
+            //   bf16: piece = 2c + u; its first four k have h = 0, the last four h = 1: two
+            //   8-byte halves of neighbouring 16-byte lane vectors.
+            char *dst0 = pblock + (piece >> 1) * kFragBytes + fl * 16;
             if constexpr (PACK) {
-                praw v[4];
+                if (whole) {
+                    load_run(cv, run, VEC);
+                } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int64_t k = kbase + j;
-                    v[j] = (f < a.F && k < a.K) ? convert_raw<C, P>(canon[f * a.sf + k]) : (praw)0;
+                    for (int j = 0; j < PER; ++j) cv[j] = (row_in && kbase + j < a.K) ? run[j] : (craw)0;
                 }
-                *(uint4 *)dst = make_uint4(v[0], v[1], v[2], v[3]);
-            } else {
-                const uint4 q = *(const uint4 *)dst;
-                const praw v[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int64_t k = kbase + j;
-                    if (f < a.F && k < a.K) canon[f * a.sf + k] = convert_raw<P, C>(v[j]);
+                for (int j = 0; j < PER; ++j) pv[j] = convert_raw<C, P>(cv[j]);
+                if constexpr (P::ES == 4) {
+                    *(uint4 *)(dst0 + (piece & 1) * 512) = make_uint4(pv[0], pv[1], pv[2], pv[3]);
+                } else {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        *(uint2 *)(dst0 + h * 512 + (piece & 1) * 8) =
+                            make_uint2((uint32_t)pv[4 * h] | ((uint32_t)pv[4 * h + 1] << 16),
+                                       (uint32_t)pv[4 * h + 2] | ((uint32_t)pv[4 * h + 3] << 16));
+                }
+            } else {
+                if constexpr (P::ES == 4) {
+                    const uint4 q = *(const uint4 *)(dst0 + (piece & 1) * 512);
+                    pv[0] = q.x; pv[1] = q.y; pv[2] = q.z; pv[3] = q.w;
+                } else {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint2 q = *(const uint2 *)(dst0 + h * 512 + (piece & 1) * 8);
+                        pv[4 * h] = (praw)(q.x & 0xffff); pv[4 * h + 1] = (praw)(q.x >> 16);
+                        pv[4 * h + 2] = (praw)(q.y & 0xffff); pv[4 * h + 3] = (praw)(q.y >> 16);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < PER; ++j) cv[j] = convert_raw<P, C>(pv[j]);
+                if (whole && VEC) {
+                    store_run(run, cv);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < PER; ++j)
+                        if (row_in && kbase + j < a.K) run[j] = cv[j];
                 }
             }
         } else {
-            const int c = piece >> 1, u = piece & 1;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                praw *dst = (praw *)(pblock + c * kFragBytes + h * 512 + fl * 16 + u * 8);
-                if constexpr (PACK) {
-                    praw v[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int64_t k = kbase + 4 * h + j;
-                        v[j] = (f < a.F && k < a.K) ? convert_raw<C, P>(canon[f * a.sf + k])
-                                                    : (praw)0;
-                    }
-                    *(uint2 *)dst = make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16),
-                                               (uint32_t)v[2] | ((uint32_t)v[3] << 16));
+            const int c = t >> 6, lane = t & 63, h = lane >> 5, fl = lane & 31;
+            const int64_t f = (int64_t)g * 32 + fl;
+            praw *dst = (praw *)(pblock + t * 16);
+            praw v[KV];
+            if constexpr (!PACK) {
+                const uint4 q = *(const uint4 *)dst;
+                if constexpr (P::ES == 4) {
+                    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
                 } else {
-                    const uint2 q = *(const uint2 *)dst;
-                    const praw v[4] = {(praw)(q.x & 0xffff), (praw)(q.x >> 16),
-                                       (praw)(q.y & 0xffff), (praw)(q.y >> 16)};
+                    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int64_t k = kbase + 4 * h + j;
-                        if (f < a.F && k < a.K) canon[f * a.sf + k] = convert_raw<P, C>(v[j]);
-                    }
+                    for (int j = 0; j < 8; ++j) v[j] = (praw)((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
                 }
             }
-        }
-    } else {
-        const int c = t >> 6, lane = t & 63, h = lane >> 5, fl = lane & 31;
-        const int64_t f = (int64_t)g * 32 + fl;
-        praw *dst = (praw *)(pblock + t * 16);
-        praw v[KV];
-        if constexpr (!PACK) {
-            const uint4 q = *(const uint4 *)dst;
-            if constexpr (P::ES == 4) {
-                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-            } else {
-                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = (praw)((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
+            for (int j = 0; j < KV; ++j) {
+                const int64_t k = (int64_t)kb * KB + KF * c + 8 * (j >> 2) + 4 * h + (j & 3);
+                const bool in = (f < a.F && k < a.K);
+                if constexpr (PACK)
+                    v[j] = in ? convert_raw<C, P>(canon[k * a.sk + f]) : (praw)0;
+                else if (in)
+                    canon[k * a.sk + f] = convert_raw<P, C>(v[j]);
             }
-        }
+            if constexpr (PACK) {
+                if constexpr (P::ES == 4) {
+                    *(uint4 *)dst = make_uint4(v[0], v[1], v[2], v[3]);
+                } else {
+                    uint32_t w[4];
 #pragma unroll
-        for (int j = 0; j < KV; ++j) {
-            const int64_t k = (int64_t)kb * KB + KF * c + 8 * (j >> 2) + 4 * h + (j & 3);
-            const bool in = (f < a.F && k < a.K);
-            if constexpr (PACK)
-                v[j] = in ? convert_raw<C, P>(canon[k * a.sk + f]) : (praw)0;
-            else if (in)
-                canon[k * a.sk + f] = convert_raw<P, C>(v[j]);
-        }
-        if constexpr (PACK) {
-            if constexpr (P::ES == 4) {
-                *(uint4 *)dst = make_uint4(v[0], v[1], v[2], v[3]);
-            } else {
-                uint32_t w[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) w[j] = (uint32_t)v[2 * j] | ((uint32_t)v[2 * j + 1] << 16);
-                *(uint4 *)dst = make_uint4(w[0], w[1], w[2], w[3]);
+                    for (int j = 0; j < 4; ++j) w[j] = (uint32_t)v[2 * j] | ((uint32_t)v[2 * j + 1] << 16);
+                    *(uint4 *)dst = make_uint4(w[0], w[1], w[2], w[3]);
+                }
             }
         }
     }
 }
 
 template <bool PACK>
-static hipError_t launch_pack_impl(const PackArgs &a, int cdt, int pdt, hipStream_t st)
+static hipError_t launch_pack_impl(PackArgs a, int cdt, int pdt, hipStream_t st)
 {
     if (a.ngroups <= 0 || a.nkb <= 0 || a.batch <= 0) return hipSuccess;
-    dim3 grid(a.ngroups, a.nkb, a.batch), block(256);
+    a.kpw = a.nkb >= 16 ? 4 : 1;
+    dim3 grid(a.ngroups, (a.nkb + a.kpw - 1) / a.kpw, a.batch), block(256);
     const bool kc = (a.sk == 1);
-#define LPG_PACK_CASE(CT, PT)                                                          \
-    do {                                                                               \
-        if (kc)                                                                        \
-            hipLaunchKernelGGL((pack_kernel<PACK, CT, PT, true>), grid, block, 0, st, a); \
-        else                                                                           \
-            hipLaunchKernelGGL((pack_kernel<PACK, CT, PT, false>), grid, block, 0, st, a); \
+    // vector path: every PER-element run of the canonical side starts on a 16-byte boundary
+    const int ces = cdt == LPG_F32 ? 4 : 2;
+    const bool vec = kc && ((uintptr_t)a.canon % 16 == 0) && ((a.sf * ces) % 16 == 0) && (a.c_slot % 16 == 0);
+#define LPG_PACK_CASE(CT, PT)                                                                    \
+    do {                                                                                         \
+        if (kc && vec)                                                                           \
+            hipLaunchKernelGGL((pack_kernel<PACK, CT, PT, true, true>), grid, block, 0, st, a);  \
+        else if (kc)                                                                             \
+            hipLaunchKernelGGL((pack_kernel<PACK, CT, PT, true, false>), grid, block, 0, st, a); \
+        else                                                                                     \
+            hipLaunchKernelGGL((pack_kernel<PACK, CT, PT, false, false>), grid, block, 0, st, a); \
     } while (0)
     if (cdt == LPG_F32 && pdt == LPG_F32) LPG_PACK_CASE(F32, F32);
     else if (cdt == LPG_BF16 && pdt == LPG_BF16) LPG_PACK_CASE(BF16, BF16);
