@@ -4,6 +4,9 @@
 // contraction indices, each made of four 1 KiB fragments; a fragment is the
 // 64-lane x 16-byte register image of an MFMA operand.  Lane l = 32*h + fl of
 // fragment c holds free index fl and k = KF*c + 8*(v/4) + 4*h + v%4, v < KV.
+#include <cstdio>
+#include <cstdlib>
+
 #include "lpg_internal.h"
 
 namespace lpg {
@@ -516,10 +519,12 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     int c_st = 0;                      // ring stage it fills next
     int pending = 0;                   // steps copied (or in flight) and not yet multiplied
     bool c_live = spt > 0;
-    auto copy_step = [&]() {
-        const uint32_t dst = sbase + c_st * STAGE + wave * kFragBytes;
-#pragma unroll
-        for (int i = 0; i < FPW; ++i) lds_dma16(src[i], dst + i * NW * kFragBytes);
+    // fragment i of the step the copy cursor stands on -> ring stage c_st
+    auto copy_issue = [&](int i) {
+        lds_dma16(src[i], sbase + c_st * STAGE + (i * NW + wave) * kFragBytes);
+    };
+    // move the copy cursor one step on
+    auto copy_advance = [&]() {
         c_st = (c_st + 1 == NS) ? 0 : c_st + 1;
         ++pending;
         if (++c_s == spt) {  // next tile
@@ -538,6 +543,11 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
 #pragma unroll
             for (int i = 0; i < FPW; ++i) src[i] += (i < FPW_L) ? dl : dr;
         }
+    };
+    auto copy_step = [&]() {
+#pragma unroll
+        for (int i = 0; i < FPW; ++i) copy_issue(i);
+        copy_advance();
     };
     aim(decode(c_vb));
 #pragma unroll
@@ -580,68 +590,52 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
             if (pending == NS - 1) wait_vmcnt<KEEP * FPW>();
             else wait_vmcnt<0>();
             __syncthreads();  // everyone's transfers landed; the stage multiplied last step is free
-            if (c_live) copy_step();
 
             const char *sL = sLw + st * STAGE;
             const char *sR = sRw + st * STAGE;
             const int stn = (st + 1 == NS) ? 0 : st + 1;
-            if (LPG_DBG & 2) { st = stn; --pending; continue; }
+            if (LPG_DBG & 2) { st = stn; --pending; if (c_live) copy_step(); continue; }
             if constexpr (!XPF) {
 #pragma unroll
                 for (int a = 0; a < WTL; ++a) lf[0][a] = *(const uint4 *)(sL + a * (FS * kFragBytes));
 #pragma unroll
                 for (int q = 0; q < WTR; ++q) rf[0][q] = *(const uint4 *)(sR + q * (FS * kFragBytes));
             }
+            // The step is cut into FS*WTL phases (one row of the wave's tiles each).  A phase
+            // reads its share of the NEXT fragment from LDS, multiplies one row of the current
+            // fragment, and issues its share of this step's global->LDS transfers, so that
+            // neither LDS reads nor transfer issue ever pile up in front of the MFMAs.  After
+            // the last real step the transfers go on as harmless refills of the one ring
+            // stage nobody reads again (their sources stay valid), which keeps this loop free
+            // of branches.
+            constexpr int SLOTS = FS * WTL;
 #pragma unroll
             for (int c = 0; c < FS; ++c) {
-                if (c + 1 < FS) {
+                const int cb = c & 1, nb = (c + 1) & 1;
+                const bool more = c + 1 < FS;
+                const char *nL = more ? sL + (c + 1) * kFragBytes : sLw + stn * STAGE;
+                const char *nR = more ? sR + (c + 1) * kFragBytes : sRw + stn * STAGE;
 #pragma unroll
-                    for (int a = 0; a < WTL; ++a)
-                        lf[(c + 1) & 1][a] = *(const uint4 *)(sL + a * (FS * kFragBytes) + (c + 1) * kFragBytes);
+                for (int a = 0; a < WTL; ++a) {
+                    if (more || XPF) {
+                        lf[nb][a] = *(const uint4 *)(nL + a * (FS * kFragBytes));
+                        if (a < WTR) rf[nb][a] = *(const uint4 *)(nR + a * (FS * kFragBytes));
+                        if (a == WTL - 1) {
 #pragma unroll
-                    for (int q = 0; q < WTR; ++q)
-                        rf[(c + 1) & 1][q] = *(const uint4 *)(sR + q * (FS * kFragBytes) + (c + 1) * kFragBytes);
-                } else if constexpr (XPF) {
-                    // fragment 0 of the next step (after the very last step this reads a stage
-                    // nobody uses; the address stays inside the ring)
-#pragma unroll
-                    for (int a = 0; a < WTL; ++a)
-                        lf[0][a] = *(const uint4 *)(sLw + stn * STAGE + a * (FS * kFragBytes));
-#pragma unroll
-                    for (int q = 0; q < WTR; ++q)
-                        rf[0][q] = *(const uint4 *)(sRw + stn * STAGE + q * (FS * kFragBytes));
-                }
-#pragma unroll
-                for (int a = 0; a < WTL; ++a)
-#pragma unroll
-                    for (int q = 0; q < WTR; ++q) mma_frag<IN>(acc[a][q], rf[c & 1][q], lf[c & 1][a]);
-            }
-            // Scheduling recipe for the block above: the reads of the next fragment are spread
-            // one by one between the MFMAs of the current one, so LDS latency hides behind
-            // matrix work instead of being waited for in front of every MFMA.
-            {
-                constexpr int NR = WTL + WTR;
-                constexpr int NM = WTL * WTR * (IN::ES == 4 ? 4 : 1);
-                constexpr int PAIRS = NM < NR ? NM : NR;
-                if constexpr (!XPF) sched_group<0x100, NR>();
-#pragma unroll
-                for (int c = 0; c < FS; ++c) {
-                    if (c + 1 < FS || XPF) {
-#pragma unroll
-                        for (int i = 0; i < PAIRS - 1; ++i) {
-                            sched_group<0x008, 1>();
-                            sched_group<0x100, 1>();
+                            for (int q = WTL; q < WTR; ++q) rf[nb][q] = *(const uint4 *)(nR + q * (FS * kFragBytes));
                         }
-                        sched_group<0x008, 1>();
-                        sched_group<0x100, NR - (PAIRS - 1)>();
-                        sched_group<0x008, NM - PAIRS>();
-                    } else {
-                        sched_group<0x008, NM>();
                     }
+#pragma unroll
+                    for (int q = 0; q < WTR; ++q) mma_frag<IN>(acc[a][q], rf[cb][q], lf[cb][a]);
+                    const int slot = c * WTL + a;
+#pragma unroll
+                    for (int i = (slot * FPW) / SLOTS; i < ((slot + 1) * FPW) / SLOTS; ++i) copy_issue(i);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             st = stn;
             --pending;
+            if (c_live) copy_advance();
         }
 
         // ---- epilogue
@@ -661,6 +655,7 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
             }
         }
     }
+    wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
 }
 
 // Tile configurations (TLG, TRG, WL, WR) in 32-groups; index = position in this list.
@@ -710,9 +705,11 @@ static int workgroups_per_cu(const TileCfg &c, bool bf16)
     return occ < 1 ? 1 : occ;
 }
 
-// Estimated run time (arbitrary units) of one GEMM with a tile configuration: the MFMA
-// work of the busiest compute unit, derated when few waves share a SIMD (less latency
-// hiding) or when a wave's tile is so small that LDS reads per MFMA dominate.
+// Estimated run time (cycles of the busiest compute unit) of one GEMM with a tile
+// configuration.  Three terms: MFMA time, derated when only one wave feeds a SIMD or when a
+// wave's tile is so small that LDS reads per MFMA dominate; the L2->LDS transfer time that
+// does not hide behind the MFMAs; and a fixed cost per tile (epilogue, pipeline refill).
+// The constants were fitted to measured timings of the benchmark shapes on MI355X.
 static double estimate_cost(const GemmArgs &a, const TileCfg &c, bool bf16)
 {
     const int64_t tl = (a.FLg + c.tlg - 1) / c.tlg, tr = (a.FRg_out + c.trg - 1) / c.trg;
@@ -722,16 +719,16 @@ static double estimate_cost(const GemmArgs &a, const TileCfg &c, bool bf16)
     const int64_t per_cu = (tiles + ncu - 1) / ncu;  // tiles the busiest CU runs
     const int wtl = c.tlg / c.wl, wtr = c.trg / c.wr;
     const double waves_per_simd = (double)(c.wl * c.wr) / 4.0;
-    double tile_time = (double)wtl * wtr * waves_per_simd * (a.nkb > 0 ? a.nkb : 1) + 0.35 * wtl * wtr;
+    const int nkb = a.nkb > 0 ? a.nkb : 1;
+    const double cy_block = bf16 ? 128.0 : 1024.0;  // MFMA cycles of one 32x32 tile over one K block
     const int resident = (int)((per_cu < occ ? per_cu : occ) * waves_per_simd);  // waves per SIMD
-    double eff = resident >= 2 ? 1.0 : 0.8;
-    if (bf16) {
-        const double reads_per_mma = (double)(wtl + wtr) / (wtl * wtr);
-        eff /= (1.0 + 0.35 * reads_per_mma);
-    } else {
-        eff /= (1.0 + 0.03 * (double)(wtl + wtr) / (wtl * wtr));
-    }
-    return per_cu * tile_time / eff;
+    double eff = resident >= 2 ? 1.0 : (bf16 ? 0.8 : 1.0);
+    const double reads_per_mma = (double)(wtl + wtr) / (wtl * wtr);
+    eff /= 1.0 + (bf16 ? 0.217 : 0.0525) * reads_per_mma;
+    const double mfma = (double)per_cu * (c.tlg * c.trg / 4.0) * nkb * cy_block / eff;
+    const double traffic = (double)per_cu * nkb * (c.tlg + c.trg) * 205.0 * (bf16 ? 0.141 : 0.0805);
+    const double fixed = (double)per_cu * (c.tlg * c.trg * (bf16 ? 60.0 : 32.0) + 2228.0);
+    return mfma + traffic + fixed;
 }
 
 template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR>
@@ -786,7 +783,7 @@ int choose_gemm_config(const GemmArgs &a, int in_dtype)
     double best_cost = 1e300;
     for (int i = 0; i < kNumCfgs; ++i) {
         const double c = estimate_cost(a, kCfgs[i], bf16);
-        if (c < best_cost * 0.999) {  // later (larger) configurations must win clearly
+        if (c < best_cost * 0.9995) {  // later (larger) configurations must win clearly
             best_cost = c;
             best = i;
         }
@@ -797,6 +794,8 @@ int choose_gemm_config(const GemmArgs &a, int in_dtype)
 hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, int cfg, hipStream_t st)
 {
     if (cfg < 0 || cfg >= kNumCfgs) cfg = choose_gemm_config(a, in_dtype);
+    if (getenv("LPG_TRACE_TILE"))
+        fprintf(stderr, "lpg gemm: FL %d FR %d nkb %d batch %d -> tile configuration %d\n", a.FL, a.FR, a.nkb, a.batch, cfg);
     if (in_dtype == LPG_F32 && out_dtype == LPG_F32) return launch_gemm_dtype<F32, F32>(a, cfg, st);
     if (in_dtype == LPG_BF16 && out_dtype == LPG_BF16) return launch_gemm_dtype<BF16, BF16>(a, cfg, st);
     if (in_dtype == LPG_BF16 && out_dtype == LPG_F32) return launch_gemm_dtype<BF16, F32>(a, cfg, st);
