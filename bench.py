@@ -100,6 +100,12 @@ def measure(name, steps, warmup, shape_over=None, modes="both"):
         res["canonical_ms_per_step"] = round(mc * 1e3, 4)
         res["propagated_ms_per_step_interleaved"] = round(mp * 1e3, 4)
         res["speedup_vs_canonical"] = round(mc / mp, 3)
+        # the same chain with the entry pack / exit unpack fused into the first / last GEMM
+        fch = chains.build(name, inp, shape, fused=True)
+        t_f = time_chain(fch, api.LPG_CHAIN_PROPAGATED, steps, warmup)
+        res["fused_boundaries_ms_per_step"] = round(t_f * 1e3, 4)
+        res["fused_boundaries_tflops"] = round(flops / t_f / 1e12, 2)
+        del fch
     return res, ch, inp, shape
 
 

@@ -154,6 +154,16 @@ int lpg_unpack(const void *src, const lpg_desc *src_d, void *dst, const lpg_desc
  *   supports).  C_in == C_out (in place) is allowed; C_out must not alias A or B.
  *   Batches: c_d.batch matrices; A, B use slot b / batch_div of their descriptors.
  *   Padding of C_out is written as zeros.
+ * The same call is also the paper's Initial and Ending kernels (III-A.1, III-A.3):
+ *   Initial: a_d may be LPG_ROW_MAJOR and/or b_d LPG_COL_MAJOR (the canonical order
+ *   that is contiguous along the contraction index).  The kernel then gathers MFMA
+ *   fragments straight from the canonical matrix, no pack pass.  fp32 only, the
+ *   contraction extent a multiple of 32, base/ld/origin keeping rows 16-byte
+ *   aligned; anything else is reported (LPG_EUNSUPPORTED / LPG_EALIGN): pack it.
+ *   Ending: c_d may be LPG_ROW_MAJOR or LPG_COL_MAJOR (any dtype pair above, any
+ *   ld): C_out, and C_in / epi_arg if used, are then canonical, elements outside the
+ *   logical extent are left untouched, and no unpack pass is needed.
+ * Both give bit-identical values to lpg_pack / lpg_unpack around the packed call.
  */
 int lpg_gemm_packed(float alpha, const void *A, const lpg_desc *a_d, const void *B,
                     const lpg_desc *b_d, float beta, const void *C_in, void *C_out,

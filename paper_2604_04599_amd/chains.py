@@ -1,5 +1,11 @@
 """The five benchmark workloads expressed as lpg chains (lists of lpg_stage).
 
+Each builder has two forms.  The default packs the activations with lpg_pack at the
+chain's entry and unpacks the result with lpg_unpack at its exit.  With fused=True the
+first GEMM reads its canonical operand itself and the last GEMM writes the canonical
+result itself (the Initial and Ending kernels), so those passes disappear where the
+library supports it (fp32, k-contiguous inputs; any output).
+
 This module only allocates device memory (torch), fills descriptors and stage
 lists, and calls the C ABI through `api`; all computation happens in the HIP
 library.  Weights are packed once when a chain is built (they are constants of
@@ -127,7 +133,7 @@ def _packed_elems(dtype, free, k):
 
 # ------------------------------------------------------------------------------------
 
-def build_two_gemm(inp, shape):
+def build_two_gemm(inp, shape, fused=False):
     n = shape["n"]
     ch = Chain("two_gemm", shape, 2 * 2 * n ** 3)
     a = ch.inputs["A"] = device_array(inp["A"])
@@ -139,6 +145,10 @@ def build_two_gemm(inp, shape):
     c2 = ch.new_packed("C2", ad)
     out = ch.outputs["C2"] = torch.empty((n, n), dtype=torch.float32, device=_dev())
     rm = desc(LPG_ROW_MAJOR, LPG_F32, n, n)
+    if fused:
+        ch.add(api.stage_gemm(1.0, a, rm, ch.bufs["B1"][0], b1d, 0.0, None, c1, ad))
+        ch.add(api.stage_gemm(1.0, c1, ad, ch.bufs["B2"][0], b2d, 0.0, None, out, rm))
+        return ch
     ch.add(api.stage_pack(a, rm, pa, ad))
     ch.add(api.stage_gemm(1.0, pa, ad, ch.bufs["B1"][0], b1d, 0.0, None, c1, ad))
     ch.add(api.stage_gemm(1.0, c1, ad, ch.bufs["B2"][0], b2d, 0.0, None, c2, ad))
@@ -146,7 +156,7 @@ def build_two_gemm(inp, shape):
     return ch
 
 
-def build_mlp(inp, shape):
+def build_mlp(inp, shape, fused=False):
     m, d, h = shape["m"], shape["d"], shape["h"]
     ch = Chain("mlp", shape, 2 * 2 * m * d * h)
     x = ch.inputs["X"] = device_array(inp["X"])
@@ -159,6 +169,12 @@ def build_mlp(inp, shape):
     py = ch.new_packed("Y", xd)
     out = ch.outputs["Y"] = torch.empty((m, d), dtype=torch.float32, device=_dev())
     rm = desc(LPG_ROW_MAJOR, LPG_F32, m, d)
+    if fused:
+        # X is read twice, both times in row-major: as the first GEMM's left operand and as
+        # the residual C_in of the second, whose C_out is row-major as well
+        ch.add(api.stage_gemm(1.0, x, rm, ch.bufs["W1"][0], w1d, 0.0, None, ph, hd))
+        ch.add(api.stage_gemm(1.0, ph, hd, ch.bufs["W2"][0], w2d, 1.0, x, out, rm))
+        return ch
     ch.add(api.stage_pack(x, rm, px, xd))
     ch.add(api.stage_gemm(1.0, px, xd, ch.bufs["W1"][0], w1d, 0.0, None, ph, hd))
     # residual: Y = H*W2 + 1*X, with C_in = packed X (it has Y's layout) and a separate C_out
@@ -167,7 +183,7 @@ def build_mlp(inp, shape):
     return ch
 
 
-def build_attention(inp, shape):
+def build_attention(inp, shape, fused=False):
     nh, t, dh = shape["heads"], shape["t"], shape["dh"]
     ch = Chain("attention", shape, nh * 2 * 2 * t * t * dh)
     q = ch.inputs["Q"] = device_array(inp["Q"])
@@ -185,6 +201,13 @@ def build_attention(inp, shape):
     pq, pk, pv = ch.new_packed("Q", qd), ch.new_packed("Kt", ktd), ch.new_packed("V", vd)
     ps, po = ch.new_packed("S", sd), ch.new_packed("O", od)
     out = ch.outputs["O"] = torch.empty((nh, t, dh), dtype=torch.float32, device=_dev())
+    if fused:
+        # Q_h and K_h^T are contiguous along the contraction index as they stand; V_h (a right
+        # operand stored row-major) is not and is still packed
+        ch.add(api.stage_pack(v, rm, pv, vd))
+        ch.add(api.stage_gemm(1.0 / float(np.sqrt(dh)), q, rm, k, ktd_src, 0.0, None, ps, sd))
+        ch.add(api.stage_gemm(1.0, ps, sd, pv, vd, 0.0, None, out, rm))
+        return ch
     ch.add(api.stage_pack(q, rm, pq, qd))
     ch.add(api.stage_pack(k, ktd_src, pk, ktd))
     ch.add(api.stage_pack(v, rm, pv, vd))
@@ -194,7 +217,7 @@ def build_attention(inp, shape):
     return ch
 
 
-def build_deep_chain(inp, shape):
+def build_deep_chain(inp, shape, fused=False):
     n, depth = shape["n"], shape["depth"]
     ch = Chain("deep_chain", shape, depth * 2 * n ** 3)
     c0 = ch.inputs["C0"] = device_array(inp["C0"])
@@ -203,24 +226,30 @@ def build_deep_chain(inp, shape):
     rm = desc(LPG_ROW_MAJOR, LPG_F32, n, n)
     for i in range(depth):
         ch.pack_weight(f"B{i}", inp["B"][i], LPG_PACKED_B, LPG_F32)
-    cur = ch.new_packed("C0", a_d)
-    ch.add(api.stage_pack(c0, rm, cur, a_d))
+    out = ch.outputs["C"] = torch.empty((n, n), dtype=torch.float32, device=_dev())
+    cm = desc(LPG_COL_MAJOR, LPG_F32, n, n)       # C^T column-major is C row-major
+    cur, cur_a, cur_b = ch.new_packed("C0", a_d), a_d, b_d
+    if fused:
+        cur, cur_a, cur_b = c0, rm, cm              # C_0 (or C_0^T) read as it stands
+    else:
+        ch.add(api.stage_pack(c0, rm, cur, a_d))
     for i in range(depth):
-        nxt = ch.new_packed(f"C{i + 1}", a_d)
+        last = fused and i == depth - 1
+        nxt = out if last else ch.new_packed(f"C{i + 1}", a_d)
         w = ch.bufs[f"B{i}"][0]
         if i % 2 == 0:
-            # C_{i+1} = C_i * B_i : C_i consumed as a packed left operand
-            ch.add(api.stage_gemm(1.0, cur, a_d, w, b_d, 0.0, None, nxt, a_d))
+            # C_{i+1} = C_i * B_i : C_i consumed as a left operand
+            ch.add(api.stage_gemm(1.0, cur, cur_a, w, b_d, 0.0, None, nxt, rm if last else a_d))
         else:
-            # the same bytes read as the packed right operand C_i^T of C_{i+1}^T = B_i^T * C_i^T
-            ch.add(api.stage_gemm(1.0, w, a_d, cur, b_d, 0.0, None, nxt, b_d))
-        cur = nxt
-    out = ch.outputs["C"] = torch.empty((n, n), dtype=torch.float32, device=_dev())
-    ch.add(api.stage_unpack(cur, a_d, out, rm))
+            # the same bytes read as the right operand C_i^T of C_{i+1}^T = B_i^T * C_i^T
+            ch.add(api.stage_gemm(1.0, w, a_d, cur, cur_b, 0.0, None, nxt, cm if last else b_d))
+        cur, cur_a, cur_b = nxt, a_d, b_d
+    if not fused:
+        ch.add(api.stage_unpack(cur, a_d, out, rm))
     return ch
 
 
-def build_decoder_layer(inp, shape):
+def build_decoder_layer(inp, shape, fused=False):
     t, hid, nq, nkv, ffn = shape["t"], shape["hidden"], shape["n_q"], shape["n_kv"], shape["ffn"]
     dh = hid // nq
     kvw = nkv * dh
@@ -269,6 +298,10 @@ def build_decoder_layer(inp, shape):
     ch.add(api.stage_gemm(1.0, pattn, ad, wt["Wg"], wd["Wg"], 0.0, None, pg, gd))
     ch.add(api.stage_gemm(1.0, pattn, ad, wt["Wu"], wd["Wu"], 0.0, None, pu, gd))
     ch.add(api.stage_elementwise(LPG_EW_SILU_MUL, pg, pu, 0.0, pact, gd))
+    if fused:
+        # only the exit can be fused here: X is converted fp32 -> bf16 by its pack
+        ch.add(api.stage_gemm(1.0, pact, gd, wt["Wd"], wd["Wd"], 0.0, None, out, desc(LPG_ROW_MAJOR, LPG_F32, t, hid)))
+        return ch
     ch.add(api.stage_gemm(1.0, pact, gd, wt["Wd"], wd["Wd"], 0.0, None, py, yd))
     ch.add(api.stage_unpack(py, yd, out, desc(LPG_ROW_MAJOR, LPG_F32, t, hid)))
     return ch
@@ -278,5 +311,5 @@ BUILDERS = {"two_gemm": build_two_gemm, "mlp": build_mlp, "attention": build_att
             "deep_chain": build_deep_chain, "decoder_layer": build_decoder_layer}
 
 
-def build(name, inp, shape):
-    return BUILDERS[name](inp, shape)
+def build(name, inp, shape, fused=False):
+    return BUILDERS[name](inp, shape, fused=fused)

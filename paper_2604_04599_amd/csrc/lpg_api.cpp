@@ -202,72 +202,140 @@ static int do_pack_unpack(bool pack, const void *canon, const lpg_desc *cd, cons
 
 // ------------------------------------------------------------------------------- GEMM
 
+// An input of the product in (free, contraction) terms, packed or canonical.
+struct Operand {
+    bool canon;
+    int dtype;
+    int64_t F, K;
+    int batch, bdiv;
+    int64_t origin, slot_step;  // bytes
+    int64_t kb_stride;          // packed: bytes between K blocks
+    int64_t ld_bytes;           // canonical: bytes between consecutive free indices
+};
+
+// is_a: the left operand (free = rows, must be PACKED_A or row-major); else the right operand
+// (free = cols, PACKED_B or column-major).  Canonical inputs are the fused Initial kernel:
+// fp32 only, contiguous along the contraction index, K a multiple of 32, 16-byte aligned rows.
+static int make_operand(const lpg_desc *d, const void *ptr, bool is_a, Operand *o)
+{
+    const char *what = is_a ? "lpg_gemm_packed A" : "lpg_gemm_packed B";
+    int rc = check_common(d, what);
+    if (rc) return rc;
+    if (!ptr) return fail(LPG_EINVAL, "%s: NULL pointer", what);
+    if ((uintptr_t)ptr % 16) return fail(LPG_EALIGN, "%s: buffer must be 16-byte aligned", what);
+    if (is_packed(d->kind)) {
+        if (d->kind != (is_a ? LPG_PACKED_A : LPG_PACKED_B))
+            return fail(LPG_ELAYOUT, "%s: must be %s", what, is_a ? "LPG_PACKED_A" : "LPG_PACKED_B");
+        PView v;
+        rc = make_pview(d, what, &v);
+        if (rc) return rc;
+        *o = Operand{false, v.dtype, v.F, v.K, v.batch, v.bdiv, v.origin, v.slot_step, v.kb_stride, 0};
+        return LPG_OK;
+    }
+    if (d->kind != (is_a ? LPG_ROW_MAJOR : LPG_COL_MAJOR))
+        return fail(LPG_ELAYOUT, "%s: a canonical operand must be contiguous along the contraction index (%s)", what,
+                    is_a ? "row-major" : "column-major");
+    CView v;
+    rc = make_cview(d, what, &v);
+    if (rc) return rc;
+    if (v.dtype != LPG_F32) return fail(LPG_EUNSUPPORTED, "%s: canonical operands are read directly only in fp32; pack it", what);
+    const int64_t K = is_a ? d->cols : d->rows, F = is_a ? d->rows : d->cols;
+    if (K % 32) return fail(LPG_EUNSUPPORTED, "%s: a canonical operand needs a contraction extent that is a multiple of 32; pack it", what);
+    const int64_t ld = is_a ? v.row_stride : v.col_stride;
+    if ((ld * 4) % 16 || (v.origin * 4) % 16 || (v.slot_step * 4) % 16)
+        return fail(LPG_EALIGN, "%s: rows of a canonical operand must start on 16-byte boundaries", what);
+    *o = Operand{true, v.dtype, F, K, v.batch, v.bdiv, v.origin * 4, v.slot_step * 4, 0, ld * 4};
+    return LPG_OK;
+}
+
 static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *B, const lpg_desc *b_d,
                    float beta, const void *C_in, void *C_out, const lpg_desc *c_d, int epi,
                    const void *epi_arg, hipStream_t st, bool launch)
 {
-    PView av, bv, cv;
-    int rc = make_pview(a_d, "lpg_gemm_packed A", &av);
+    Operand ao, bo;
+    int rc = make_operand(a_d, A, true, &ao);
     if (rc) return rc;
-    rc = make_pview(b_d, "lpg_gemm_packed B", &bv);
+    rc = make_operand(b_d, B, false, &bo);
     if (rc) return rc;
-    rc = make_pview(c_d, "lpg_gemm_packed C", &cv);
+    rc = check_common(c_d, "lpg_gemm_packed C");
     if (rc) return rc;
-    if (a_d->kind != LPG_PACKED_A) return fail(LPG_ELAYOUT, "lpg_gemm_packed: A must be LPG_PACKED_A");
-    if (b_d->kind != LPG_PACKED_B) return fail(LPG_ELAYOUT, "lpg_gemm_packed: B must be LPG_PACKED_B");
-    if (a_d->cols != b_d->rows)
+    const bool c_canon = is_canon(c_d->kind);
+    PView cv{};
+    CView ccv{};
+    rc = c_canon ? make_cview(c_d, "lpg_gemm_packed C", &ccv) : make_pview(c_d, "lpg_gemm_packed C", &cv);
+    if (rc) return rc;
+    const int c_dtype = c_d->dtype, c_batch = nbatch(c_d);
+    if (ao.K != bo.K)
         return fail(LPG_EINVAL, "lpg_gemm_packed: inner dimensions differ (A cols %lld, B rows %lld)",
                     (long long)a_d->cols, (long long)b_d->rows);
     if (c_d->rows != a_d->rows || c_d->cols != b_d->cols)
         return fail(LPG_EINVAL, "lpg_gemm_packed: C is %lldx%lld but A*B is %lldx%lld", (long long)c_d->rows,
                     (long long)c_d->cols, (long long)a_d->rows, (long long)b_d->cols);
-    if (av.dtype != bv.dtype) return fail(LPG_EUNSUPPORTED, "lpg_gemm_packed: A and B dtypes differ");
-    if (av.dtype == LPG_F32 && cv.dtype != LPG_F32)
+    if (ao.dtype != bo.dtype) return fail(LPG_EUNSUPPORTED, "lpg_gemm_packed: A and B dtypes differ");
+    if (ao.dtype == LPG_F32 && c_dtype != LPG_F32)
         return fail(LPG_EUNSUPPORTED, "lpg_gemm_packed: f32 inputs need an f32 output");
     if (epi < LPG_EPI_NONE || epi > LPG_EPI_GATE_SILU) return fail(LPG_EINVAL, "lpg_gemm_packed: bad epilogue op %d", epi);
     if (epi == LPG_EPI_GATE_SILU && !epi_arg) return fail(LPG_EINVAL, "lpg_gemm_packed: LPG_EPI_GATE_SILU needs epi_arg");
     if (beta != 0.0f && !C_in) return fail(LPG_EINVAL, "lpg_gemm_packed: beta != 0 needs C_in");
-    if (cv.bdiv != 1) return fail(LPG_EINVAL, "lpg_gemm_packed: C batch_div must be 1");
-    const int nb = cv.batch;
-    if ((nb + av.bdiv - 1) / av.bdiv > (av.batch + av.bdiv - 1) / av.bdiv && av.batch != 1)
+    if (bdiv(c_d) != 1) return fail(LPG_EINVAL, "lpg_gemm_packed: C batch_div must be 1");
+    const int nb = c_batch;
+    if ((nb + ao.bdiv - 1) / ao.bdiv > (ao.batch + ao.bdiv - 1) / ao.bdiv && ao.batch != 1)
         return fail(LPG_EINVAL, "lpg_gemm_packed: A has too few batch slots");
-    if ((nb + bv.bdiv - 1) / bv.bdiv > (bv.batch + bv.bdiv - 1) / bv.bdiv && bv.batch != 1)
+    if ((nb + bo.bdiv - 1) / bo.bdiv > (bo.batch + bo.bdiv - 1) / bo.bdiv && bo.batch != 1)
         return fail(LPG_EINVAL, "lpg_gemm_packed: B has too few batch slots");
-    rc = check_ptr16(A, "lpg_gemm_packed A");
-    if (rc) return rc;
-    rc = check_ptr16(B, "lpg_gemm_packed B");
-    if (rc) return rc;
-    rc = check_ptr16(C_out, "lpg_gemm_packed C_out");
-    if (rc) return rc;
-    if (C_in && (uintptr_t)C_in % 16) return fail(LPG_EALIGN, "lpg_gemm_packed: C_in not 16-byte aligned");
-    if (epi_arg && (uintptr_t)epi_arg % 16) return fail(LPG_EALIGN, "lpg_gemm_packed: epi_arg not 16-byte aligned");
+    if (!C_out) return fail(LPG_EINVAL, "lpg_gemm_packed C_out: NULL pointer");
+    const int c_align = c_canon ? elem_size(c_dtype) : 16;
+    if ((uintptr_t)C_out % c_align) return fail(LPG_EALIGN, "lpg_gemm_packed: C_out not aligned");
+    if (C_in && (uintptr_t)C_in % c_align) return fail(LPG_EALIGN, "lpg_gemm_packed: C_in not aligned");
+    if (epi_arg && (uintptr_t)epi_arg % c_align) return fail(LPG_EALIGN, "lpg_gemm_packed: epi_arg not aligned");
     if (C_out == A || C_out == B) return fail(LPG_EINVAL, "lpg_gemm_packed: C_out must not alias A or B");
     if (!launch) return LPG_OK;
 
-    // Which operand rides on lanes decides the role C is written in.
-    const bool c_is_left = c_d->kind == LPG_PACKED_A;  // out free = rows(M): L = A, R = B
-    const PView &L = c_is_left ? av : bv;
-    const PView &R = c_is_left ? bv : av;
+    // Which operand rides on lanes decides the role C is written in: lanes become the free
+    // dimension of a packed C, and the contiguous dimension of a canonical C.
+    const bool l_is_a = c_canon ? c_d->kind == LPG_COL_MAJOR : c_d->kind == LPG_PACKED_A;
+    const Operand &L = l_is_a ? ao : bo;
+    const Operand &R = l_is_a ? bo : ao;
     GemmArgs g;
-    g.L = (const char *)(c_is_left ? A : B) + L.origin;
-    g.R = (const char *)(c_is_left ? B : A) + R.origin;
-    g.Cin = (beta != 0.0f) ? (const char *)C_in + cv.origin : nullptr;
-    g.Epi = epi_arg ? (const char *)epi_arg + cv.origin : nullptr;
-    g.Out = (char *)C_out + cv.origin;
+    g.L = (const char *)(l_is_a ? A : B) + L.origin;
+    g.R = (const char *)(l_is_a ? B : A) + R.origin;
+    g.l_canon = L.canon;
+    g.r_canon = R.canon;
+    g.l_ld = L.ld_bytes;
+    g.r_ld = R.ld_bytes;
     g.l_kbs = L.kb_stride;
     g.r_kbs = R.kb_stride;
-    g.o_kbs = cv.kb_stride;
     g.l_slot = L.batch == 1 ? 0 : L.slot_step;
     g.r_slot = R.batch == 1 ? 0 : R.slot_step;
-    g.o_slot = cv.slot_step;
     g.l_div = L.bdiv;
     g.r_div = R.bdiv;
+    int64_t c_origin;
+    if (c_canon) {
+        const int es = elem_size(c_dtype);
+        c_origin = ccv.origin * es;
+        g.o_canon = 1;
+        g.o_kbs = 0;
+        g.o_slot = ccv.slot_step * es;
+        // lanes <-> L's free index: rows of C if L is A, columns if L is B
+        g.o_sf = (l_is_a ? ccv.row_stride : ccv.col_stride) * es;
+        g.o_sk = (l_is_a ? ccv.col_stride : ccv.row_stride) * es;
+        g.FRg_out = (int32_t)((R.F + 31) / 32);
+    } else {
+        c_origin = cv.origin;
+        g.o_canon = 0;
+        g.o_kbs = cv.kb_stride;
+        g.o_slot = cv.slot_step;
+        g.o_sf = g.o_sk = 0;
+        g.FRg_out = (int32_t)(round_up(R.F, kb_of(c_dtype)) / 32);
+    }
+    g.Cin = (beta != 0.0f) ? (const char *)C_in + c_origin : nullptr;
+    g.Epi = epi_arg ? (const char *)epi_arg + c_origin : nullptr;
+    g.Out = (char *)C_out + c_origin;
     g.FL = (int32_t)L.F;
     g.FR = (int32_t)R.F;
     g.FLg = (int32_t)((L.F + 31) / 32);
     g.FRg = (int32_t)((R.F + 31) / 32);
-    g.FRg_out = (int32_t)(round_up(R.F, kb_of(cv.dtype)) / 32);
-    g.nkb = (int32_t)((av.K + kb_of(av.dtype) - 1) / kb_of(av.dtype));
+    g.nkb = (int32_t)((ao.K + kb_of(ao.dtype) - 1) / kb_of(ao.dtype));
     g.tiles_l = g.tiles_r = 0;
     g.batch = nb;
     g.epi = epi;
@@ -277,7 +345,7 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     // LPG_FORCE_TILE=<index> pins the tile configuration (a tuning aid; unset = automatic)
     int cfg = -1;
     if (const char *f = getenv("LPG_FORCE_TILE")) cfg = atoi(f);
-    hipError_t e = launch_gemm(g, av.dtype, cv.dtype, cfg, st);
+    hipError_t e = launch_gemm(g, ao.dtype, c_dtype, cfg, st);
     if (e != hipSuccess) return fail(LPG_EHIP, "lpg_gemm_packed: %s", hipGetErrorString(e));
     return LPG_OK;
 }

@@ -66,8 +66,15 @@ struct GemmArgs {
     const char *Cin;     // may be null (beta == 0)
     const char *Epi;     // may be null
     char *Out;
-    int64_t l_kbs, r_kbs, o_kbs;     // bytes between K blocks
+    int64_t l_kbs, r_kbs, o_kbs;     // bytes between K blocks (packed operands)
     int64_t l_slot, r_slot, o_slot;  // bytes per slot
+    // Canonical (row/column-major) operands read or written directly, without a pack or
+    // unpack pass: the fused Initial / Ending kernels.  Inputs: fp32, contiguous along k;
+    // l_ld / r_ld = bytes between consecutive free indices.  Output: o_sf / o_sk = bytes per
+    // step of out's lane index (free) and register index (contraction).
+    int32_t l_canon, r_canon, o_canon;
+    int64_t l_ld, r_ld;
+    int64_t o_sf, o_sk;
     int32_t l_div, r_div;
     int32_t FL, FR;                  // logical extents of out: free dim, contraction dim
     int32_t FLg, FRg;                // 32-groups present in L and R

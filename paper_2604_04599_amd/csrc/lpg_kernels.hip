@@ -376,6 +376,30 @@ __device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc,
 #pragma unroll
         for (int e = 0; e < 16; ++e) v[e] *= p.alpha;
     }
+    if (p.o_canon) {
+        // Ending kernel: straight to row/column-major.  Lanes run along out's free index, so
+        // for each register the 32 lanes of a half wave write one contiguous run.
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+            if (fl >= p.FL || fr >= p.FR) continue;
+            const int64_t off = (int64_t)fl * p.o_sf + (int64_t)fr * p.o_sk;
+            float x = v[e];
+            if (use_c) {
+                if constexpr (OUT::ES == 4) x += p.beta * *(const float *)(Cb + off);
+                else x += p.beta * bf16_to_f32(*(const uint16_t *)(Cb + off));
+            }
+            float gte = 0.0f;
+            if (use_e) {
+                if constexpr (OUT::ES == 4) gte = *(const float *)(Eb + off);
+                else gte = bf16_to_f32(*(const uint16_t *)(Eb + off));
+            }
+            x = epi_apply(p.epi, x, gte);
+            if constexpr (OUT::ES == 4) *(float *)(Ob + off) = x;
+            else *(uint16_t *)(Ob + off) = (uint16_t)bf16_rne(x);
+        }
+        return;
+    }
     int64_t obase;  // byte offset of this tile's first fragment inside out
     if constexpr (OUT::ES == 4)
         obase = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
@@ -492,8 +516,9 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
         t.gr0 = tr * TRG;
         t.nlg = min(TLG, p.FLg - t.gl0);
         t.nrg = max(0, min(TRG, p.FRg - t.gr0));
-        t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (int64_t)t.gl0 * kBlockBytes;
-        t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (int64_t)t.gr0 * kBlockBytes;
+        // packed: first block of the tile; canonical: the operand's (slot's) first element
+        t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (p.l_canon ? 0 : (int64_t)t.gl0 * kBlockBytes);
+        t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (p.r_canon ? 0 : (int64_t)t.gr0 * kBlockBytes);
         return t;
     };
 
@@ -508,9 +533,22 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
         for (int i = 0; i < FPW; ++i) {
             const int fid = i * NW + wave;
             const int grp = fid / FS, c = fid % FS;
-            const char *base = (i < FPW_L) ? t.Lp + min(grp, t.nlg - 1) * kBlockBytes
-                                           : t.Rp + max(0, min(grp - TLG, t.nrg - 1)) * kBlockBytes;
-            src[i] = base + c * kFragBytes + lane * 16;
+            const bool is_l = i < FPW_L;
+            if (is_l ? p.l_canon : p.r_canon) {
+                // Initial kernel: gather the fragment straight from the canonical matrix.  Lane
+                // (fl, h) of fragment c needs k = KF*c + 4*h .. +3 of free index fl: 16
+                // contiguous bytes of a k-contiguous fp32 row, which the transfer drops at
+                // lane*16 of the stage, i.e. in fragment order.  Rows past the end are
+                // replaced by the last row (never used).
+                const int g0 = is_l ? t.gl0 + grp : t.gr0 + grp - TLG;
+                const int row = min(g0 * 32 + (lane & 31), (is_l ? p.FL : p.FR) - 1);
+                const char *base = is_l ? t.Lp + (int64_t)row * p.l_ld : t.Rp + (int64_t)row * p.r_ld;
+                src[i] = base + c * (IN::KF * IN::ES) + (lane >> 5) * 16;
+            } else {
+                const char *base = is_l ? t.Lp + min(grp, t.nlg - 1) * kBlockBytes
+                                        : t.Rp + max(0, min(grp - TLG, t.nrg - 1)) * kBlockBytes;
+                src[i] = base + c * kFragBytes + lane * 16;
+            }
         }
     };
     uint32_t c_tiles_left = my_tiles;  // tiles the copy cursor still has to start or finish
@@ -540,6 +578,8 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
             } else {                          // second half of the same K block
                 dl = dr = FS * kFragBytes;
             }
+            if (p.l_canon) dl = FS * IN::KF * IN::ES;  // canonical rows are contiguous along k
+            if (p.r_canon) dr = FS * IN::KF * IN::ES;
 #pragma unroll
             for (int i = 0; i < FPW; ++i) src[i] += (i < FPW_L) ? dl : dr;
         }

@@ -160,3 +160,25 @@ def test_chain_rejects_mismatched_geometry_on_device_buffers():
         api.lpg_chain(bad)
     assert e.value.code == api.LPG_ELAYOUT
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name,over,out", [
+    ("two_gemm", dict(n=160), "C2"), ("mlp", dict(m=160, d=96, h=224), "Y"),
+    ("attention", dict(heads=3, t=160, dh=64), "O"), ("deep_chain", dict(n=192, depth=5), "C"),
+    ("deep_chain", dict(n=160, depth=4), "C"),
+    ("decoder_layer", dict(t=192, hidden=256, n_q=4, n_kv=2, ffn=320), "Y"), ("mlp", dict(), "Y")])
+def test_fused_initial_and_ending_kernels_give_the_same_bits(name, over, out):
+    """The chain whose first GEMM reads the canonical input itself and whose last GEMM writes
+    the canonical output itself (no pack / unpack pass) equals the standard chain bit for bit."""
+    inp, shape = inputs.make(name, **over)
+    std = chains.build(name, inp, shape)
+    fus = chains.build(name, inp, shape, fused=True)
+    assert len(fus.stages) < len(std.stages)
+    std.run()
+    fus.run()
+    a, b = std.output(out), fus.output(out)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    # the control mode of a fused chain still agrees
+    fus.outputs[out].fill_(float("nan"))
+    fus.run(LPG_CHAIN_CANONICAL)
+    assert np.array_equal(fus.output(out).view(np.uint32), a.view(np.uint32))

@@ -226,3 +226,107 @@ def test_every_tile_configuration(cfg, monkeypatch):
     B = rng.integers(-2, 3, (64, 96)).astype(np.float32)
     got, _, _ = run_gemm(A, B, LPG_F32, LPG_F32, LPG_PACKED_A)
     assert np.array_equal(got, ref.gemm(A, B))
+
+
+# ---- fused boundary kernels: canonical operands read / written by the GEMM itself
+
+def _canon_dev(a, ld):
+    rows, cols = a.shape
+    buf = np.full((rows, ld), np.float32(777.0), dtype=np.float32)
+    buf[:, :cols] = a
+    return dev_bytes(buf), buf
+
+
+@pytest.mark.parametrize("m,n,k", [(64, 64, 64), (130, 70, 96), (300, 520, 160), (33, 257, 32)])
+@pytest.mark.parametrize("c_kind", [LPG_PACKED_A, LPG_PACKED_B])
+def test_initial_kernel_reads_canonical_operands(m, n, k, c_kind):
+    """A row-major and/or B column-major (both contiguous along k) fed straight to the GEMM:
+    same bits as packing first."""
+    rng = np.random.default_rng(m + n + k)
+    A = rng.uniform(-1, 1, (m, k)).astype(np.float32)
+    B = rng.uniform(-1, 1, (k, n)).astype(np.float32)
+    want_bits, raw_ref, cd = run_gemm(A, B, LPG_F32, LPG_F32, c_kind, alpha=1.25)
+    ta, _ = _canon_dev(A, k + 4)
+    tbt, _ = _canon_dev(np.ascontiguousarray(B.T), k + 8)                 # B column-major, ld = k + 8
+    a_can = desc(LPG_ROW_MAJOR, LPG_F32, m, k, ld=k + 4)
+    b_can = desc(api.LPG_COL_MAJOR, LPG_F32, k, n, ld=k + 8)
+    pa, pad = pack_dev(A, LPG_PACKED_A, LPG_F32)
+    pb, pbd = pack_dev(B, LPG_PACKED_B, LPG_F32)
+    for (xa, xad, xb, xbd) in ((ta, a_can, pb, pbd), (pa, pad, tbt, b_can), (ta, a_can, tbt, b_can)):
+        tc = dev_empty(api.lpg_packed_bytes(cd), fill=0xFF)
+        api.lpg_gemm_packed(1.25, xa, xad, xb, xbd, 0.0, None, tc, cd, 0, None, stream())
+        raw = host(tc, np.uint32)[:raw_ref.size]
+        assert np.array_equal(raw, raw_ref)
+    assert ref.rel_frobenius(want_bits, ref.gemm(A, B, alpha=1.25)) <= F32_TOL
+
+
+@pytest.mark.parametrize("m,n,k", [(64, 64, 64), (130, 70, 100), (300, 520, 33), (1, 1, 1)])
+@pytest.mark.parametrize("c_kind", [LPG_ROW_MAJOR, api.LPG_COL_MAJOR])
+@pytest.mark.parametrize("in_dt,out_dt", [(LPG_F32, LPG_F32), (LPG_BF16, LPG_F32), (LPG_BF16, LPG_BF16)])
+def test_ending_kernel_writes_canonical_c(m, n, k, c_kind, in_dt, out_dt):
+    """C written straight to row/column-major (with a leading dimension), beta*C_in read from
+    the same canonical layout; elements outside the logical extent are never touched."""
+    rng = np.random.default_rng(3 * m + n + k)
+    A = bf16_exact(rng.uniform(-1, 1, (m, k)))
+    B = bf16_exact(rng.uniform(-1, 1, (k, n)))
+    C = bf16_exact(rng.uniform(-1, 1, (m, n)))
+    rm = c_kind == LPG_ROW_MAJOR
+    ld = (n if rm else m) + 5
+    es = ES[out_dt]
+    def to_canon(x):
+        rows = x if rm else np.ascontiguousarray(x.T)
+        buf = np.full((rows.shape[0], ld), 3.0, dtype=np.float32)
+        buf[:, :rows.shape[1]] = rows
+        if out_dt == LPG_BF16:
+            return (buf.view(np.uint32) >> 16).astype(np.uint16)
+        return buf
+    cin = to_canon(C)
+    t_cin = dev_bytes(cin)
+    t_out = dev_bytes(to_canon(np.zeros((m, n), dtype=np.float32)))      # poison 3.0 everywhere outside
+    ta, ad = pack_dev(A, LPG_PACKED_A, in_dt)
+    tb, bd = pack_dev(B, LPG_PACKED_B, in_dt)
+    cd = desc(c_kind, out_dt, m, n, ld=ld)
+    api.lpg_gemm_packed(0.5, ta, ad, tb, bd, 2.0, t_cin, t_out, cd, 0, None, stream())
+    got_raw = host(t_out, NP_RAW[out_dt])[:cin.size].reshape(cin.shape)
+    got_f = got_raw.view(np.float32) if es == 4 else (got_raw.astype(np.uint32) << 16).view(np.float32)
+    inner = got_f[:, :(n if rm else m)]
+    got = (inner if rm else inner.T).astype(np.float64)
+    want = ref.gemm(A, B, alpha=0.5, beta=2.0, C=C)
+    assert ref.rel_frobenius(got, want) <= (BF16_TOL if out_dt == LPG_BF16 else 1e-5)
+    assert np.all(got_f[:, (n if rm else m):] == 3.0)                      # ld padding untouched
+    # identical bits to the packed result unpacked afterwards
+    pk_kind = LPG_PACKED_A if not rm else LPG_PACKED_B
+    got2, _, _ = run_gemm(A, B, in_dt, out_dt, pk_kind, alpha=0.5, beta=2.0, C=C)
+    assert np.array_equal(got, got2)
+
+
+def test_fused_boundaries_with_heads():
+    """Initial + Ending in one call, batched over heads: S_h = Q_h K_h^T with Q, K row-major
+    [heads, t, d] read directly and S written row-major."""
+    rng = np.random.default_rng(77)
+    nh, t, d = 3, 100, 64
+    Q = rng.standard_normal((nh, t, d)).astype(np.float32)
+    K = rng.standard_normal((nh, t, d)).astype(np.float32)
+    qd = desc(LPG_ROW_MAJOR, LPG_F32, t, d, batch=nh, batch_stride=t * d)
+    ktd = desc(api.LPG_COL_MAJOR, LPG_F32, d, t, batch=nh, batch_stride=t * d)      # K_h^T column-major = K_h row-major
+    sd = desc(LPG_ROW_MAJOR, LPG_F32, t, t, batch=nh, batch_stride=t * t)
+    ts = dev_empty(nh * t * t * 4, fill=0xFF)
+    api.lpg_gemm_packed(0.125, dev_bytes(Q), qd, dev_bytes(K), ktd, 0.0, None, ts, sd, 0, None, stream())
+    S = host(ts, np.float32, (nh, t, t)).astype(np.float64)
+    for h in range(nh):
+        assert ref.rel_frobenius(S[h], ref.gemm(Q[h], K[h].T.copy(), alpha=0.125)) <= F32_TOL
+
+
+def test_canonical_operand_restrictions_are_reported():
+    fake = 1 << 20
+    pb = desc(LPG_PACKED_B, LPG_F32, 64, 64)
+    pc = desc(LPG_PACKED_A, LPG_F32, 64, 64)
+    def err(a_d, b_d=pb, c_d=pc):
+        with pytest.raises(api.LpgError) as e:
+            api.lpg_gemm_packed(1.0, fake, a_d, 2 * fake, b_d, 0.0, None, 3 * fake, c_d)
+        return e.value.code
+    assert err(desc(api.LPG_COL_MAJOR, LPG_F32, 64, 64)) == api.LPG_ELAYOUT            # A must be k-contiguous
+    assert err(desc(LPG_ROW_MAJOR, LPG_BF16, 64, 64), desc(LPG_PACKED_B, LPG_BF16, 64, 64),
+               desc(LPG_PACKED_A, LPG_BF16, 64, 64)) == api.LPG_EUNSUPPORTED             # bf16 must be packed
+    assert err(desc(LPG_ROW_MAJOR, LPG_F32, 64, 40), desc(LPG_PACKED_B, LPG_F32, 40, 64)) == api.LPG_EUNSUPPORTED
+    assert err(desc(LPG_ROW_MAJOR, LPG_F32, 64, 64, ld=66)) == api.LPG_EALIGN
