@@ -296,12 +296,15 @@ def build_decoder_layer(inp, shape, fused=False):
     ch.add(api.stage_gemm(1.0, ps, sd, pv, v_view, 0.0, None, po, o_view))
     ch.add(api.stage_gemm(1.0, po, od_full, wt["Wo"], wd["Wo"], 0.0, None, pattn, ad))
     ch.add(api.stage_gemm(1.0, pattn, ad, wt["Wg"], wd["Wg"], 0.0, None, pg, gd))
-    ch.add(api.stage_gemm(1.0, pattn, ad, wt["Wu"], wd["Wu"], 0.0, None, pu, gd))
-    ch.add(api.stage_elementwise(LPG_EW_SILU_MUL, pg, pu, 0.0, pact, gd))
     if fused:
-        # only the exit can be fused here: X is converted fp32 -> bf16 by its pack
+        # SiLU(gate) * up applied in the up projection's epilogue (no U buffer, no elementwise
+        # pass), and the exit written row-major by the last GEMM.  The entry stays a pack: X is
+        # converted fp32 -> bf16 there.
+        ch.add(api.stage_gemm(1.0, pattn, ad, wt["Wu"], wd["Wu"], 0.0, None, pact, gd, api.LPG_EPI_GATE_SILU, pg))
         ch.add(api.stage_gemm(1.0, pact, gd, wt["Wd"], wd["Wd"], 0.0, None, out, desc(LPG_ROW_MAJOR, LPG_F32, t, hid)))
         return ch
+    ch.add(api.stage_gemm(1.0, pattn, ad, wt["Wu"], wd["Wu"], 0.0, None, pu, gd))
+    ch.add(api.stage_elementwise(LPG_EW_SILU_MUL, pg, pu, 0.0, pact, gd))
     ch.add(api.stage_gemm(1.0, pact, gd, wt["Wd"], wd["Wd"], 0.0, None, py, yd))
     ch.add(api.stage_unpack(py, yd, out, desc(LPG_ROW_MAJOR, LPG_F32, t, hid)))
     return ch

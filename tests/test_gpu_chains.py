@@ -176,9 +176,16 @@ def test_fused_initial_and_ending_kernels_give_the_same_bits(name, over, out):
     assert len(fus.stages) < len(std.stages)
     std.run()
     fus.run()
-    a, b = std.output(out), fus.output(out)
-    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
-    # the control mode of a fused chain still agrees
+    a, b = std.output(out).copy(), fus.output(out).copy()
+    if name == "decoder_layer":
+        # its fused form also applies SiLU(gate)*up in the up projection's epilogue, which skips
+        # one bf16 rounding (of U): close to, not identical with, the standard chain
+        assert ref.rel_frobenius(b, a) <= 5e-3
+        want = workloads.decoder_layer(inp, shape["n_q"], shape["n_kv"])["Y"]
+        assert ref.rel_frobenius(b, want) <= BF16_TOL
+    else:
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    # the control mode of a fused chain still agrees with its propagated mode
     fus.outputs[out].fill_(float("nan"))
     fus.run(LPG_CHAIN_CANONICAL)
-    assert np.array_equal(fus.output(out).view(np.uint32), a.view(np.uint32))
+    assert np.array_equal(fus.output(out).view(np.uint32), b.view(np.uint32))
