@@ -21,6 +21,11 @@ import time
 import numpy as np
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6}     # dense MFMA, MI355X (256 CU x 2.4 GHz)
+# HBM bytes per fp32 GEMM launch of the headline chain, from profiles/hbm_traffic_mlp_chain.txt:
+# FETCH_SIZE (x2.0 calibration) 80.7 and 168.4 MiB, WRITE_SIZE (x1.0) 32 and 8 MiB for the two
+# launches of a step -> mean 144.5 MiB; the algorithmic bytes are 56 and 64 MiB.
+GEMM_TRAFFIC_BYTES = 144.5 * 2 ** 20
+GEMM_ALGORITHMIC_BYTES = 60.0 * 2 ** 20
 HEADLINE = "mlp"
 
 
@@ -179,7 +184,9 @@ def main():
     achieved = gemm_flops / t_gemm / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_kernel<F32,F32>", "achieved": round(achieved, 2),
                 "peak": PEAK_TFLOPS["f32"], "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS["f32"], 4),
-                "avg_launch_us": round(t_gemm * 1e6, 2), "flops_per_launch": gemm_flops, "traffic": None}
+                "avg_launch_us": round(t_gemm * 1e6, 2), "flops_per_launch": gemm_flops,
+                "traffic": GEMM_TRAFFIC_BYTES, "algorithmic_bytes": GEMM_ALGORITHMIC_BYTES,
+                "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)"}
 
     if args.workloads == "all":
         names = [w for w in inputs.WORKLOADS if w != HEADLINE]
