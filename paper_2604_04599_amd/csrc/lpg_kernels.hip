@@ -312,12 +312,8 @@ hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st)
 // 16 bytes per lane, global -> LDS at lds_addr + lane*16 (lds_addr wave-uniform).  Written
 // as inline asm so that the compiler does not serialise later LDS reads of the OTHER stage
 // behind this transfer; completion is awaited explicitly (vmcnt) before the stage is read.
-#ifndef LPG_DBG
-#define LPG_DBG 0  // timing experiments only: 1 = no copies, 2 = no multiplies, 4 = no stores
-#endif
 __device__ __forceinline__ void lds_dma16(const void *g, uint32_t lds_addr)
 {
-    if (LPG_DBG & 1) return;
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
 }
 
@@ -634,7 +630,6 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
             const char *sL = sLw + st * STAGE;
             const char *sR = sRw + st * STAGE;
             const int stn = (st + 1 == NS) ? 0 : st + 1;
-            if (LPG_DBG & 2) { st = stn; --pending; if (c_live) copy_step(); continue; }
             if constexpr (!XPF) {
 #pragma unroll
                 for (int a = 0; a < WTL; ++a) lf[0][a] = *(const uint4 *)(sL + a * (FS * kFragBytes));
@@ -679,7 +674,6 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
         }
 
         // ---- epilogue
-        if (LPG_DBG & 4) continue;
         const TileInfo cur = decode(vb);
         const int64_t oslot = (int64_t)cur.b * p.o_slot;
 #pragma unroll
