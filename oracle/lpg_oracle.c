@@ -14,6 +14,8 @@
  *   orc_bf16_bits   fp32 bit pattern -> bf16 bit pattern, round-nearest-even
  *   orc_silu_mul    g*sigmoid(g)*u in fp64 (the activation F_i of Eq. 2 used by
  *                   the Llama-shaped workload)
+ *   orc_softmax_rows  scale, optional causal mask, row softmax (Alg. 2, the steps
+ *                   between the two attention GEMMs)
  *   orc_pack / orc_unpack            canonical <-> packed layout, by walking the
  *                   layout's nested dimensions outermost to innermost (the GPU
  *                   re-design of the dimension order of Eq. 3)
@@ -132,6 +134,34 @@ void orc_round_bf16(double *x, int64_t n)
 void orc_silu_mul(const double *g, const double *u, double *out, int64_t n)
 {
     for (int64_t i = 0; i < n; ++i) out[i] = g[i] / (1.0 + exp(-g[i])) * u[i];
+}
+
+/* Row softmax of scale*x (Alg. 2: scale, optional mask, softmax), fp64, row-major.
+ * causal != 0 applies the usual attention mask: row i keeps columns j <= i + shift
+ * (shift = cols - rows aligns the last row with the last column); masked positions get
+ * probability 0.  Each row: subtract the maximum of the kept entries, exponentiate, divide
+ * by the sum. */
+void orc_softmax_rows(const double *x, double *out, int64_t rows, int64_t cols, double scale, int causal)
+{
+    const int64_t shift = cols - rows;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        int64_t last = causal ? i + shift : cols - 1;
+        if (last > cols - 1) last = cols - 1;
+        const double *xr = x + i * cols;
+        double *o = out + i * cols;
+        for (int64_t j = 0; j < cols; ++j) o[j] = 0.0;
+        if (last < 0) continue;
+        double m = scale * xr[0];
+        for (int64_t j = 1; j <= last; ++j)
+            if (scale * xr[j] > m) m = scale * xr[j];
+        double sum = 0.0;
+        for (int64_t j = 0; j <= last; ++j) {
+            o[j] = exp(scale * xr[j] - m);
+            sum += o[j];
+        }
+        for (int64_t j = 0; j <= last; ++j) o[j] = o[j] / sum;
+    }
 }
 
 /* ----------------------------------------------------------- packed layout */

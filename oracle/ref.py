@@ -39,6 +39,7 @@ def lib():
         L.orc_pack.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64]
         L.orc_unpack.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64]
         L.orc_threads.restype = ctypes.c_int
+        L.orc_softmax_rows.argtypes = [vp, vp, i64, i64, dbl, i32]
         _lib = L
     return _lib
 
@@ -124,6 +125,14 @@ def silu_mul(g, u):
     u = _f64(u)
     out = np.empty_like(g)
     lib().orc_silu_mul(g.ctypes.data, u.ctypes.data, out.ctypes.data, g.size)
+    return out
+
+
+def softmax_rows(x, scale=1.0, causal=False):
+    """softmax over each row of scale*x (2-D, fp64); causal keeps columns j <= i + cols - rows."""
+    x = _f64(x)
+    out = np.empty_like(x)
+    lib().orc_softmax_rows(x.ctypes.data, out.ctypes.data, x.shape[0], x.shape[1], float(scale), int(bool(causal)))
     return out
 
 

@@ -49,16 +49,21 @@ def mlp(inp, store=None, rows=None):
     return {"H": h, "Y": y}
 
 
-def attention(inp, store=None, rows=None, heads=None, keep_s=False):
-    """Per head: S = (1/sqrt(d)) * Q_h * K_h^T, O = S * V_h.  No softmax, no mask.
-    Inputs Q, K, V have shape [heads, T, d]."""
+def attention(inp, store=None, rows=None, heads=None, keep_s=False, softmax=False, causal=False):
+    """Per head: S = (1/sqrt(d)) * Q_h * K_h^T, O = S * V_h.  With softmax=True the scale moves
+    into the softmax, S = softmax((1/sqrt(d)) * Q_h K_h^T [causally masked]) (Alg. 2), and
+    `rows` must then be None (a causal mask is positional).  Inputs Q, K, V: [heads, T, d]."""
     q, k, v = (np.asarray(inp[n], dtype=np.float64) for n in ("Q", "K", "V"))
     nh, _, d = q.shape
     alpha = 1.0 / np.sqrt(d)
     hs = range(nh) if heads is None else heads
     out = {"O": {}, "S": {}}
     for h in hs:
-        s = _st(ref.gemm(_rows(q[h], rows), k[h].T, alpha=alpha), store)
+        if softmax:
+            raw = _st(ref.gemm(q[h], k[h].T), store)
+            s = _st(ref.softmax_rows(raw, scale=alpha, causal=causal), store)
+        else:
+            s = _st(ref.gemm(_rows(q[h], rows), k[h].T, alpha=alpha), store)
         out["O"][h] = ref.gemm(s, v[h])
         if keep_s:
             out["S"][h] = s
