@@ -178,28 +178,50 @@ int lpg_gemm_packed(float alpha, const void *A, const lpg_desc *a_d, const void 
 int lpg_elementwise_packed(int op, const void *x0, const void *x1, float s, void *out,
                            const lpg_desc *d, void *stream);
 
+/*
+ * lpg_softmax_packed - the steps between the two attention GEMMs (Alg. 2: scale,
+ * optional mask, softmax), done on the packed layout so that the scores never leave
+ * it (section IV-A: operations that are not layout-oblivious are re-written for the
+ * propagated layout instead of unpacking around them):
+ *     out[i][j] = exp(scale*x[i][j] - m_i) / sum_j' exp(scale*x[i][j'] - m_i),
+ * m_i = max_j scale*x[i][j], over the logical columns of every row of every slot.
+ * causal != 0 keeps only columns j <= i + (cols - rows) of row i; masked positions,
+ * and rows with no kept column, get 0.
+ *   d->kind == LPG_PACKED_A (the row index is the free index, the softmax runs along
+ *   the contraction index of the GEMM that will consume the result as its left
+ *   operand; views as in lpg_desc, batch_div must be 1) or LPG_ROW_MAJOR (any ld /
+ *   view; what the canonical control chain calls).  Other kinds: LPG_EUNSUPPORTED.
+ *   x and out share the descriptor; in place (out == x) is allowed, partial overlap
+ *   is not.  Math in fp32; bf16 results are rounded to nearest even.  Packed kinds:
+ *   every block the view touches is written, padding as zeros.
+ */
+int lpg_softmax_packed(const void *x, void *out, const lpg_desc *d, float scale, int causal,
+                       void *stream);
+
 /* One stage of a chain. */
 typedef enum {
     LPG_STAGE_PACK = 0,
     LPG_STAGE_GEMM = 1,
     LPG_STAGE_ELEMENTWISE = 2,
-    LPG_STAGE_UNPACK = 3
+    LPG_STAGE_UNPACK = 3,
+    LPG_STAGE_SOFTMAX = 4
 } lpg_stage_type;
 
 typedef struct lpg_stage {
     int32_t type;       /* lpg_stage_type                                               */
-    int32_t op;         /* GEMM: lpg_epilogue_op; ELEMENTWISE: lpg_ew_op                */
+    int32_t op;         /* GEMM: lpg_epilogue_op; ELEMENTWISE: lpg_ew_op; SOFTMAX: causal */
     float alpha, beta;  /* GEMM                                                         */
-    float scalar;       /* ELEMENTWISE: s                                               */
+    float scalar;       /* ELEMENTWISE: s; SOFTMAX: scale                               */
     int32_t reserved;
-    const void *in0;    /* PACK/UNPACK: src; GEMM: A; ELEMENTWISE: x0                   */
+    const void *in0;    /* PACK/UNPACK: src; GEMM: A; ELEMENTWISE: x0; SOFTMAX: x       */
     const void *in1;    /* GEMM: B; ELEMENTWISE: x1                                     */
     const void *in2;    /* GEMM: C_in (or NULL)                                         */
     const void *epi_arg;/* GEMM: epilogue argument (or NULL)                            */
     void *out;
     lpg_desc in0_d;     /* descriptor of in0                                            */
     lpg_desc in1_d;     /* GEMM: descriptor of B                                        */
-    lpg_desc out_d;     /* descriptor of out (and of in2, epi_arg, ELEMENTWISE inputs)  */
+    lpg_desc out_d;     /* descriptor of out (and of in2, epi_arg, ELEMENTWISE / SOFTMAX
+                           inputs)                                                       */
 } lpg_stage;
 
 typedef enum {

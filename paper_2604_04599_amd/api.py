@@ -17,7 +17,7 @@ LPG_F32, LPG_BF16 = 0, 1
 LPG_ROW_MAJOR, LPG_COL_MAJOR, LPG_PACKED_A, LPG_PACKED_B = 0, 1, 2, 3
 LPG_EW_SCALE, LPG_EW_ADD, LPG_EW_SILU_MUL = 0, 1, 2
 LPG_EPI_NONE, LPG_EPI_SILU, LPG_EPI_GATE_SILU = 0, 1, 2
-LPG_STAGE_PACK, LPG_STAGE_GEMM, LPG_STAGE_ELEMENTWISE, LPG_STAGE_UNPACK = 0, 1, 2, 3
+LPG_STAGE_PACK, LPG_STAGE_GEMM, LPG_STAGE_ELEMENTWISE, LPG_STAGE_UNPACK, LPG_STAGE_SOFTMAX = 0, 1, 2, 3, 4
 LPG_CHAIN_PROPAGATED, LPG_CHAIN_CANONICAL = 0, 1
 
 ELEM_SIZE = {LPG_F32: 4, LPG_BF16: 2}
@@ -82,6 +82,8 @@ def lib():
         L.lpg_gemm_packed.restype = ctypes.c_int
         L.lpg_elementwise_packed.argtypes = [ctypes.c_int, vp, vp, ctypes.c_float, vp, dp, vp]
         L.lpg_elementwise_packed.restype = ctypes.c_int
+        L.lpg_softmax_packed.argtypes = [vp, vp, dp, ctypes.c_float, ctypes.c_int, vp]
+        L.lpg_softmax_packed.restype = ctypes.c_int
         L.lpg_chain_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.c_int]
         L.lpg_chain_workspace_bytes.restype = ctypes.c_size_t
         L.lpg_chain.argtypes = [sp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp]
@@ -93,7 +95,7 @@ def lib():
 
 
 EXPORTS = ("lpg_packed_bytes", "lpg_layout_offset", "lpg_pack", "lpg_unpack", "lpg_gemm_packed",
-           "lpg_elementwise_packed", "lpg_chain_workspace_bytes", "lpg_chain", "lpg_last_error",
+           "lpg_elementwise_packed", "lpg_softmax_packed", "lpg_chain_workspace_bytes", "lpg_chain", "lpg_last_error",
            "lpg_version")
 
 
@@ -160,6 +162,10 @@ def lpg_elementwise_packed(op, x0, x1, s, out, d, stream=None):
     return _check(lib().lpg_elementwise_packed(op, _ptr(x0), _ptr(x1), s, _ptr(out), ctypes.byref(d), stream))
 
 
+def lpg_softmax_packed(x, out, d, scale=1.0, causal=False, stream=None):
+    return _check(lib().lpg_softmax_packed(_ptr(x), _ptr(out), ctypes.byref(d), scale, int(bool(causal)), stream))
+
+
 def stage_array(stages):
     arr = (lpg_stage * len(stages))()
     for i, s in enumerate(stages):
@@ -206,4 +212,11 @@ def stage_elementwise(op, x0, x1, scalar, out, d):
     s = lpg_stage()
     s.type, s.op, s.scalar = LPG_STAGE_ELEMENTWISE, op, scalar
     s.in0, s.in1, s.out, s.out_d = _ptr(x0), _ptr(x1), _ptr(out), d
+    return s
+
+
+def stage_softmax(x, out, d, scale=1.0, causal=False):
+    s = lpg_stage()
+    s.type, s.op, s.scalar = LPG_STAGE_SOFTMAX, int(bool(causal)), scale
+    s.in0, s.out, s.out_d = _ptr(x), _ptr(out), d
     return s

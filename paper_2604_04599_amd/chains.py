@@ -183,8 +183,13 @@ def build_mlp(inp, shape, fused=False):
     return ch
 
 
-def build_attention(inp, shape, fused=False):
+def build_attention(inp, shape, fused=False, softmax=False, causal=False):
+    """softmax=False: O = (Q K^T / sqrt(dh)) V, the two chained GEMMs alone.  softmax=True: the
+    scale moves into a softmax stage (optionally causally masked) that runs in place on the
+    packed scores between the two GEMMs."""
     nh, t, dh = shape["heads"], shape["t"], shape["dh"]
+    scale = 1.0 / float(np.sqrt(dh))
+    alpha = 1.0 if softmax else scale
     ch = Chain("attention", shape, nh * 2 * 2 * t * t * dh)
     q = ch.inputs["Q"] = device_array(inp["Q"])
     k = ch.inputs["K"] = device_array(inp["K"])
@@ -205,13 +210,17 @@ def build_attention(inp, shape, fused=False):
         # Q_h and K_h^T are contiguous along the contraction index as they stand; V_h (a right
         # operand stored row-major) is not and is still packed
         ch.add(api.stage_pack(v, rm, pv, vd))
-        ch.add(api.stage_gemm(1.0 / float(np.sqrt(dh)), q, rm, k, ktd_src, 0.0, None, ps, sd))
+        ch.add(api.stage_gemm(alpha, q, rm, k, ktd_src, 0.0, None, ps, sd))
+        if softmax:
+            ch.add(api.stage_softmax(ps, ps, sd, scale, causal))
         ch.add(api.stage_gemm(1.0, ps, sd, pv, vd, 0.0, None, out, rm))
         return ch
     ch.add(api.stage_pack(q, rm, pq, qd))
     ch.add(api.stage_pack(k, ktd_src, pk, ktd))
     ch.add(api.stage_pack(v, rm, pv, vd))
-    ch.add(api.stage_gemm(1.0 / float(np.sqrt(dh)), pq, qd, pk, ktd, 0.0, None, ps, sd))
+    ch.add(api.stage_gemm(alpha, pq, qd, pk, ktd, 0.0, None, ps, sd))
+    if softmax:
+        ch.add(api.stage_softmax(ps, ps, sd, scale, causal))
     ch.add(api.stage_gemm(1.0, ps, sd, pv, vd, 0.0, None, po, od))
     ch.add(api.stage_unpack(po, od, out, rm))
     return ch
@@ -314,5 +323,5 @@ BUILDERS = {"two_gemm": build_two_gemm, "mlp": build_mlp, "attention": build_att
             "deep_chain": build_deep_chain, "decoder_layer": build_decoder_layer}
 
 
-def build(name, inp, shape, fused=False):
-    return BUILDERS[name](inp, shape, fused=fused)
+def build(name, inp, shape, fused=False, **options):
+    return BUILDERS[name](inp, shape, fused=fused, **options)

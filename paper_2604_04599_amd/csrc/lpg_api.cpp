@@ -384,6 +384,54 @@ static int do_elementwise(int op, const void *x0, const void *x1, float s, void 
     return LPG_OK;
 }
 
+// ---------------------------------------------------------------------------- softmax
+
+static int do_softmax(const void *x, void *out, const lpg_desc *d, float scale, int causal, hipStream_t st,
+                      bool launch)
+{
+    int rc = check_common(d, "lpg_softmax_packed");
+    if (rc) return rc;
+    if (d->kind != LPG_PACKED_A && d->kind != LPG_ROW_MAJOR)
+        return fail(LPG_EUNSUPPORTED, "lpg_softmax_packed: kind %d (rows must be the free index: PACKED_A, or ROW_MAJOR)", d->kind);
+    if (bdiv(d) != 1) return fail(LPG_EUNSUPPORTED, "lpg_softmax_packed: batch_div must be 1");
+    if (!x || !out) return fail(LPG_EINVAL, "lpg_softmax_packed: NULL pointer");
+    SoftmaxArgs a{};
+    const bool packed = d->kind == LPG_PACKED_A;
+    if (packed) {
+        PView v;
+        rc = make_pview(d, "lpg_softmax_packed", &v);
+        if (rc) return rc;
+        if ((uintptr_t)x % 16 || (uintptr_t)out % 16)
+            return fail(LPG_EALIGN, "lpg_softmax_packed: packed buffers must be 16-byte aligned");
+        a.x = (const char *)x + v.origin;
+        a.out = (char *)out + v.origin;
+        a.kbs = v.kb_stride;
+        a.slot = v.slot_step;
+        a.ngroups = (int32_t)((v.F + 31) / 32);
+        a.nkb = (int32_t)((v.K + kb_of(v.dtype) - 1) / kb_of(v.dtype));
+        if ((int64_t)v.batch * a.ngroups * 4 > 0x7fffffff) return fail(LPG_EUNSUPPORTED, "lpg_softmax_packed: too many row groups");
+    } else {
+        CView v;
+        rc = make_cview(d, "lpg_softmax_packed", &v);
+        if (rc) return rc;
+        if ((uintptr_t)x % v.es || (uintptr_t)out % v.es) return fail(LPG_EALIGN, "lpg_softmax_packed: misaligned buffer");
+        a.x = (const char *)x + v.origin * v.es;
+        a.out = (char *)out + v.origin * v.es;
+        a.row_stride = v.row_stride * v.es;
+        a.slot = v.slot_step * v.es;
+        if ((int64_t)v.batch * d->rows > 0x7fffffff) return fail(LPG_EUNSUPPORTED, "lpg_softmax_packed: too many rows");
+    }
+    a.rows = (int32_t)d->rows;
+    a.cols = (int32_t)d->cols;
+    a.batch = nbatch(d);
+    a.causal = causal != 0;
+    a.scale_log2e = (float)((double)scale * 1.4426950408889634);
+    if (!launch) return LPG_OK;
+    hipError_t e = launch_softmax(a, d->dtype, packed, st);
+    if (e != hipSuccess) return fail(LPG_EHIP, "lpg_softmax_packed: %s", hipGetErrorString(e));
+    return LPG_OK;
+}
+
 // ------------------------------------------------------------------------------ chain
 
 // Packed geometry two descriptors must share to address the same bytes the same way.
@@ -442,7 +490,7 @@ static bool later_reads(const lpg_stage *st, int n, int from, const void *buf, b
                            (s.type == LPG_STAGE_ELEMENTWISE && s.in1 == buf);
         if (reads) {
             any = true;
-            if (s.type == LPG_STAGE_GEMM || s.type == LPG_STAGE_ELEMENTWISE) *by_compute = true;
+            if (s.type == LPG_STAGE_GEMM || s.type == LPG_STAGE_ELEMENTWISE || s.type == LPG_STAGE_SOFTMAX) *by_compute = true;
         }
         if (s.out == buf) break;  // overwritten from here on
     }
@@ -469,6 +517,8 @@ static int validate_stage(const lpg_stage &s, int i)
                            s.epi_arg, nullptr, false);
         case LPG_STAGE_ELEMENTWISE:
             return do_elementwise(s.op, s.in0, s.in1, s.scalar, s.out, &s.out_d, nullptr, false);
+        case LPG_STAGE_SOFTMAX:
+            return do_softmax(s.in0, s.out, &s.out_d, s.scalar, s.op, nullptr, false);
         default:
             return fail(LPG_EINVAL, "lpg_chain: stage %d has unknown type %d", i, s.type);
     }
@@ -490,6 +540,8 @@ static int check_links(const lpg_stage *st, int n)
         } else if (s.type == LPG_STAGE_ELEMENTWISE) {
             ins[ni++] = {s.in0, &s.out_d};
             if (s.in1) ins[ni++] = {s.in1, &s.out_d};
+        } else if (s.type == LPG_STAGE_SOFTMAX) {
+            ins[ni++] = {s.in0, &s.out_d};
         } else if (s.type == LPG_STAGE_UNPACK) {
             ins[ni++] = {s.in0, &s.in0_d};
         }
@@ -522,6 +574,7 @@ static int run_stage(const lpg_stage &s, hipStream_t hs)
         case LPG_STAGE_GEMM:
             return do_gemm(s.alpha, s.in0, &s.in0_d, s.in1, &s.in1_d, s.beta, s.in2, s.out, &s.out_d, s.op, s.epi_arg,
                            hs, true);
+        case LPG_STAGE_SOFTMAX: return do_softmax(s.in0, s.out, &s.out_d, s.scalar, s.op, hs, true);
         default: return do_elementwise(s.op, s.in0, s.in1, s.scalar, s.out, &s.out_d, hs, true);
     }
 }
@@ -545,6 +598,11 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
     // descriptors under which stages wrote a buffer since it was last re-packed
     struct Wrote { const void *p; lpg_desc d; bool pending; };
     std::vector<Wrote> wrote;
+    auto note_write = [&](const void *p, const lpg_desc &d) {
+        for (auto &w : wrote)
+            if (w.p == p && w.pending && !memcmp(&w.d, &d, sizeof(d))) return;  // already due for the same re-pack
+        wrote.push_back({p, d, true});
+    };
     auto get_slot = [&](const void *p, const lpg_desc *pd) -> Slot * {
         Slot *s = find(p);
         const size_t bytes = twin_bytes(pd);
@@ -574,32 +632,38 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
 
     for (int i = 0; i < n; ++i) {
         const lpg_stage &s = st[i];
-        if (s.type == LPG_STAGE_ELEMENTWISE) {
-            Slot *s0 = find(s.in0), *s1 = s.in1 ? find(s.in1) : nullptr;
+        if (s.type == LPG_STAGE_ELEMENTWISE || s.type == LPG_STAGE_SOFTMAX) {
+            const bool sm = s.type == LPG_STAGE_SOFTMAX;
+            Slot *s0 = find(s.in0), *s1 = (!sm && s.in1) ? find(s.in1) : nullptr;
             const size_t tb = is_packed(s.out_d.kind) ? twin_bytes(&s.out_d) : 0;
             const bool canon_in = s0 && s0->canonical_live && s0->bytes == tb &&
-                                  (!s.in1 || (s1 && s1->canonical_live && s1->bytes == tb));
+                                  (sm || !s.in1 || (s1 && s1->canonical_live && s1->bytes == tb));
             bool by_compute = false;
             later_reads(st, n, i + 1, s.out, &by_compute);
             if (canon_in && is_packed(s.out_d.kind)) {
                 // run on the row-major copies; result stays row-major in the workspace
                 lpg_desc c = canonical_twin(&s.out_d);
-                c.ld = 0;
                 Slot *so = get_slot(s.out, &s.out_d);
                 // get_slot may have moved the vector: look the inputs up again
                 s0 = find(s.in0);
-                s1 = s.in1 ? find(s.in1) : nullptr;
+                s1 = (!sm && s.in1) ? find(s.in1) : nullptr;
                 if (!dry) {
-                    int rc = do_elementwise(s.op, s0->canon, s1 ? s1->canon : nullptr, s.scalar, so->canon, &c, hs, true);
+                    int rc;
+                    if (sm) {
+                        rc = do_softmax(s0->canon, so->canon, &c, s.scalar, s.op, hs, true);
+                    } else {
+                        c.ld = 0;
+                        rc = do_elementwise(s.op, s0->canon, s1 ? s1->canon : nullptr, s.scalar, so->canon, &c, hs, true);
+                    }
                     if (rc) return rc;
                 }
                 so->canonical_live = true;
-                wrote.push_back({s.out, s.out_d, true});
+                note_write(s.out, s.out_d);
                 continue;
             }
             int rc = repack(s.in0);
             if (rc) return rc;
-            if (s.in1) { rc = repack(s.in1); if (rc) return rc; }
+            if (!sm && s.in1) { rc = repack(s.in1); if (rc) return rc; }
         } else if (s.type == LPG_STAGE_GEMM) {
             int rc = repack(s.in0);
             if (rc) return rc;
@@ -615,11 +679,12 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
             int rc = run_stage(s, hs);
             if (rc) return rc;
         }
-        if ((s.type == LPG_STAGE_GEMM || s.type == LPG_STAGE_ELEMENTWISE) && is_packed(s.out_d.kind)) {
+        if ((s.type == LPG_STAGE_GEMM || s.type == LPG_STAGE_ELEMENTWISE || s.type == LPG_STAGE_SOFTMAX) &&
+            is_packed(s.out_d.kind)) {
             bool by_compute = false;
             later_reads(st, n, i + 1, s.out, &by_compute);
             if (by_compute) {
-                wrote.push_back({s.out, s.out_d, true});
+                note_write(s.out, s.out_d);
                 Slot *so = get_slot(s.out, &s.out_d);
                 if (!dry) {
                     lpg_desc c = canonical_twin(&s.out_d);
@@ -697,6 +762,11 @@ int lpg_elementwise_packed(int op, const void *x0, const void *x1, float s, void
                            void *stream)
 {
     return do_elementwise(op, x0, x1, s, out, d, (hipStream_t)stream, true);
+}
+
+int lpg_softmax_packed(const void *x, void *out, const lpg_desc *d, float scale, int causal, void *stream)
+{
+    return do_softmax(x, out, d, scale, causal, (hipStream_t)stream, true);
 }
 
 size_t lpg_chain_workspace_bytes(const lpg_stage *stages, int n, int mode)

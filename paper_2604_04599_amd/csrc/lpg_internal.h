@@ -93,6 +93,20 @@ struct EwArgs {
     float s;
 };
 
+struct SoftmaxArgs {
+    const char *x;       // buffer + origin (bytes applied)
+    char *out;
+    int64_t kbs;         // packed: bytes between K blocks
+    int64_t row_stride;  // canonical: bytes between rows
+    int64_t slot;        // bytes per slot
+    int32_t rows, cols;  // logical extents (packed: free, contraction)
+    int32_t ngroups;     // packed: ceil(rows/32)
+    int32_t nkb;         // packed: ceil(cols/KB)
+    int32_t batch;
+    int32_t causal;
+    float scale_log2e;   // scale * log2(e)
+};
+
 // Launchers (lpg_kernels.hip).  Return hipError_t of the launch.
 hipError_t launch_pack(const PackArgs &a, int src_dtype, int dst_dtype, hipStream_t st);
 hipError_t launch_unpack(const PackArgs &a, int src_dtype, int dst_dtype, hipStream_t st);
@@ -100,5 +114,6 @@ hipError_t launch_unpack(const PackArgs &a, int src_dtype, int dst_dtype, hipStr
 hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, int cfg, hipStream_t st);
 int choose_gemm_config(const GemmArgs &a, int in_dtype);
 hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st);
+hipError_t launch_softmax(const SoftmaxArgs &a, int dtype, bool packed, hipStream_t st);
 
 }  // namespace lpg

@@ -287,6 +287,240 @@ hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st)
 }
 
 // ---------------------------------------------------------------------------------
+// softmax over the contraction index of a packed left operand (row = free index), with
+// the scale and the optional causal mask of the attention block folded in.  Values are
+// v = x * scale * log2(e); a row part is summarised as (m, s) = (max v, sum 2^(v - m)).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr float kNegBig = -3.0e38f;  // "no element yet": finite, so differences never give NaN
+
+__device__ __forceinline__ void sm_merge(float &m, float &s, float m2, float s2)
+{
+    const float M = fmaxf(m, m2);
+    s = s * __builtin_amdgcn_exp2f(m - M) + s2 * __builtin_amdgcn_exp2f(m2 - M);
+    m = M;
+}
+
+// element v (< KV) of a 16-byte chunk, widened to fp32
+template <typename T>
+__device__ __forceinline__ float chunk_elem(const u32x4 &c, int v)
+{
+    if constexpr (T::ES == 4) {
+        return __uint_as_float(c[v]);
+    } else {
+        return (v & 1) ? __uint_as_float(c[v / 2] & 0xffff0000u) : __uint_as_float(c[v / 2] << 16);
+    }
+}
+
+// A workgroup of eight waves owns R (32, 16 or 8) consecutive rows of one 32-row group over
+// the whole contraction range.  In every fragment half those rows are one contiguous run of
+// R*16 bytes; runs are numbered q = 8*kb + 2*c + h, a wave load covers 64/R consecutive runs
+// (lane l: row l%R of run l/R), and consecutive waves take consecutive loads, so the
+// workgroup streams whole blocks in address order.  Lane-local k of chunk element v:
+// k0 + 8*(v/4) + v%4 with k0 = KB*kb + KF*c + 4*h.
+// CACHED: the R rows fit in 16 chunks per lane; they are read once, kept in registers
+// across the reduction and written once.  Otherwise the rows are streamed twice.
+template <typename T, int R, bool CACHED>
+__global__ __launch_bounds__(512) void softmax_packed_kernel(SoftmaxArgs a)
+{
+    constexpr int NW = 8, RPW = 64 / R, NCH = 16, KV = T::KV;
+    __shared__ float red_m[NW][32], red_s[NW][32];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int rl = lane % R, rsel = lane / R;
+    uint32_t wg = blockIdx.x;
+    const int sub = wg % (32 / R);
+    wg /= (32 / R);
+    const int g = wg % a.ngroups, b = wg / a.ngroups;
+    const int row = 32 * g + sub * R + rl;
+    int last = a.causal ? row + (a.cols - a.rows) : a.cols - 1;  // last kept column of this row
+    last = last < a.cols - 1 ? last : a.cols - 1;
+    if (row >= a.rows) last = -1;
+    const int nruns = a.nkb * 8;
+    const int64_t base = (int64_t)b * a.slot + (int64_t)g * kBlockBytes + (sub * R + rl) * 16;
+    const char *xp = a.x + base;
+    char *op = a.out + base;
+    const float sl = a.scale_log2e;
+    const int nbatches = CACHED ? 1 : (nruns + NCH * NW * RPW - 1) / (NCH * NW * RPW);
+
+    u32x4 buf[NCH];
+    auto run_of = [&](int i0, int i) { return ((i0 + i) * NW + w) * RPW + rsel; };
+    auto k0_of = [](int q) { return T::KB * (q >> 3) + T::KF * ((q >> 1) & 3) + 4 * (q & 1); };
+    auto off_of = [&](int q) { return (int64_t)(q >> 3) * a.kbs + (q & 7) * 512; };
+
+    float m = kNegBig, s = 0.0f;
+    for (int bt = 0; bt < nbatches; ++bt) {
+        const int i0 = bt * NCH;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int q = run_of(i0, i);
+            buf[i] = (u32x4){0u, 0u, 0u, 0u};
+            if (k0_of(q) <= last) buf[i] = *(const u32x4 *)(xp + off_of(q));  // also false past the last run
+        }
+        float bm = m;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int k0 = k0_of(run_of(i0, i));
+#pragma unroll
+            for (int v = 0; v < KV; ++v)
+                bm = (k0 + 8 * (v / 4) + v % 4 <= last) ? fmaxf(bm, chunk_elem<T>(buf[i], v) * sl) : bm;
+        }
+        float bs = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int k0 = k0_of(run_of(i0, i));
+#pragma unroll
+            for (int v = 0; v < KV; ++v)
+                bs += (k0 + 8 * (v / 4) + v % 4 <= last) ? __builtin_amdgcn_exp2f(chunk_elem<T>(buf[i], v) * sl - bm) : 0.0f;
+        }
+        s = s * __builtin_amdgcn_exp2f(m - bm) + bs;
+        m = bm;
+    }
+    // lanes l, l^R, l^2R, ... hold parts of the same row; then the eight waves
+#pragma unroll
+    for (int off = R; off < 64; off <<= 1) sm_merge(m, s, __shfl_xor(m, off, 64), __shfl_xor(s, off, 64));
+    if (lane < R) {
+        red_m[w][lane] = m;
+        red_s[w][lane] = s;
+    }
+    __syncthreads();
+    m = red_m[0][rl];
+    s = red_s[0][rl];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) sm_merge(m, s, red_m[ww][rl], red_s[ww][rl]);
+    const float inv = s > 0.0f ? 1.0f / s : 0.0f;
+
+    for (int bt = 0; bt < nbatches; ++bt) {
+        const int i0 = bt * NCH;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int q = run_of(i0, i);
+            const int k0 = k0_of(q);
+            if constexpr (!CACHED) {
+                buf[i] = (u32x4){0u, 0u, 0u, 0u};
+                if (k0 <= last) buf[i] = *(const u32x4 *)(xp + off_of(q));
+            }
+            float e[KV];
+#pragma unroll
+            for (int v = 0; v < KV; ++v)
+                e[v] = (k0 + 8 * (v / 4) + v % 4 <= last) ? __builtin_amdgcn_exp2f(chunk_elem<T>(buf[i], v) * sl - m) * inv : 0.0f;
+            u32x4 o;
+            if constexpr (T::ES == 4) {
+                o = (u32x4){__float_as_uint(e[0]), __float_as_uint(e[1]), __float_as_uint(e[2]), __float_as_uint(e[3])};
+            } else {
+                o = (u32x4){bf16_pack2(e[0], e[1]), bf16_pack2(e[2], e[3]), bf16_pack2(e[4], e[5]), bf16_pack2(e[6], e[7])};
+            }
+            if (q < nruns) *(u32x4 *)(op + off_of(q)) = o;
+        }
+    }
+}
+
+// The same operation on a row-major matrix: one workgroup per row, lanes along the row
+// (16-byte chunks when VEC says rows start and end on 16-byte boundaries).  The row is
+// read twice; the second read comes from cache for rows of ordinary length.
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void softmax_rows_kernel(SoftmaxArgs a)
+{
+    typedef typename T::raw raw;
+    constexpr int CH = VEC ? T::KV : 1;
+    __shared__ float red_m[4], red_s[4];
+    const int row = blockIdx.x % a.rows, b = blockIdx.x / a.rows;
+    int last = a.causal ? row + (a.cols - a.rows) : a.cols - 1;
+    last = last < a.cols - 1 ? last : a.cols - 1;
+    const int64_t base = (int64_t)b * a.slot + (int64_t)row * a.row_stride;
+    const raw *xp = (const raw *)(a.x + base);
+    raw *op = (raw *)(a.out + base);
+    const float sl = a.scale_log2e;
+    auto widen = [](raw r) {
+        if constexpr (T::ES == 4) return __uint_as_float(r); else return bf16_to_f32(r);
+    };
+
+    float m = kNegBig, s = 0.0f;
+    for (int j = threadIdx.x * CH; j <= last; j += 256 * CH) {
+        raw r[CH];
+        if constexpr (VEC) {
+            const u32x4 c = *(const u32x4 *)(xp + j);
+            __builtin_memcpy(r, &c, 16);
+        } else {
+            r[0] = xp[j];
+        }
+        float bm = m;
+#pragma unroll
+        for (int v = 0; v < CH; ++v) bm = (j + v <= last) ? fmaxf(bm, widen(r[v]) * sl) : bm;
+        float bs = 0.0f;
+#pragma unroll
+        for (int v = 0; v < CH; ++v) bs += (j + v <= last) ? __builtin_amdgcn_exp2f(widen(r[v]) * sl - bm) : 0.0f;
+        s = s * __builtin_amdgcn_exp2f(m - bm) + bs;
+        m = bm;
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) sm_merge(m, s, __shfl_xor(m, off, 64), __shfl_xor(s, off, 64));
+    if ((threadIdx.x & 63) == 0) {
+        red_m[threadIdx.x >> 6] = m;
+        red_s[threadIdx.x >> 6] = s;
+    }
+    __syncthreads();
+    m = red_m[0];
+    s = red_s[0];
+#pragma unroll
+    for (int ww = 1; ww < 4; ++ww) sm_merge(m, s, red_m[ww], red_s[ww]);
+    const float inv = s > 0.0f ? 1.0f / s : 0.0f;
+
+    for (int j = threadIdx.x * CH; j < a.cols; j += 256 * CH) {
+        raw r[CH] = {};
+        if (j <= last) {
+            if constexpr (VEC) {
+                const u32x4 c = *(const u32x4 *)(xp + j);
+                __builtin_memcpy(r, &c, 16);
+            } else {
+                r[0] = xp[j];
+            }
+        }
+        float e[CH];
+#pragma unroll
+        for (int v = 0; v < CH; ++v)
+            e[v] = (j + v <= last) ? __builtin_amdgcn_exp2f(widen(r[v]) * sl - m) * inv : 0.0f;
+        if constexpr (!VEC) {
+            if constexpr (T::ES == 4) op[j] = __float_as_uint(e[0]); else op[j] = (raw)bf16_rne(e[0]);
+        } else if constexpr (T::ES == 4) {
+            *(u32x4 *)(op + j) = (u32x4){__float_as_uint(e[0]), __float_as_uint(e[1]), __float_as_uint(e[2]), __float_as_uint(e[3])};
+        } else {
+            *(u32x4 *)(op + j) = (u32x4){bf16_pack2(e[0], e[1]), bf16_pack2(e[2], e[3]), bf16_pack2(e[4], e[5]), bf16_pack2(e[6], e[7])};
+        }
+    }
+}
+
+template <typename T>
+static hipError_t launch_softmax_dtype(const SoftmaxArgs &a, bool packed, hipStream_t st)
+{
+    if (!packed) {
+        const int64_t grid = (int64_t)a.batch * a.rows;
+        const bool vec = ((uintptr_t)a.x | (uintptr_t)a.out | (uint64_t)a.row_stride | (uint64_t)a.slot |
+                          (uint64_t)((int64_t)a.cols * T::ES)) % 16 == 0;
+        if (vec)
+            hipLaunchKernelGGL((softmax_rows_kernel<T, true>), dim3((unsigned)grid), dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL((softmax_rows_kernel<T, false>), dim3((unsigned)grid), dim3(256), 0, st, a);
+        return hipGetLastError();
+    }
+    // largest row count per workgroup whose rows still fit in the register cache
+    const int64_t groups = (int64_t)a.batch * a.ngroups;
+    if (32 * a.nkb <= 1024)
+        hipLaunchKernelGGL((softmax_packed_kernel<T, 32, true>), dim3((unsigned)groups), dim3(512), 0, st, a);
+    else if (16 * a.nkb <= 1024)
+        hipLaunchKernelGGL((softmax_packed_kernel<T, 16, true>), dim3((unsigned)(groups * 2)), dim3(512), 0, st, a);
+    else if (8 * a.nkb <= 1024)
+        hipLaunchKernelGGL((softmax_packed_kernel<T, 8, true>), dim3((unsigned)(groups * 4)), dim3(512), 0, st, a);
+    else
+        hipLaunchKernelGGL((softmax_packed_kernel<T, 32, false>), dim3((unsigned)groups), dim3(512), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax(const SoftmaxArgs &a, int dtype, bool packed, hipStream_t st)
+{
+    if (a.batch <= 0 || a.rows <= 0 || a.cols <= 0) return hipSuccess;
+    return dtype == LPG_F32 ? launch_softmax_dtype<F32>(a, packed, st) : launch_softmax_dtype<BF16>(a, packed, st);
+}
+
+// ---------------------------------------------------------------------------------
 // GEMM.  out[fl][fr] = epilogue(alpha * sum_k L[fl][k] * R[fr][k] + beta * Cin[fl][fr]),
 // L = P(L; FL, K), R = P(R; FR, K), out = P(out; free = FL, contraction = FR).
 //

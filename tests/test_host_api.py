@@ -108,6 +108,15 @@ def test_descriptor_errors_are_caught_on_the_host():
     assert _err(api.lpg_elementwise_packed, 9, fake, fake, 1.0, fake, pa) == api.LPG_EINVAL
     v = desc(LPG_PACKED_A, LPG_F32, 32, 32, parent=(64, 64))
     assert _err(api.lpg_elementwise_packed, api.LPG_EW_ADD, fake, fake, 1.0, fake, v) == api.LPG_EUNSUPPORTED
+    # softmax: rows must be the free index, one slot per matrix, aligned packed buffers
+    assert _err(api.lpg_softmax_packed, fake, fake, pb, 1.0, False) == api.LPG_EUNSUPPORTED
+    assert _err(api.lpg_softmax_packed, fake, fake, desc(api.LPG_COL_MAJOR, LPG_F32, 64, 64), 1.0, False) == api.LPG_EUNSUPPORTED
+    assert _err(api.lpg_softmax_packed, fake, fake, desc(LPG_PACKED_A, LPG_F32, 64, 64, batch=4, batch_div=2),
+                1.0, False) == api.LPG_EUNSUPPORTED
+    assert _err(api.lpg_softmax_packed, None, fake, pa, 1.0, False) == api.LPG_EINVAL
+    assert _err(api.lpg_softmax_packed, fake, fake + 8, pa, 1.0, False) == api.LPG_EALIGN
+    assert _err(api.lpg_softmax_packed, fake, fake, desc(LPG_PACKED_A, LPG_F32, 32, 32, parent=(64, 64), origin=(0, 16)),
+                1.0, False) == api.LPG_EALIGN
 
 
 def test_chain_link_check_and_workspace():
@@ -123,6 +132,13 @@ def test_chain_link_check_and_workspace():
     assert api.lpg_chain_workspace_bytes(stages, api.LPG_CHAIN_PROPAGATED) == 0
     # only C1 crosses a GEMM->GEMM boundary: one 64x64 fp32 row-major copy
     assert api.lpg_chain_workspace_bytes(stages, api.LPG_CHAIN_CANONICAL) == 64 * 64 * 4
+    # a softmax between the GEMMs runs in place on that same copy: no extra workspace
+    with_sm = stages[:2] + [api.stage_softmax(c1, c1, a_d, 0.5, True)] + stages[2:]
+    assert api.lpg_chain_workspace_bytes(with_sm, api.LPG_CHAIN_CANONICAL) == 64 * 64 * 4
+    with_sm[2] = api.stage_softmax(c1, c1, desc(LPG_PACKED_A, LPG_F32, 64, 64, parent=(128, 64)), 0.5, True)
+    with pytest.raises(api.LpgError) as e:
+        api.lpg_chain(with_sm, api.LPG_CHAIN_PROPAGATED)
+    assert e.value.code == api.LPG_ELAYOUT
     # consumer reads C1 with another geometry -> layout error before any launch
     wrong = desc(LPG_PACKED_A, LPG_F32, 64, 64, parent=(128, 64))
     stages[2] = api.stage_gemm(1.0, c1, wrong, w2, b_d, 0.0, None, c2, desc(LPG_PACKED_A, LPG_F32, 64, 64))
