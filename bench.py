@@ -83,10 +83,39 @@ def time_gemm_launches(ch, steps):
     return total_ms * 1e-3 / len(pairs), nflops / ngemm
 
 
-def measure(name, steps, warmup, shape_over=None, modes="both"):
+def time_softmax_launches(ch, steps):
+    """Average duration of the chain's softmax launch (event pair around each), with the bytes
+    it has to move: the kept scores read once, the whole score matrix written once."""
+    import torch
+    from paper_2604_04599_amd import api
+    st = torch.cuda.current_stream().cuda_stream
+    pairs = []
+    nbytes = 0
+    for it in range(steps):
+        for s in ch.stages:
+            if s.type != api.LPG_STAGE_SOFTMAX:
+                api.lpg_chain([s], api.LPG_CHAIN_PROPAGATED, None, 0, st)
+                continue
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            api.lpg_chain([s], api.LPG_CHAIN_PROPAGATED, None, 0, st)
+            e1.record()
+            pairs.append((e0, e1))
+            if it == 0:
+                d = s.out_d
+                r, c, nb = d.rows, d.cols, max(d.batch, 1)
+                kept = r * c if not s.op else sum(min(c, max(0, i + c - r + 1)) for i in range(r))
+                nbytes += (kept + r * c) * nb * api.ELEM_SIZE[d.dtype]
+    torch.cuda.synchronize()
+    t = sum(a.elapsed_time(b) for a, b in pairs) * 1e-3 / len(pairs)
+    return t, nbytes
+
+
+def measure(name, steps, warmup, shape_over=None, modes="both", options=None):
     from paper_2604_04599_amd import api, chains, inputs
+    options = options or {}
     inp, shape = inputs.make(name, **(shape_over or {}))
-    ch = chains.build(name, inp, shape)
+    ch = chains.build(name, inp, shape, **options)
     flops = inputs.gemm_flops(name, shape)
     dt = inputs.DTYPES[name]
     res = {"dtype": dt, "shape": shape, "gemm_gflop": round(flops / 1e9, 3)}
@@ -106,7 +135,7 @@ def measure(name, steps, warmup, shape_over=None, modes="both"):
         res["propagated_ms_per_step_interleaved"] = round(mp * 1e3, 4)
         res["speedup_vs_canonical"] = round(mc / mp, 3)
         # the same chain with the entry pack / exit unpack fused into the first / last GEMM
-        fch = chains.build(name, inp, shape, fused=True)
+        fch = chains.build(name, inp, shape, fused=True, **options)
         t_f = time_chain(fch, api.LPG_CHAIN_PROPAGATED, steps, warmup)
         res["fused_boundaries_ms_per_step"] = round(t_f * 1e3, 4)
         res["fused_boundaries_tflops"] = round(flops / t_f / 1e12, 2)
@@ -204,6 +233,18 @@ def main():
         steps = args.steps if w != "deep_chain" else max(3, args.steps // 4)
         res, c2, _, _ = measure(w, steps, min(args.warmup, steps))
         per[w] = res
+        del c2
+        torch.cuda.empty_cache()
+
+    if args.workloads == "all" or "attention_softmax" in args.workloads.split(","):
+        # the attention chain with the scale + causal mask + softmax stage between its GEMMs,
+        # run on the packed scores (propagated) or on their row-major copy (canonical control)
+        res, c2, _, _ = measure("attention", args.steps, args.warmup, options={"softmax": True, "causal": True})
+        t_sm, sm_bytes = time_softmax_launches(c2, args.steps)
+        res["softmax_kernel"] = {"bound": "hbm", "achieved": round(sm_bytes / t_sm / 1e9, 1), "peak": 8000.0,
+                                 "unit": "GB/s", "frac": round(sm_bytes / t_sm / 8e12, 4),
+                                 "avg_launch_us": round(t_sm * 1e6, 2), "algorithmic_bytes": sm_bytes}
+        per["attention_softmax_causal"] = res
         del c2
         torch.cuda.empty_cache()
 

@@ -290,6 +290,8 @@ hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st)
 // softmax over the contraction index of a packed left operand (row = free index), with
 // the scale and the optional causal mask of the attention block folded in.  Values are
 // v = x * scale * log2(e); a row part is summarised as (m, s) = (max v, sum 2^(v - m)).
+// The maximum is taken over products x*sl, the exponent's argument is one fused
+// multiply-add fma(x, sl, -m): one rounding, and no product is kept between the passes.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr float kNegBig = -3.0e38f;  // "no element yet": finite, so differences never give NaN
 
@@ -311,18 +313,32 @@ __device__ __forceinline__ float chunk_elem(const u32x4 &c, int v)
     }
 }
 
-// A workgroup of eight waves owns R (32, 16 or 8) consecutive rows of one 32-row group over
+// Makes the compiler treat the chunks as new values (no instruction is emitted), so that it
+// re-derives widened elements from the 16-byte chunks in the next pass instead of keeping
+// every element of the previous pass alive in a register of its own.
+template <int N>
+__device__ __forceinline__ void forget_derived(u32x4 (&buf)[N])
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(buf[i]));
+}
+
+// A workgroup of NW waves owns R (32, 16 or 8) consecutive rows of one 32-row group over
 // the whole contraction range.  In every fragment half those rows are one contiguous run of
 // R*16 bytes; runs are numbered q = 8*kb + 2*c + h, a wave load covers 64/R consecutive runs
 // (lane l: row l%R of run l/R), and consecutive waves take consecutive loads, so the
-// workgroup streams whole blocks in address order.  Lane-local k of chunk element v:
+// workgroup streams whole blocks in address order.  NW*64/R is a multiple of 8, so a lane
+// stays on one (c, h) and only its K block advances, by NW*8/R per load: addresses and k
+// indices are affine in the load counter.  Lane-local k of chunk element v:
 // k0 + 8*(v/4) + v%4 with k0 = KB*kb + KF*c + 4*h.
 // CACHED: the R rows fit in 16 chunks per lane; they are read once, kept in registers
 // across the reduction and written once.  Otherwise the rows are streamed twice.
-template <typename T, int R, bool CACHED>
-__global__ __launch_bounds__(512) void softmax_packed_kernel(SoftmaxArgs a)
+template <typename T, int R, int NW, bool CACHED>
+__global__ __launch_bounds__(NW * 64) void softmax_packed_kernel(SoftmaxArgs a)
 {
-    constexpr int NW = 8, RPW = 64 / R, NCH = 16, KV = T::KV;
+    constexpr int RPW = 64 / R, NCH = 16, KV = T::KV;
+    constexpr int KBSTEP = NW * RPW / 8;  // K blocks a lane advances per load
+    static_assert((NW * RPW) % 8 == 0, "a lane must stay on one fragment half");
     __shared__ float red_m[NW][32], red_s[NW][32];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int rl = lane % R, rsel = lane / R;
@@ -334,47 +350,48 @@ __global__ __launch_bounds__(512) void softmax_packed_kernel(SoftmaxArgs a)
     int last = a.causal ? row + (a.cols - a.rows) : a.cols - 1;  // last kept column of this row
     last = last < a.cols - 1 ? last : a.cols - 1;
     if (row >= a.rows) last = -1;
-    const int nruns = a.nkb * 8;
-    const int64_t base = (int64_t)b * a.slot + (int64_t)g * kBlockBytes + (sub * R + rl) * 16;
+    const int q0 = w * RPW + rsel;  // this lane's run in load 0
+    const int kfirst = T::KB * (q0 >> 3) + T::KF * ((q0 >> 1) & 3) + 4 * (q0 & 1);
+    const int kend = T::KB * a.nkb;  // runs exist for k0 < kend
+    const int64_t base = (int64_t)b * a.slot + (int64_t)g * kBlockBytes + (sub * R + rl) * 16 +
+                         (int64_t)(q0 >> 3) * a.kbs + (q0 & 7) * 512;
     const char *xp = a.x + base;
     char *op = a.out + base;
+    const int64_t step = (int64_t)KBSTEP * a.kbs;
     const float sl = a.scale_log2e;
-    const int nbatches = CACHED ? 1 : (nruns + NCH * NW * RPW - 1) / (NCH * NW * RPW);
+    const int nbatches = CACHED ? 1 : (a.nkb + NCH * KBSTEP - 1) / (NCH * KBSTEP);
 
     u32x4 buf[NCH];
-    auto run_of = [&](int i0, int i) { return ((i0 + i) * NW + w) * RPW + rsel; };
-    auto k0_of = [](int q) { return T::KB * (q >> 3) + T::KF * ((q >> 1) & 3) + 4 * (q & 1); };
-    auto off_of = [&](int q) { return (int64_t)(q >> 3) * a.kbs + (q & 7) * 512; };
-
     float m = kNegBig, s = 0.0f;
     for (int bt = 0; bt < nbatches; ++bt) {
-        const int i0 = bt * NCH;
+        const int k0b = kfirst + bt * NCH * KBSTEP * T::KB;
+        const char *xb = xp + (int64_t)bt * NCH * step;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int q = run_of(i0, i);
             buf[i] = (u32x4){0u, 0u, 0u, 0u};
-            if (k0_of(q) <= last) buf[i] = *(const u32x4 *)(xp + off_of(q));  // also false past the last run
+            if (k0b + i * KBSTEP * T::KB <= last) buf[i] = *(const u32x4 *)(xb + i * step);  // last < kend
         }
         float bm = m;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int k0 = k0_of(run_of(i0, i));
+            const int k0 = k0b + i * KBSTEP * T::KB;
 #pragma unroll
             for (int v = 0; v < KV; ++v)
                 bm = (k0 + 8 * (v / 4) + v % 4 <= last) ? fmaxf(bm, chunk_elem<T>(buf[i], v) * sl) : bm;
         }
+        forget_derived(buf);
         float bs = 0.0f;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int k0 = k0_of(run_of(i0, i));
+            const int k0 = k0b + i * KBSTEP * T::KB;
 #pragma unroll
             for (int v = 0; v < KV; ++v)
-                bs += (k0 + 8 * (v / 4) + v % 4 <= last) ? __builtin_amdgcn_exp2f(chunk_elem<T>(buf[i], v) * sl - bm) : 0.0f;
+                bs += (k0 + 8 * (v / 4) + v % 4 <= last) ? __builtin_amdgcn_exp2f(fmaf(chunk_elem<T>(buf[i], v), sl, -bm)) : 0.0f;
         }
         s = s * __builtin_amdgcn_exp2f(m - bm) + bs;
         m = bm;
     }
-    // lanes l, l^R, l^2R, ... hold parts of the same row; then the eight waves
+    // lanes l, l^R, l^2R, ... hold parts of the same row; then the NW waves
 #pragma unroll
     for (int off = R; off < 64; off <<= 1) sm_merge(m, s, __shfl_xor(m, off, 64), __shfl_xor(s, off, 64));
     if (lane < R) {
@@ -387,28 +404,30 @@ __global__ __launch_bounds__(512) void softmax_packed_kernel(SoftmaxArgs a)
 #pragma unroll
     for (int ww = 1; ww < NW; ++ww) sm_merge(m, s, red_m[ww][rl], red_s[ww][rl]);
     const float inv = s > 0.0f ? 1.0f / s : 0.0f;
+    forget_derived(buf);
 
     for (int bt = 0; bt < nbatches; ++bt) {
-        const int i0 = bt * NCH;
+        const int k0b = kfirst + bt * NCH * KBSTEP * T::KB;
+        const char *xb = xp + (int64_t)bt * NCH * step;
+        char *ob = op + (int64_t)bt * NCH * step;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int q = run_of(i0, i);
-            const int k0 = k0_of(q);
+            const int k0 = k0b + i * KBSTEP * T::KB;
             if constexpr (!CACHED) {
                 buf[i] = (u32x4){0u, 0u, 0u, 0u};
-                if (k0 <= last) buf[i] = *(const u32x4 *)(xp + off_of(q));
+                if (k0 <= last) buf[i] = *(const u32x4 *)(xb + i * step);
             }
             float e[KV];
 #pragma unroll
             for (int v = 0; v < KV; ++v)
-                e[v] = (k0 + 8 * (v / 4) + v % 4 <= last) ? __builtin_amdgcn_exp2f(chunk_elem<T>(buf[i], v) * sl - m) * inv : 0.0f;
+                e[v] = (k0 + 8 * (v / 4) + v % 4 <= last) ? __builtin_amdgcn_exp2f(fmaf(chunk_elem<T>(buf[i], v), sl, -m)) * inv : 0.0f;
             u32x4 o;
             if constexpr (T::ES == 4) {
                 o = (u32x4){__float_as_uint(e[0]), __float_as_uint(e[1]), __float_as_uint(e[2]), __float_as_uint(e[3])};
             } else {
                 o = (u32x4){bf16_pack2(e[0], e[1]), bf16_pack2(e[2], e[3]), bf16_pack2(e[4], e[5]), bf16_pack2(e[6], e[7])};
             }
-            if (q < nruns) *(u32x4 *)(op + off_of(q)) = o;
+            if (k0 < kend) *(u32x4 *)(ob + i * step) = o;
         }
     }
 }
@@ -447,7 +466,7 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(SoftmaxArgs a)
         for (int v = 0; v < CH; ++v) bm = (j + v <= last) ? fmaxf(bm, widen(r[v]) * sl) : bm;
         float bs = 0.0f;
 #pragma unroll
-        for (int v = 0; v < CH; ++v) bs += (j + v <= last) ? __builtin_amdgcn_exp2f(widen(r[v]) * sl - bm) : 0.0f;
+        for (int v = 0; v < CH; ++v) bs += (j + v <= last) ? __builtin_amdgcn_exp2f(fmaf(widen(r[v]), sl, -bm)) : 0.0f;
         s = s * __builtin_amdgcn_exp2f(m - bm) + bs;
         m = bm;
     }
@@ -477,7 +496,7 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(SoftmaxArgs a)
         float e[CH];
 #pragma unroll
         for (int v = 0; v < CH; ++v)
-            e[v] = (j + v <= last) ? __builtin_amdgcn_exp2f(widen(r[v]) * sl - m) * inv : 0.0f;
+            e[v] = (j + v <= last) ? __builtin_amdgcn_exp2f(fmaf(widen(r[v]), sl, -m)) * inv : 0.0f;
         if constexpr (!VEC) {
             if constexpr (T::ES == 4) op[j] = __float_as_uint(e[0]); else op[j] = (raw)bf16_rne(e[0]);
         } else if constexpr (T::ES == 4) {
@@ -501,16 +520,27 @@ static hipError_t launch_softmax_dtype(const SoftmaxArgs &a, bool packed, hipStr
             hipLaunchKernelGGL((softmax_rows_kernel<T, false>), dim3((unsigned)grid), dim3(256), 0, st, a);
         return hipGetLastError();
     }
-    // largest row count per workgroup whose rows still fit in the register cache
-    const int64_t groups = (int64_t)a.batch * a.ngroups;
-    if (32 * a.nkb <= 1024)
-        hipLaunchKernelGGL((softmax_packed_kernel<T, 32, true>), dim3((unsigned)groups), dim3(512), 0, st, a);
-    else if (16 * a.nkb <= 1024)
-        hipLaunchKernelGGL((softmax_packed_kernel<T, 16, true>), dim3((unsigned)(groups * 2)), dim3(512), 0, st, a);
-    else if (8 * a.nkb <= 1024)
-        hipLaunchKernelGGL((softmax_packed_kernel<T, 8, true>), dim3((unsigned)(groups * 4)), dim3(512), 0, st, a);
-    else
-        hipLaunchKernelGGL((softmax_packed_kernel<T, 32, false>), dim3((unsigned)groups), dim3(512), 0, st, a);
+    // Variants: rows per workgroup, waves, cached.  A cached variant holds rows of up to
+    // 128 * waves / R K blocks (16 chunks a lane).  LPG_SOFTMAX_VARIANT=<n> pins the choice
+    // if that variant can hold the rows (a tuning aid).
+    struct Variant { int r, nw; bool cached; };
+    static const Variant kVariants[] = {{32, 8, true}, {16, 8, true}, {8, 8, true}, {8, 16, true},
+                                        {8, 8, false}};
+    auto fits = [&](int v) { return !kVariants[v].cached || kVariants[v].r * a.nkb <= 128 * kVariants[v].nw; };
+    int variant = fits(0) ? 0 : fits(1) ? 1 : fits(2) ? 2 : fits(3) ? 3 : 4;
+    if (const char *f = getenv("LPG_SOFTMAX_VARIANT")) {
+        const int v = atoi(f);
+        if (v >= 0 && v < 5 && fits(v)) variant = v;
+    }
+    const unsigned grid = (unsigned)((int64_t)a.batch * a.ngroups * (32 / kVariants[variant].r));
+    const dim3 block(kVariants[variant].nw * 64);
+    switch (variant) {
+        case 0: hipLaunchKernelGGL((softmax_packed_kernel<T, 32, 8, true>), dim3(grid), block, 0, st, a); break;
+        case 1: hipLaunchKernelGGL((softmax_packed_kernel<T, 16, 8, true>), dim3(grid), block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL((softmax_packed_kernel<T, 8, 8, true>), dim3(grid), block, 0, st, a); break;
+        case 3: hipLaunchKernelGGL((softmax_packed_kernel<T, 8, 16, true>), dim3(grid), block, 0, st, a); break;
+        default: hipLaunchKernelGGL((softmax_packed_kernel<T, 8, 8, false>), dim3(grid), block, 0, st, a); break;
+    }
     return hipGetLastError();
 }
 
