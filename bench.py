@@ -172,7 +172,8 @@ def main():
                     help="comma list of extra workloads to report beside the headline, 'all' or 'none'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default=None,
-                    help="profiling aid: time just this workload and print its line")
+                    help="profiling aid: time just this workload (a workload name, or "
+                         "attention_softmax_causal) and print its line")
     ap.add_argument("--mode", default="both", choices=["both", "propagated", "canonical"],
                     help="with --only: which chain mode(s) to run")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -204,7 +205,10 @@ def main():
         return
 
     if args.only:
-        res, _, _, _ = measure(args.only, args.steps, args.warmup, modes=args.mode)
+        name, options = args.only, None
+        if name == "attention_softmax_causal":
+            name, options = "attention", {"softmax": True, "causal": True}
+        res, _, _, _ = measure(name, args.steps, args.warmup, modes=args.mode, options=options)
         print(json.dumps({"workload": args.only, **res}))
         return
 
