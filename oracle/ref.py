@@ -136,6 +136,44 @@ def softmax_rows(x, scale=1.0, causal=False):
     return out
 
 
+def rope_angles(positions, head_dim, base=10000.0):
+    """theta[t][i] = positions[t] * base**(-2i/head_dim), i < head_dim/2 (rotary position
+    embedding; Alg. 2 applies it to Q and K before the score GEMM)."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    return np.asarray(positions, dtype=np.float64)[:, None] * base ** (-2.0 * i / head_dim)[None, :]
+
+
+def rope(x, cos, sin, head_dim):
+    """Rotary embedding of every head of x [T, heads*head_dim] with tables cos, sin
+    [T, head_dim/2]: element i of a head's first half pairs with element i of its second half,
+    and the pair (a, b) of row t becomes (a cos - b sin, b cos + a sin) with the angle of
+    (t, i).  Rows rotate independently (section IV-A)."""
+    x = _f64(x)
+    cos, sin = _f64(cos), _f64(sin)
+    half = head_dim // 2
+    out = np.empty_like(x)
+    for h0 in range(0, x.shape[1], head_dim):
+        a, b = x[:, h0:h0 + half], x[:, h0 + half:h0 + head_dim]
+        out[:, h0:h0 + half] = a * cos - b * sin
+        out[:, h0 + half:h0 + head_dim] = b * cos + a * sin
+    return out
+
+
+def rmsnorm(x, weight, eps):
+    """Row-wise root-mean-square normalisation: y[t][j] = x[t][j] / sqrt(mean_j x[t][j]^2 + eps)
+    * weight[j] (the RMSNorm of the contributions list; Llama's normalisation)."""
+    x = _f64(x)
+    w = _f64(weight)
+    out = np.empty_like(x)
+    for t in range(x.shape[0]):
+        ms = 0.0
+        for v in x[t]:
+            ms += v * v
+        ms /= x.shape[1]
+        out[t] = x[t] / np.sqrt(ms + eps) * w
+    return out
+
+
 # ------------------------------------------------------------------ packed layout
 
 def layout_consts(es):

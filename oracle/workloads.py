@@ -112,3 +112,37 @@ def decoder_layer(inp, n_q, n_kv, store=None, rows=None):
     return {"Q": q, "K": k, "V": v, "O": o, "attn": attn, "gate": gate, "up": up,
             "act": act, "Y": y}
 
+
+
+def llama_layer(inp, n_q, n_kv, eps=1e-5, rope_base=500000.0, store=None):
+    """A whole pre-norm decoder layer on the chain (Alg. 2 with its RoPE, causal mask and softmax,
+    between RMSNorm-ed residual blocks, followed by the gated MLP):
+        h1 = RMSNorm(X) ; Q, K, V = h1 Wq, h1 Wk, h1 Wv ; RoPE on Q and K (positions 0..T-1) ;
+        per query head: P = softmax(causal((1/sqrt(d)) Q_h K_g^T)), O_h = P V_g ;
+        A = O Wo + X ; h2 = RMSNorm(A) ; Y = (SiLU(h2 Wg) * (h2 Wu)) Wd + A."""
+    x = np.asarray(inp["X"], dtype=np.float64)
+    T = x.shape[0]
+    d = inp["Wq"].shape[1] // n_q
+    rep = n_q // n_kv
+    h1 = _st(ref.rmsnorm(x, inp["norm1"], eps), store)
+    q = _st(ref.gemm(h1, inp["Wq"]), store)
+    k = _st(ref.gemm(h1, inp["Wk"]), store)
+    v = _st(ref.gemm(h1, inp["Wv"]), store)
+    th = ref.rope_angles(np.arange(T), d, rope_base)
+    q = _st(ref.rope(q, np.cos(th), np.sin(th), d), store)
+    k = _st(ref.rope(k, np.cos(th), np.sin(th), d), store)
+    o = np.empty((T, n_q * d), dtype=np.float64)
+    for h in range(n_q):
+        g = h // rep
+        kg = np.ascontiguousarray(k[:, g * d:(g + 1) * d].T)
+        s = _st(ref.gemm(np.ascontiguousarray(q[:, h * d:(h + 1) * d]), kg), store)
+        p = _st(ref.softmax_rows(s, scale=1.0 / np.sqrt(d), causal=True), store)
+        o[:, h * d:(h + 1) * d] = ref.gemm(p, np.ascontiguousarray(v[:, g * d:(g + 1) * d]))
+    o = _st(o, store)
+    a = _st(ref.gemm(o, inp["Wo"], beta=1.0, C=x), store)
+    h2 = _st(ref.rmsnorm(a, inp["norm2"], eps), store)
+    gate = _st(ref.gemm(h2, inp["Wg"]), store)
+    up = _st(ref.gemm(h2, inp["Wu"]), store)
+    act = _st(ref.silu_mul(gate, up), store)
+    y = ref.gemm(act, inp["Wd"], beta=1.0, C=a)
+    return {"h1": h1, "Q": q, "K": k, "V": v, "O": o, "A": a, "h2": h2, "act": act, "Y": y}
