@@ -186,7 +186,7 @@ int lpg_elementwise_packed(int op, const void *x0, const void *x1, float s, void
  *     out[i][j] = exp(scale*x[i][j] - m_i) / sum_j' exp(scale*x[i][j'] - m_i),
  * m_i = max_j scale*x[i][j], over the logical columns of every row of every slot.
  * causal != 0 keeps only columns j <= i + (cols - rows) of row i; masked positions,
- * and rows with no kept column, get 0.
+ * and rows with no kept column, get 0.  scale must be positive and finite (LPG_EINVAL).
  *   d->kind == LPG_PACKED_A (the row index is the free index, the softmax runs along
  *   the contraction index of the GEMM that will consume the result as its left
  *   operand; views as in lpg_desc, batch_div must be 1) or LPG_ROW_MAJOR (any ld /
@@ -198,30 +198,68 @@ int lpg_elementwise_packed(int op, const void *x0, const void *x1, float s, void
 int lpg_softmax_packed(const void *x, void *out, const lpg_desc *d, float scale, int causal,
                        void *stream);
 
+/*
+ * lpg_rmsnorm_packed - RMS normalisation on the packed layout (the RMSNorm the paper lists
+ * among the operations re-implemented for the propagated layout; it gives no formula, so
+ * the usual one is taken):  out[i][j] = x[i][j] / sqrt(mean_j x[i][j]^2 + eps) * weight[j].
+ *   d, x, out: as for lpg_softmax_packed (LPG_PACKED_A or LPG_ROW_MAJOR, shared descriptor,
+ *   in place allowed).  weight: device, d->cols fp32 values.  eps >= 0.
+ */
+int lpg_rmsnorm_packed(const void *x, const float *weight, void *out, const lpg_desc *d, float eps,
+                       void *stream);
+
+/*
+ * lpg_rope_tables - cosine / sine tables for lpg_rope_packed: device fp32, row-major
+ * [rows][head_dim/2], cos_t[t][i] = cos((pos0 + t) * base^(-2i/head_dim)), sin_t likewise.
+ * Angles, cosines and sines are computed in fp64 and rounded once.
+ */
+int lpg_rope_tables(float *cos_t, float *sin_t, int64_t rows, int32_t head_dim, double base,
+                    int64_t pos0, void *stream);
+
+/*
+ * lpg_rope_packed - rotary position embedding of Q or K on the packed layout (Alg. 2, the
+ * step before the score GEMM; section IV-A: rows rotate independently, which is how the
+ * layout interleaves them, so 32 positions are rotated per wave access).  d->cols must be
+ * heads * head_dim; in every head, element i of the first half pairs with element i of the
+ * second half (the paper fixes no pairing; this is the one Llama checkpoints are stored
+ * for), and row t's pair (a, b) becomes (a*cos - b*sin, b*cos + a*sin) with cos_t[t][i],
+ * sin_t[t][i] (device fp32 tables with at least d->rows rows, 16-byte aligned; every slot
+ * of a batch uses the same tables).
+ *   d, x, out: as for lpg_softmax_packed.  Packed kinds need head_dim to be a multiple of
+ *   16 (fp32) or 32 (bf16), so that a head's halves are whole fragments apart
+ *   (LPG_EUNSUPPORTED otherwise).  Math in fp32; bf16 results rounded to nearest even.
+ */
+int lpg_rope_packed(const void *x, void *out, const lpg_desc *d, const float *cos_t,
+                    const float *sin_t, int32_t head_dim, void *stream);
+
 /* One stage of a chain. */
 typedef enum {
     LPG_STAGE_PACK = 0,
     LPG_STAGE_GEMM = 1,
     LPG_STAGE_ELEMENTWISE = 2,
     LPG_STAGE_UNPACK = 3,
-    LPG_STAGE_SOFTMAX = 4
+    LPG_STAGE_SOFTMAX = 4,
+    LPG_STAGE_RMSNORM = 5,
+    LPG_STAGE_ROPE = 6
 } lpg_stage_type;
 
 typedef struct lpg_stage {
     int32_t type;       /* lpg_stage_type                                               */
-    int32_t op;         /* GEMM: lpg_epilogue_op; ELEMENTWISE: lpg_ew_op; SOFTMAX: causal */
+    int32_t op;         /* GEMM: lpg_epilogue_op; ELEMENTWISE: lpg_ew_op; SOFTMAX: causal;
+                           ROPE: head_dim                                                */
     float alpha, beta;  /* GEMM                                                         */
-    float scalar;       /* ELEMENTWISE: s; SOFTMAX: scale                               */
+    float scalar;       /* ELEMENTWISE: s; SOFTMAX: scale; RMSNORM: eps                 */
     int32_t reserved;
-    const void *in0;    /* PACK/UNPACK: src; GEMM: A; ELEMENTWISE: x0; SOFTMAX: x       */
-    const void *in1;    /* GEMM: B; ELEMENTWISE: x1                                     */
-    const void *in2;    /* GEMM: C_in (or NULL)                                         */
+    const void *in0;    /* PACK/UNPACK: src; GEMM: A; ELEMENTWISE: x0; SOFTMAX, RMSNORM,
+                           ROPE: x                                                       */
+    const void *in1;    /* GEMM: B; ELEMENTWISE: x1; RMSNORM: weight; ROPE: cos table   */
+    const void *in2;    /* GEMM: C_in (or NULL); ROPE: sin table                        */
     const void *epi_arg;/* GEMM: epilogue argument (or NULL)                            */
     void *out;
     lpg_desc in0_d;     /* descriptor of in0                                            */
     lpg_desc in1_d;     /* GEMM: descriptor of B                                        */
-    lpg_desc out_d;     /* descriptor of out (and of in2, epi_arg, ELEMENTWISE / SOFTMAX
-                           inputs)                                                       */
+    lpg_desc out_d;     /* descriptor of out (and of in2, epi_arg, and of the x inputs of
+                           ELEMENTWISE / SOFTMAX / RMSNORM / ROPE)                       */
 } lpg_stage;
 
 typedef enum {

@@ -114,35 +114,46 @@ def decoder_layer(inp, n_q, n_kv, store=None, rows=None):
 
 
 
-def llama_layer(inp, n_q, n_kv, eps=1e-5, rope_base=500000.0, store=None):
+def llama_layer(inp, n_q, n_kv, eps=1e-5, rope_base=500000.0, store=None, rows=None):
     """A whole pre-norm decoder layer on the chain (Alg. 2 with its RoPE, causal mask and softmax,
     between RMSNorm-ed residual blocks, followed by the gated MLP):
         h1 = RMSNorm(X) ; Q, K, V = h1 Wq, h1 Wk, h1 Wv ; RoPE on Q and K (positions 0..T-1) ;
         per query head: P = softmax(causal((1/sqrt(d)) Q_h K_g^T)), O_h = P V_g ;
-        A = O Wo + X ; h2 = RMSNorm(A) ; Y = (SiLU(h2 Wg) * (h2 Wu)) Wd + A."""
+        A = O Wo + X ; h2 = RMSNorm(A) ; Y = (SiLU(h2 Wg) * (h2 Wu)) Wd + A.
+    rows: compute only these token rows of everything downstream of K and V (which are always
+    whole); a sampled row keeps its position for RoPE and for the causal mask."""
     x = np.asarray(inp["X"], dtype=np.float64)
     T = x.shape[0]
+    pos = np.arange(T) if rows is None else np.asarray(rows)
     d = inp["Wq"].shape[1] // n_q
     rep = n_q // n_kv
     h1 = _st(ref.rmsnorm(x, inp["norm1"], eps), store)
-    q = _st(ref.gemm(h1, inp["Wq"]), store)
+    q = _st(ref.gemm(h1[pos], inp["Wq"]), store)
     k = _st(ref.gemm(h1, inp["Wk"]), store)
     v = _st(ref.gemm(h1, inp["Wv"]), store)
     th = ref.rope_angles(np.arange(T), d, rope_base)
-    q = _st(ref.rope(q, np.cos(th), np.sin(th), d), store)
+    q = _st(ref.rope(q, np.cos(th[pos]), np.sin(th[pos]), d), store)
     k = _st(ref.rope(k, np.cos(th), np.sin(th), d), store)
-    o = np.empty((T, n_q * d), dtype=np.float64)
+    o = np.empty((len(pos), n_q * d), dtype=np.float64)
+    P = {}
     for h in range(n_q):
         g = h // rep
         kg = np.ascontiguousarray(k[:, g * d:(g + 1) * d].T)
         s = _st(ref.gemm(np.ascontiguousarray(q[:, h * d:(h + 1) * d]), kg), store)
-        p = _st(ref.softmax_rows(s, scale=1.0 / np.sqrt(d), causal=True), store)
+        if rows is None:
+            p = ref.softmax_rows(s, scale=1.0 / np.sqrt(d), causal=True)
+        else:
+            p = np.zeros_like(s)
+            for i, r in enumerate(pos):                  # row at position r sees keys 0..r
+                p[i, :r + 1] = ref.softmax_rows(s[i:i + 1, :r + 1], scale=1.0 / np.sqrt(d))
+        p = _st(p, store)
+        P[h] = p
         o[:, h * d:(h + 1) * d] = ref.gemm(p, np.ascontiguousarray(v[:, g * d:(g + 1) * d]))
     o = _st(o, store)
-    a = _st(ref.gemm(o, inp["Wo"], beta=1.0, C=x), store)
+    a = _st(ref.gemm(o, inp["Wo"], beta=1.0, C=x[pos]), store)
     h2 = _st(ref.rmsnorm(a, inp["norm2"], eps), store)
     gate = _st(ref.gemm(h2, inp["Wg"]), store)
     up = _st(ref.gemm(h2, inp["Wu"]), store)
     act = _st(ref.silu_mul(gate, up), store)
     y = ref.gemm(act, inp["Wd"], beta=1.0, C=a)
-    return {"h1": h1, "Q": q, "K": k, "V": v, "O": o, "A": a, "h2": h2, "act": act, "Y": y}
+    return {"h1": h1, "Q": q, "K": k, "V": v, "P": P, "O": o, "A": a, "h2": h2, "act": act, "Y": y}

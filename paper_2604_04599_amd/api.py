@@ -18,6 +18,7 @@ LPG_ROW_MAJOR, LPG_COL_MAJOR, LPG_PACKED_A, LPG_PACKED_B = 0, 1, 2, 3
 LPG_EW_SCALE, LPG_EW_ADD, LPG_EW_SILU_MUL = 0, 1, 2
 LPG_EPI_NONE, LPG_EPI_SILU, LPG_EPI_GATE_SILU = 0, 1, 2
 LPG_STAGE_PACK, LPG_STAGE_GEMM, LPG_STAGE_ELEMENTWISE, LPG_STAGE_UNPACK, LPG_STAGE_SOFTMAX = 0, 1, 2, 3, 4
+LPG_STAGE_RMSNORM, LPG_STAGE_ROPE = 5, 6
 LPG_CHAIN_PROPAGATED, LPG_CHAIN_CANONICAL = 0, 1
 
 ELEM_SIZE = {LPG_F32: 4, LPG_BF16: 2}
@@ -84,6 +85,12 @@ def lib():
         L.lpg_elementwise_packed.restype = ctypes.c_int
         L.lpg_softmax_packed.argtypes = [vp, vp, dp, ctypes.c_float, ctypes.c_int, vp]
         L.lpg_softmax_packed.restype = ctypes.c_int
+        L.lpg_rmsnorm_packed.argtypes = [vp, vp, vp, dp, ctypes.c_float, vp]
+        L.lpg_rmsnorm_packed.restype = ctypes.c_int
+        L.lpg_rope_tables.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_double, ctypes.c_int64, vp]
+        L.lpg_rope_tables.restype = ctypes.c_int
+        L.lpg_rope_packed.argtypes = [vp, vp, dp, vp, vp, ctypes.c_int32, vp]
+        L.lpg_rope_packed.restype = ctypes.c_int
         L.lpg_chain_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.c_int]
         L.lpg_chain_workspace_bytes.restype = ctypes.c_size_t
         L.lpg_chain.argtypes = [sp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp]
@@ -95,7 +102,8 @@ def lib():
 
 
 EXPORTS = ("lpg_packed_bytes", "lpg_layout_offset", "lpg_pack", "lpg_unpack", "lpg_gemm_packed",
-           "lpg_elementwise_packed", "lpg_softmax_packed", "lpg_chain_workspace_bytes", "lpg_chain", "lpg_last_error",
+           "lpg_elementwise_packed", "lpg_softmax_packed", "lpg_rmsnorm_packed", "lpg_rope_tables", "lpg_rope_packed",
+           "lpg_chain_workspace_bytes", "lpg_chain", "lpg_last_error",
            "lpg_version")
 
 
@@ -166,6 +174,18 @@ def lpg_softmax_packed(x, out, d, scale=1.0, causal=False, stream=None):
     return _check(lib().lpg_softmax_packed(_ptr(x), _ptr(out), ctypes.byref(d), scale, int(bool(causal)), stream))
 
 
+def lpg_rmsnorm_packed(x, weight, out, d, eps, stream=None):
+    return _check(lib().lpg_rmsnorm_packed(_ptr(x), _ptr(weight), _ptr(out), ctypes.byref(d), eps, stream))
+
+
+def lpg_rope_tables(cos_t, sin_t, rows, head_dim, base=10000.0, pos0=0, stream=None):
+    return _check(lib().lpg_rope_tables(_ptr(cos_t), _ptr(sin_t), rows, head_dim, base, pos0, stream))
+
+
+def lpg_rope_packed(x, out, d, cos_t, sin_t, head_dim, stream=None):
+    return _check(lib().lpg_rope_packed(_ptr(x), _ptr(out), ctypes.byref(d), _ptr(cos_t), _ptr(sin_t), head_dim, stream))
+
+
 def stage_array(stages):
     arr = (lpg_stage * len(stages))()
     for i, s in enumerate(stages):
@@ -219,4 +239,18 @@ def stage_softmax(x, out, d, scale=1.0, causal=False):
     s = lpg_stage()
     s.type, s.op, s.scalar = LPG_STAGE_SOFTMAX, int(bool(causal)), scale
     s.in0, s.out, s.out_d = _ptr(x), _ptr(out), d
+    return s
+
+
+def stage_rmsnorm(x, weight, out, d, eps):
+    s = lpg_stage()
+    s.type, s.scalar = LPG_STAGE_RMSNORM, eps
+    s.in0, s.in1, s.out, s.out_d = _ptr(x), _ptr(weight), _ptr(out), d
+    return s
+
+
+def stage_rope(x, out, d, cos_t, sin_t, head_dim):
+    s = lpg_stage()
+    s.type, s.op = LPG_STAGE_ROPE, head_dim
+    s.in0, s.in1, s.in2, s.out, s.out_d = _ptr(x), _ptr(cos_t), _ptr(sin_t), _ptr(out), d
     return s

@@ -319,7 +319,72 @@ def build_decoder_layer(inp, shape, fused=False):
     return ch
 
 
-BUILDERS = {"two_gemm": build_two_gemm, "mlp": build_mlp, "attention": build_attention,
+def build_llama_layer(inp, shape, fused=False):
+    """The decoder layer with every step between its GEMMs on the packed layout: RMSNorm, Q/K/V
+    projections, RoPE on Q and K, causal softmax attention with grouped keys/values, output
+    projection + residual, RMSNorm, gated MLP + residual.  bf16 intermediates, fp32 math.
+    fused=True folds SiLU(gate)*up into the up projection's epilogue."""
+    t, hid, nq, nkv, ffn = shape["t"], shape["hidden"], shape["n_q"], shape["n_kv"], shape["ffn"]
+    eps, base = 1.0 / shape["inv_eps"], float(shape["rope_base"])
+    dh = hid // nq
+    kvw = nkv * dh
+    rep = nq // nkv
+    if dh % 64:
+        raise ValueError("bf16 head slices need head_dim to be a multiple of 64")
+    flops = (2 * t * hid * (hid + 2 * kvw) + nq * 4 * t * t * dh + 2 * t * hid * hid + 3 * 2 * t * hid * ffn)
+    ch = Chain("llama_layer", shape, flops)
+    B = LPG_BF16
+    x = ch.inputs["X"] = device_array(inp["X"])
+    for nm in ("Wq", "Wk", "Wv", "Wo", "Wg", "Wu", "Wd"):
+        ch.pack_weight(nm, inp[nm], LPG_PACKED_B, B)
+    wd = {nm: ch.bufs[nm][1] for nm in ("Wq", "Wk", "Wv", "Wo", "Wg", "Wu", "Wd")}
+    wt = {nm: ch.bufs[nm][0] for nm in wd}
+    n1, n2 = device_array(inp["norm1"]), device_array(inp["norm2"])
+    cos_t = torch.empty((t, dh // 2), dtype=torch.float32, device=_dev())
+    sin_t = torch.empty_like(cos_t)
+    api.lpg_rope_tables(cos_t, sin_t, t, dh, base, 0, _stream())          # constants of the model, like the weights
+    torch.cuda.synchronize()
+    ch.consts = (n1, n2, cos_t, sin_t)
+    hd = desc(LPG_PACKED_A, B, t, hid)
+    kd = desc(LPG_PACKED_A, B, t, kvw)          # K written as a left-operand image, read as K_g^T
+    vd = desc(LPG_PACKED_B, B, t, kvw)
+    gd = desc(LPG_PACKED_A, B, t, ffn)
+    sd = desc(LPG_PACKED_A, B, t, t, batch=nq, batch_stride=_packed_elems(B, t, t))
+    px, ph1, pq, po, pa, ph2, py = (ch.new_packed(n_, hd) for n_ in ("X", "h1", "Q", "O", "A", "h2", "Y"))
+    pk, pv, ps = ch.new_packed("K", kd), ch.new_packed("V", vd), ch.new_packed("S", sd)
+    pg, pact = ch.new_packed("gate", gd), ch.new_packed("act", gd)
+    out = ch.outputs["Y"] = torch.empty((t, hid), dtype=torch.float32, device=_dev())
+    rm = desc(LPG_ROW_MAJOR, LPG_F32, t, hid)
+
+    ch.add(api.stage_pack(x, rm, px, hd))
+    ch.add(api.stage_rmsnorm(px, n1, ph1, hd, eps))
+    ch.add(api.stage_gemm(1.0, ph1, hd, wt["Wq"], wd["Wq"], 0.0, None, pq, hd))
+    ch.add(api.stage_gemm(1.0, ph1, hd, wt["Wk"], wd["Wk"], 0.0, None, pk, kd))
+    ch.add(api.stage_gemm(1.0, ph1, hd, wt["Wv"], wd["Wv"], 0.0, None, pv, vd))
+    ch.add(api.stage_rope(pq, pq, hd, cos_t, sin_t, dh))
+    ch.add(api.stage_rope(pk, pk, kd, cos_t, sin_t, dh))
+    q_view = desc(LPG_PACKED_A, B, t, dh, parent=(t, hid), batch=nq, batch_step=(0, dh))
+    kt_view = desc(LPG_PACKED_B, B, dh, t, parent=(kvw, t), batch=nq, batch_div=rep, batch_step=(dh, 0))
+    v_view = desc(LPG_PACKED_B, B, t, dh, parent=(t, kvw), batch=nq, batch_div=rep, batch_step=(0, dh))
+    o_view = desc(LPG_PACKED_A, B, t, dh, parent=(t, hid), batch=nq, batch_step=(0, dh))
+    ch.add(api.stage_gemm(1.0, pq, q_view, pk, kt_view, 0.0, None, ps, sd))
+    ch.add(api.stage_softmax(ps, ps, sd, 1.0 / float(np.sqrt(dh)), True))
+    ch.add(api.stage_gemm(1.0, ps, sd, pv, v_view, 0.0, None, po, o_view))
+    ch.add(api.stage_gemm(1.0, po, hd, wt["Wo"], wd["Wo"], 1.0, px, pa, hd))           # + residual X
+    ch.add(api.stage_rmsnorm(pa, n2, ph2, hd, eps))
+    ch.add(api.stage_gemm(1.0, ph2, hd, wt["Wg"], wd["Wg"], 0.0, None, pg, gd))
+    if fused:
+        ch.add(api.stage_gemm(1.0, ph2, hd, wt["Wu"], wd["Wu"], 0.0, None, pact, gd, api.LPG_EPI_GATE_SILU, pg))
+    else:
+        pu = ch.new_packed("up", gd)
+        ch.add(api.stage_gemm(1.0, ph2, hd, wt["Wu"], wd["Wu"], 0.0, None, pu, gd))
+        ch.add(api.stage_elementwise(LPG_EW_SILU_MUL, pg, pu, 0.0, pact, gd))
+    ch.add(api.stage_gemm(1.0, pact, gd, wt["Wd"], wd["Wd"], 1.0, pa, py, hd))           # + residual A
+    ch.add(api.stage_unpack(py, hd, out, rm))
+    return ch
+
+
+BUILDERS = {"llama_layer": build_llama_layer, "two_gemm": build_two_gemm, "mlp": build_mlp, "attention": build_attention,
             "deep_chain": build_deep_chain, "decoder_layer": build_decoder_layer}
 
 

@@ -384,51 +384,123 @@ static int do_elementwise(int op, const void *x0, const void *x1, float s, void 
     return LPG_OK;
 }
 
-// ---------------------------------------------------------------------------- softmax
+// ------------------------------------------------- softmax / RMS normalisation / RoPE
 
-static int do_softmax(const void *x, void *out, const lpg_desc *d, float scale, int causal, hipStream_t st,
-                      bool launch)
+// Shared by the row operations: resolve x/out under descriptor d (PACKED_A or ROW_MAJOR).
+struct RowTarget {
+    bool packed;
+    const char *x;
+    char *out;
+    int64_t kbs, row_stride, slot;
+    int32_t ngroups, nkb;
+};
+static int make_row_target(const char *what, const void *x, void *out, const lpg_desc *d, RowTarget *t)
 {
-    int rc = check_common(d, "lpg_softmax_packed");
+    int rc = check_common(d, what);
     if (rc) return rc;
     if (d->kind != LPG_PACKED_A && d->kind != LPG_ROW_MAJOR)
-        return fail(LPG_EUNSUPPORTED, "lpg_softmax_packed: kind %d (rows must be the free index: PACKED_A, or ROW_MAJOR)", d->kind);
-    if (bdiv(d) != 1) return fail(LPG_EUNSUPPORTED, "lpg_softmax_packed: batch_div must be 1");
-    if (!x || !out) return fail(LPG_EINVAL, "lpg_softmax_packed: NULL pointer");
-    SoftmaxArgs a{};
-    const bool packed = d->kind == LPG_PACKED_A;
-    if (packed) {
+        return fail(LPG_EUNSUPPORTED, "%s: kind %d (rows must be the free index: PACKED_A, or ROW_MAJOR)", what, d->kind);
+    if (bdiv(d) != 1) return fail(LPG_EUNSUPPORTED, "%s: batch_div must be 1", what);
+    if (!x || !out) return fail(LPG_EINVAL, "%s: NULL pointer", what);
+    *t = RowTarget{};
+    t->packed = d->kind == LPG_PACKED_A;
+    if (t->packed) {
         PView v;
-        rc = make_pview(d, "lpg_softmax_packed", &v);
+        rc = make_pview(d, what, &v);
         if (rc) return rc;
-        if ((uintptr_t)x % 16 || (uintptr_t)out % 16)
-            return fail(LPG_EALIGN, "lpg_softmax_packed: packed buffers must be 16-byte aligned");
-        a.x = (const char *)x + v.origin;
-        a.out = (char *)out + v.origin;
-        a.kbs = v.kb_stride;
-        a.slot = v.slot_step;
-        a.ngroups = (int32_t)((v.F + 31) / 32);
-        a.nkb = (int32_t)((v.K + kb_of(v.dtype) - 1) / kb_of(v.dtype));
-        if ((int64_t)v.batch * a.ngroups * 4 > 0x7fffffff) return fail(LPG_EUNSUPPORTED, "lpg_softmax_packed: too many row groups");
+        if ((uintptr_t)x % 16 || (uintptr_t)out % 16) return fail(LPG_EALIGN, "%s: packed buffers must be 16-byte aligned", what);
+        t->x = (const char *)x + v.origin;
+        t->out = (char *)out + v.origin;
+        t->kbs = v.kb_stride;
+        t->slot = v.slot_step;
+        t->ngroups = (int32_t)((v.F + 31) / 32);
+        t->nkb = (int32_t)((v.K + kb_of(v.dtype) - 1) / kb_of(v.dtype));
+        if ((int64_t)v.batch * t->ngroups * 4 > 0x7fffffff) return fail(LPG_EUNSUPPORTED, "%s: too many row groups", what);
     } else {
         CView v;
-        rc = make_cview(d, "lpg_softmax_packed", &v);
+        rc = make_cview(d, what, &v);
         if (rc) return rc;
-        if ((uintptr_t)x % v.es || (uintptr_t)out % v.es) return fail(LPG_EALIGN, "lpg_softmax_packed: misaligned buffer");
-        a.x = (const char *)x + v.origin * v.es;
-        a.out = (char *)out + v.origin * v.es;
-        a.row_stride = v.row_stride * v.es;
-        a.slot = v.slot_step * v.es;
-        if ((int64_t)v.batch * d->rows > 0x7fffffff) return fail(LPG_EUNSUPPORTED, "lpg_softmax_packed: too many rows");
+        if ((uintptr_t)x % v.es || (uintptr_t)out % v.es) return fail(LPG_EALIGN, "%s: misaligned buffer", what);
+        t->x = (const char *)x + v.origin * v.es;
+        t->out = (char *)out + v.origin * v.es;
+        t->row_stride = v.row_stride * v.es;
+        t->slot = v.slot_step * v.es;
+        if ((int64_t)v.batch * d->rows > 0x7fffffff) return fail(LPG_EUNSUPPORTED, "%s: too many rows", what);
     }
+    return LPG_OK;
+}
+
+static int do_row_op(int op, const void *x, const void *weight, void *out, const lpg_desc *d, float scalar, int causal,
+                     hipStream_t st, bool launch)
+{
+    const char *what = op == kRowSoftmax ? "lpg_softmax_packed" : "lpg_rmsnorm_packed";
+    RowTarget t;
+    int rc = make_row_target(what, x, out, d, &t);
+    if (rc) return rc;
+    if (op == kRowSoftmax && !(scalar > 0.0f && scalar <= 3.0e38f))
+        return fail(LPG_EINVAL, "%s: scale must be positive and finite", what);
+    if (op == kRowRmsNorm) {
+        if (!weight) return fail(LPG_EINVAL, "%s: NULL weight", what);
+        if ((uintptr_t)weight % 4) return fail(LPG_EALIGN, "%s: misaligned weight", what);
+        if (!(scalar >= 0.0f)) return fail(LPG_EINVAL, "%s: eps must be >= 0", what);
+    }
+    RowArgs a{};
+    a.x = t.x;
+    a.out = t.out;
+    a.weight = (const float *)weight;
+    a.kbs = t.kbs;
+    a.row_stride = t.row_stride;
+    a.slot = t.slot;
     a.rows = (int32_t)d->rows;
     a.cols = (int32_t)d->cols;
+    a.ngroups = t.ngroups;
+    a.nkb = t.nkb;
     a.batch = nbatch(d);
     a.causal = causal != 0;
-    a.scale_log2e = (float)((double)scale * 1.4426950408889634);
+    a.scalar = op == kRowSoftmax ? (float)((double)scalar * 1.4426950408889634) : scalar;
     if (!launch) return LPG_OK;
-    hipError_t e = launch_softmax(a, d->dtype, packed, st);
-    if (e != hipSuccess) return fail(LPG_EHIP, "lpg_softmax_packed: %s", hipGetErrorString(e));
+    hipError_t e = launch_row_op(a, op, d->dtype, t.packed, st);
+    if (e != hipSuccess) return fail(LPG_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return LPG_OK;
+}
+
+static int do_rope(const void *x, void *out, const lpg_desc *d, const void *cos_t, const void *sin_t, int head_dim,
+                   hipStream_t st, bool launch)
+{
+    const char *what = "lpg_rope_packed";
+    RowTarget t;
+    int rc = make_row_target(what, x, out, d, &t);
+    if (rc) return rc;
+    if (!cos_t || !sin_t) return fail(LPG_EINVAL, "%s: NULL table", what);
+    if ((uintptr_t)cos_t % 16 || (uintptr_t)sin_t % 16) return fail(LPG_EALIGN, "%s: tables must be 16-byte aligned", what);
+    if (head_dim <= 0 || head_dim % 2) return fail(LPG_EINVAL, "%s: head_dim must be a positive even number", what);
+    if (d->cols % head_dim) return fail(LPG_EINVAL, "%s: cols %lld is not a multiple of head_dim %d", what, (long long)d->cols, head_dim);
+    RopeArgs a{};
+    a.x = t.x;
+    a.out = t.out;
+    a.cos_t = (const float *)cos_t;
+    a.sin_t = (const float *)sin_t;
+    a.kbs = t.kbs;
+    a.row_stride = t.row_stride;
+    a.slot = t.slot;
+    a.rows = (int32_t)d->rows;
+    a.nheads = (int32_t)(d->cols / head_dim);
+    a.half = head_dim / 2;
+    a.ngroups = t.ngroups;
+    a.batch = nbatch(d);
+    if (t.packed) {
+        // a head's two halves must be whole fragments apart
+        const int kf = d->dtype == LPG_F32 ? 8 : 16;
+        if (head_dim % (2 * kf))
+            return fail(LPG_EUNSUPPORTED, "%s: packed %s needs head_dim to be a multiple of %d", what,
+                        d->dtype == LPG_F32 ? "fp32" : "bf16", 2 * kf);
+        a.fph = head_dim / (2 * kf);
+        a.nlo = a.nheads * a.fph;
+        a.npad = out == x ? 0 : t.nkb * kFragsPerBlock - 2 * a.nlo;
+    }
+    if (!launch) return LPG_OK;
+    hipError_t e = launch_rope(a, d->dtype, t.packed, st);
+    if (e != hipSuccess) return fail(LPG_EHIP, "%s: %s", what, hipGetErrorString(e));
     return LPG_OK;
 }
 
@@ -480,6 +552,22 @@ static size_t twin_bytes(const lpg_desc *p)
     return (desc_bytes(&c) + 255) / 256 * 256;
 }
 
+static inline bool is_row_stage(int type)
+{
+    return type == LPG_STAGE_SOFTMAX || type == LPG_STAGE_RMSNORM || type == LPG_STAGE_ROPE;
+}
+
+// A softmax / RMS normalisation / RoPE stage on buffers x, out under descriptor d (the
+// stage's own, or their row-major twins in the canonical control).
+static int run_row_stage(const lpg_stage &s, const void *x, void *out, const lpg_desc *d, hipStream_t hs, bool launch)
+{
+    switch (s.type) {
+        case LPG_STAGE_SOFTMAX: return do_row_op(kRowSoftmax, x, nullptr, out, d, s.scalar, s.op, hs, launch);
+        case LPG_STAGE_RMSNORM: return do_row_op(kRowRmsNorm, x, s.in1, out, d, s.scalar, 0, hs, launch);
+        default: return do_rope(x, out, d, s.in1, s.in2, s.op, hs, launch);
+    }
+}
+
 static bool later_reads(const lpg_stage *st, int n, int from, const void *buf, bool *by_compute)
 {
     bool any = false;
@@ -490,7 +578,7 @@ static bool later_reads(const lpg_stage *st, int n, int from, const void *buf, b
                            (s.type == LPG_STAGE_ELEMENTWISE && s.in1 == buf);
         if (reads) {
             any = true;
-            if (s.type == LPG_STAGE_GEMM || s.type == LPG_STAGE_ELEMENTWISE || s.type == LPG_STAGE_SOFTMAX) *by_compute = true;
+            if (s.type != LPG_STAGE_PACK && s.type != LPG_STAGE_UNPACK) *by_compute = true;
         }
         if (s.out == buf) break;  // overwritten from here on
     }
@@ -518,7 +606,9 @@ static int validate_stage(const lpg_stage &s, int i)
         case LPG_STAGE_ELEMENTWISE:
             return do_elementwise(s.op, s.in0, s.in1, s.scalar, s.out, &s.out_d, nullptr, false);
         case LPG_STAGE_SOFTMAX:
-            return do_softmax(s.in0, s.out, &s.out_d, s.scalar, s.op, nullptr, false);
+        case LPG_STAGE_RMSNORM:
+        case LPG_STAGE_ROPE:
+            return run_row_stage(s, s.in0, s.out, &s.out_d, nullptr, false);
         default:
             return fail(LPG_EINVAL, "lpg_chain: stage %d has unknown type %d", i, s.type);
     }
@@ -540,7 +630,7 @@ static int check_links(const lpg_stage *st, int n)
         } else if (s.type == LPG_STAGE_ELEMENTWISE) {
             ins[ni++] = {s.in0, &s.out_d};
             if (s.in1) ins[ni++] = {s.in1, &s.out_d};
-        } else if (s.type == LPG_STAGE_SOFTMAX) {
+        } else if (is_row_stage(s.type)) {
             ins[ni++] = {s.in0, &s.out_d};
         } else if (s.type == LPG_STAGE_UNPACK) {
             ins[ni++] = {s.in0, &s.in0_d};
@@ -574,7 +664,9 @@ static int run_stage(const lpg_stage &s, hipStream_t hs)
         case LPG_STAGE_GEMM:
             return do_gemm(s.alpha, s.in0, &s.in0_d, s.in1, &s.in1_d, s.beta, s.in2, s.out, &s.out_d, s.op, s.epi_arg,
                            hs, true);
-        case LPG_STAGE_SOFTMAX: return do_softmax(s.in0, s.out, &s.out_d, s.scalar, s.op, hs, true);
+        case LPG_STAGE_SOFTMAX:
+        case LPG_STAGE_RMSNORM:
+        case LPG_STAGE_ROPE: return run_row_stage(s, s.in0, s.out, &s.out_d, hs, true);
         default: return do_elementwise(s.op, s.in0, s.in1, s.scalar, s.out, &s.out_d, hs, true);
     }
 }
@@ -632,8 +724,8 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
 
     for (int i = 0; i < n; ++i) {
         const lpg_stage &s = st[i];
-        if (s.type == LPG_STAGE_ELEMENTWISE || s.type == LPG_STAGE_SOFTMAX) {
-            const bool sm = s.type == LPG_STAGE_SOFTMAX;
+        if (s.type == LPG_STAGE_ELEMENTWISE || is_row_stage(s.type)) {
+            const bool sm = is_row_stage(s.type);  // one layout-bound input (tables, weights are plain arrays)
             Slot *s0 = find(s.in0), *s1 = (!sm && s.in1) ? find(s.in1) : nullptr;
             const size_t tb = is_packed(s.out_d.kind) ? twin_bytes(&s.out_d) : 0;
             const bool canon_in = s0 && s0->canonical_live && s0->bytes == tb &&
@@ -650,7 +742,7 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
                 if (!dry) {
                     int rc;
                     if (sm) {
-                        rc = do_softmax(s0->canon, so->canon, &c, s.scalar, s.op, hs, true);
+                        rc = run_row_stage(s, s0->canon, so->canon, &c, hs, true);
                     } else {
                         c.ld = 0;
                         rc = do_elementwise(s.op, s0->canon, s1 ? s1->canon : nullptr, s.scalar, so->canon, &c, hs, true);
@@ -679,8 +771,7 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
             int rc = run_stage(s, hs);
             if (rc) return rc;
         }
-        if ((s.type == LPG_STAGE_GEMM || s.type == LPG_STAGE_ELEMENTWISE || s.type == LPG_STAGE_SOFTMAX) &&
-            is_packed(s.out_d.kind)) {
+        if (s.type != LPG_STAGE_PACK && s.type != LPG_STAGE_UNPACK && is_packed(s.out_d.kind)) {
             bool by_compute = false;
             later_reads(st, n, i + 1, s.out, &by_compute);
             if (by_compute) {
@@ -766,7 +857,31 @@ int lpg_elementwise_packed(int op, const void *x0, const void *x1, float s, void
 
 int lpg_softmax_packed(const void *x, void *out, const lpg_desc *d, float scale, int causal, void *stream)
 {
-    return do_softmax(x, out, d, scale, causal, (hipStream_t)stream, true);
+    return do_row_op(kRowSoftmax, x, nullptr, out, d, scale, causal, (hipStream_t)stream, true);
+}
+
+int lpg_rmsnorm_packed(const void *x, const float *weight, void *out, const lpg_desc *d, float eps, void *stream)
+{
+    return do_row_op(kRowRmsNorm, x, weight, out, d, eps, 0, (hipStream_t)stream, true);
+}
+
+int lpg_rope_tables(float *cos_t, float *sin_t, int64_t rows, int32_t head_dim, double base, int64_t pos0, void *stream)
+{
+    if (rows < 0 || head_dim <= 0 || head_dim % 2 || !(base > 0.0))
+        return fail(LPG_EINVAL, "lpg_rope_tables: need rows >= 0, an even positive head_dim and base > 0");
+    if (rows == 0) return LPG_OK;
+    if (!cos_t || !sin_t) return fail(LPG_EINVAL, "lpg_rope_tables: NULL table");
+    if ((uintptr_t)cos_t % 4 || (uintptr_t)sin_t % 4) return fail(LPG_EALIGN, "lpg_rope_tables: misaligned table");
+    if (rows * (head_dim / 2) > ((int64_t)1 << 38)) return fail(LPG_EUNSUPPORTED, "lpg_rope_tables: table too large");
+    hipError_t e = launch_rope_tables(cos_t, sin_t, rows, head_dim, base, (double)pos0, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(LPG_EHIP, "lpg_rope_tables: %s", hipGetErrorString(e));
+    return LPG_OK;
+}
+
+int lpg_rope_packed(const void *x, void *out, const lpg_desc *d, const float *cos_t, const float *sin_t,
+                    int32_t head_dim, void *stream)
+{
+    return do_rope(x, out, d, cos_t, sin_t, head_dim, (hipStream_t)stream, true);
 }
 
 size_t lpg_chain_workspace_bytes(const lpg_stage *stages, int n, int mode)

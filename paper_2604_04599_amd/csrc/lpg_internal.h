@@ -93,9 +93,12 @@ struct EwArgs {
     float s;
 };
 
-struct SoftmaxArgs {
+// Row operations (softmax, RMS normalisation) on a packed left operand or a row-major matrix.
+enum { kRowSoftmax = 0, kRowRmsNorm = 1 };
+struct RowArgs {
     const char *x;       // buffer + origin (bytes applied)
     char *out;
+    const float *weight; // RMS normalisation: per-column weights
     int64_t kbs;         // packed: bytes between K blocks
     int64_t row_stride;  // canonical: bytes between rows
     int64_t slot;        // bytes per slot
@@ -103,8 +106,20 @@ struct SoftmaxArgs {
     int32_t ngroups;     // packed: ceil(rows/32)
     int32_t nkb;         // packed: ceil(cols/KB)
     int32_t batch;
-    int32_t causal;
-    float scale_log2e;   // scale * log2(e)
+    int32_t causal;      // softmax
+    float scalar;        // softmax: scale * log2(e); RMS normalisation: eps
+};
+
+struct RopeArgs {
+    const char *x;       // buffer + origin (bytes applied)
+    char *out;
+    const float *cos_t, *sin_t;  // [rows][half]
+    int64_t kbs, row_stride, slot;
+    int32_t rows, nheads, half;  // half = head_dim / 2
+    int32_t ngroups, batch;
+    int32_t fph;         // packed: fragments per half head
+    int32_t nlo;         // packed: fragment pairs per 32-row group = nheads * fph
+    int32_t npad;        // packed: fragments of column padding to zero-fill (0 when in place)
 };
 
 // Launchers (lpg_kernels.hip).  Return hipError_t of the launch.
@@ -114,6 +129,9 @@ hipError_t launch_unpack(const PackArgs &a, int src_dtype, int dst_dtype, hipStr
 hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, int cfg, hipStream_t st);
 int choose_gemm_config(const GemmArgs &a, int in_dtype);
 hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st);
-hipError_t launch_softmax(const SoftmaxArgs &a, int dtype, bool packed, hipStream_t st);
+hipError_t launch_row_op(const RowArgs &a, int op, int dtype, bool packed, hipStream_t st);
+hipError_t launch_rope_tables(float *cos_t, float *sin_t, int64_t rows, int head_dim, double base, double pos0,
+                              hipStream_t st);
+hipError_t launch_rope(const RopeArgs &a, int dtype, bool packed, hipStream_t st);
 
 }  // namespace lpg

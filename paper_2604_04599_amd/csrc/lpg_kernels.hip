@@ -287,20 +287,11 @@ hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st)
 }
 
 // ---------------------------------------------------------------------------------
-// softmax over the contraction index of a packed left operand (row = free index), with
-// the scale and the optional causal mask of the attention block folded in.  Values are
-// v = x * scale * log2(e); a row part is summarised as (m, s) = (max v, sum 2^(v - m)).
-// The maximum is taken over products x*sl, the exponent's argument is one fused
-// multiply-add fma(x, sl, -m): one rounding, and no product is kept between the passes.
+// Row operations on a packed left operand (row = free index, reduction along the
+// contraction index): softmax with the attention block's scale and causal mask folded in,
+// and RMS normalisation.  Both reduce a row to a pair of numbers, then rewrite the row.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr float kNegBig = -3.0e38f;  // "no element yet": finite, so differences never give NaN
-
-__device__ __forceinline__ void sm_merge(float &m, float &s, float m2, float s2)
-{
-    const float M = fmaxf(m, m2);
-    s = s * __builtin_amdgcn_exp2f(m - M) + s2 * __builtin_amdgcn_exp2f(m2 - M);
-    m = M;
-}
 
 // element v (< KV) of a 16-byte chunk, widened to fp32
 template <typename T>
@@ -312,6 +303,20 @@ __device__ __forceinline__ float chunk_elem(const u32x4 &c, int v)
         return (v & 1) ? __uint_as_float(c[v / 2] & 0xffff0000u) : __uint_as_float(c[v / 2] << 16);
     }
 }
+// KV fp32 results -> one 16-byte chunk of T (bf16: round to nearest even)
+template <typename T>
+__device__ __forceinline__ u32x4 chunk_from(const float (&e)[T::KV])
+{
+    if constexpr (T::ES == 4) {
+        return (u32x4){__float_as_uint(e[0]), __float_as_uint(e[1]), __float_as_uint(e[2]), __float_as_uint(e[3])};
+    } else {
+        return (u32x4){bf16_pack2(e[0], e[1]), bf16_pack2(e[2], e[3]), bf16_pack2(e[4], e[5]), bf16_pack2(e[6], e[7])};
+    }
+}
+// column of chunk element v relative to the chunk's first: packed chunks hold k0 + 8*(v/4) + v%4
+// (a lane's share of a fragment half), chunks cut from a row-major row (LINEAR) hold k0 + v
+template <bool LINEAR>
+__device__ __forceinline__ constexpr int chunk_k(int v) { return LINEAR ? v : 8 * (v / 4) + v % 4; }
 
 // Makes the compiler treat the chunks as new values (no instruction is emitted), so that it
 // re-derives widened elements from the 16-byte chunks in the next pass instead of keeping
@@ -323,6 +328,114 @@ __device__ __forceinline__ void forget_derived(u32x4 (&buf)[N])
     for (int i = 0; i < N; ++i) asm volatile("" : "+v"(buf[i]));
 }
 
+// Softmax policy.  Values are v = x * sl, sl = scale * log2(e) > 0; a row part is summarised
+// as (m, s) = (max v, sum 2^(v - m)).  Elements outside the kept columns are replaced by -inf
+// once, when a chunk arrives (`admit`): the passes then need no masks, a masked element
+// contributes 2^(-inf) = 0 to the sum and comes out as an exact 0.  The maximum is taken over
+// products x*sl, the exponent's argument is one fused multiply-add fma(x, sl, -m): one
+// rounding, and no product is kept between the passes.
+struct SoftmaxRow {
+    static constexpr bool kMasked = true;  // honours RowArgs::causal
+    float sl;
+    __device__ __forceinline__ explicit SoftmaxRow(const RowArgs &a) : sl(a.scalar) {}
+    __device__ __forceinline__ static void init(float &m, float &s) { m = kNegBig; s = 0.0f; }
+    __device__ __forceinline__ static void merge(float &m, float &s, float m2, float s2)
+    {
+        const float M = fmaxf(m, m2);
+        s = s * __builtin_amdgcn_exp2f(m - M) + s2 * __builtin_amdgcn_exp2f(m2 - M);
+        m = M;
+    }
+    // a chunk that is not loaded because all of it is masked: -inf in every element
+    template <typename T>
+    __device__ __forceinline__ static u32x4 absent()
+    {
+        constexpr uint32_t w = T::ES == 4 ? 0xff800000u : 0xff80ff80u;
+        return (u32x4){w, w, w, w};
+    }
+    // element v of the chunk sits in column k0 + chunk_k(v); columns > last become -inf
+    template <typename T, bool LINEAR>
+    __device__ __forceinline__ static u32x4 admit(u32x4 c, int k0, int last)
+    {
+        if constexpr (T::ES == 4) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) c[v] = (k0 + chunk_k<LINEAR>(v) <= last) ? c[v] : 0xff800000u;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t lo = (k0 + chunk_k<LINEAR>(2 * j) <= last) ? (c[j] & 0xffffu) : 0xff80u;
+                const uint32_t hi = (k0 + chunk_k<LINEAR>(2 * j + 1) <= last) ? (c[j] & 0xffff0000u) : 0xff800000u;
+                c[j] = lo | hi;
+            }
+        }
+        return c;
+    }
+    // folds admitted chunks buf[0..N) into (m, s)
+    template <typename T, int N>
+    __device__ __forceinline__ void fold(u32x4 (&buf)[N], float &m, float &s) const
+    {
+        float bm = m;
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+#pragma unroll
+            for (int v = 0; v < T::KV; ++v) bm = fmaxf(bm, chunk_elem<T>(buf[i], v) * sl);
+        forget_derived(buf);
+        float bs = 0.0f;
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+#pragma unroll
+            for (int v = 0; v < T::KV; ++v) bs += __builtin_amdgcn_exp2f(fmaf(chunk_elem<T>(buf[i], v), sl, -bm));
+        s = s * __builtin_amdgcn_exp2f(m - bm) + bs;
+        m = bm;
+    }
+    // (m, s) of the whole row -> the two constants `emit` uses
+    __device__ __forceinline__ void finish(float &m, float &s) const { s = s > 0.0f ? 1.0f / s : 0.0f; }
+    template <typename T, bool LINEAR>
+    __device__ __forceinline__ u32x4 emit(const u32x4 &c, int k0, int last, float m, float inv) const
+    {
+        float e[T::KV];
+#pragma unroll
+        for (int v = 0; v < T::KV; ++v) e[v] = __builtin_amdgcn_exp2f(fmaf(chunk_elem<T>(c, v), sl, -m)) * inv;
+        return chunk_from<T>(e);
+    }
+};
+
+// RMS normalisation policy: (sum of squares, unused) -> y = x * rsqrt(mean square + eps) * w[k].
+// Padding and chunks that are not loaded are zeros: no mask is needed.
+struct RmsNormRow {
+    static constexpr bool kMasked = false;
+    const float *w;
+    float eps, inv_n;
+    __device__ __forceinline__ explicit RmsNormRow(const RowArgs &a) : w(a.weight), eps(a.scalar), inv_n(1.0f / (float)a.cols) {}
+    __device__ __forceinline__ static void init(float &q, float &u) { q = 0.0f; u = 0.0f; }
+    __device__ __forceinline__ static void merge(float &q, float &u, float q2, float) { q += q2; }
+    template <typename T>
+    __device__ __forceinline__ static u32x4 absent() { return (u32x4){0u, 0u, 0u, 0u}; }
+    template <typename T, bool LINEAR>
+    __device__ __forceinline__ static u32x4 admit(u32x4 c, int, int) { return c; }
+    template <typename T, int N>
+    __device__ __forceinline__ void fold(u32x4 (&buf)[N], float &q, float &u) const
+    {
+        float acc = 0.0f;
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+#pragma unroll
+            for (int v = 0; v < T::KV; ++v) acc = fmaf(chunk_elem<T>(buf[i], v), chunk_elem<T>(buf[i], v), acc);
+        q += acc;
+    }
+    __device__ __forceinline__ void finish(float &q, float &u) const { q = 1.0f / sqrtf(q * inv_n + eps); }
+    template <typename T, bool LINEAR>
+    __device__ __forceinline__ u32x4 emit(const u32x4 &c, int k0, int last, float r, float) const
+    {
+        float e[T::KV];
+#pragma unroll
+        for (int v = 0; v < T::KV; ++v) {
+            const int k = k0 + chunk_k<LINEAR>(v);
+            e[v] = k <= last ? chunk_elem<T>(c, v) * r * w[k] : 0.0f;
+        }
+        return chunk_from<T>(e);
+    }
+};
+
 // A workgroup of NW waves owns R (32, 16 or 8) consecutive rows of one 32-row group over
 // the whole contraction range.  In every fragment half those rows are one contiguous run of
 // R*16 bytes; runs are numbered q = 8*kb + 2*c + h, a wave load covers 64/R consecutive runs
@@ -333,13 +446,15 @@ __device__ __forceinline__ void forget_derived(u32x4 (&buf)[N])
 // k0 + 8*(v/4) + v%4 with k0 = KB*kb + KF*c + 4*h.
 // CACHED: the R rows fit in 16 chunks per lane; they are read once, kept in registers
 // across the reduction and written once.  Otherwise the rows are streamed twice.
-template <typename T, int R, int NW, bool CACHED>
-__global__ __launch_bounds__(NW * 64) void softmax_packed_kernel(SoftmaxArgs a)
+template <typename T, typename OP, int R, int NW, bool CACHED>
+__global__ __launch_bounds__(NW * 64) void row_packed_kernel(RowArgs a)
 {
-    constexpr int RPW = 64 / R, NCH = 16, KV = T::KV;
+    constexpr int RPW = 64 / R, NCH = 16;
     constexpr int KBSTEP = NW * RPW / 8;  // K blocks a lane advances per load
+    constexpr int KINC = KBSTEP * T::KB;
     static_assert((NW * RPW) % 8 == 0, "a lane must stay on one fragment half");
-    __shared__ float red_m[NW][32], red_s[NW][32];
+    __shared__ float red_a[NW][32], red_b[NW][32];
+    OP op(a);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int rl = lane % R, rsel = lane / R;
     uint32_t wg = blockIdx.x;
@@ -347,7 +462,7 @@ __global__ __launch_bounds__(NW * 64) void softmax_packed_kernel(SoftmaxArgs a)
     wg /= (32 / R);
     const int g = wg % a.ngroups, b = wg / a.ngroups;
     const int row = 32 * g + sub * R + rl;
-    int last = a.causal ? row + (a.cols - a.rows) : a.cols - 1;  // last kept column of this row
+    int last = (OP::kMasked && a.causal) ? row + (a.cols - a.rows) : a.cols - 1;  // last kept column of this row
     last = last < a.cols - 1 ? last : a.cols - 1;
     if (row >= a.rows) last = -1;
     const int q0 = w * RPW + rsel;  // this lane's run in load 0
@@ -356,198 +471,309 @@ __global__ __launch_bounds__(NW * 64) void softmax_packed_kernel(SoftmaxArgs a)
     const int64_t base = (int64_t)b * a.slot + (int64_t)g * kBlockBytes + (sub * R + rl) * 16 +
                          (int64_t)(q0 >> 3) * a.kbs + (q0 & 7) * 512;
     const char *xp = a.x + base;
-    char *op = a.out + base;
+    char *outp = a.out + base;
     const int64_t step = (int64_t)KBSTEP * a.kbs;
-    const float sl = a.scale_log2e;
     const int nbatches = CACHED ? 1 : (a.nkb + NCH * KBSTEP - 1) / (NCH * KBSTEP);
 
     u32x4 buf[NCH];
-    float m = kNegBig, s = 0.0f;
+    float ra, rb;
+    OP::init(ra, rb);
     for (int bt = 0; bt < nbatches; ++bt) {
-        const int k0b = kfirst + bt * NCH * KBSTEP * T::KB;
+        const int k0b = kfirst + bt * NCH * KINC;
         const char *xb = xp + (int64_t)bt * NCH * step;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            buf[i] = (u32x4){0u, 0u, 0u, 0u};
-            if (k0b + i * KBSTEP * T::KB <= last) buf[i] = *(const u32x4 *)(xb + i * step);  // last < kend
+            buf[i] = OP::template absent<T>();
+            if (k0b + i * KINC <= last) buf[i] = *(const u32x4 *)(xb + i * step);  // last < kend
         }
-        float bm = m;
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            const int k0 = k0b + i * KBSTEP * T::KB;
-#pragma unroll
-            for (int v = 0; v < KV; ++v)
-                bm = (k0 + 8 * (v / 4) + v % 4 <= last) ? fmaxf(bm, chunk_elem<T>(buf[i], v) * sl) : bm;
-        }
+        for (int i = 0; i < NCH; ++i) buf[i] = OP::template admit<T, false>(buf[i], k0b + i * KINC, last);
         forget_derived(buf);
-        float bs = 0.0f;
-#pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            const int k0 = k0b + i * KBSTEP * T::KB;
-#pragma unroll
-            for (int v = 0; v < KV; ++v)
-                bs += (k0 + 8 * (v / 4) + v % 4 <= last) ? __builtin_amdgcn_exp2f(fmaf(chunk_elem<T>(buf[i], v), sl, -bm)) : 0.0f;
-        }
-        s = s * __builtin_amdgcn_exp2f(m - bm) + bs;
-        m = bm;
+        op.template fold<T>(buf, ra, rb);
     }
     // lanes l, l^R, l^2R, ... hold parts of the same row; then the NW waves
 #pragma unroll
-    for (int off = R; off < 64; off <<= 1) sm_merge(m, s, __shfl_xor(m, off, 64), __shfl_xor(s, off, 64));
+    for (int off = R; off < 64; off <<= 1) OP::merge(ra, rb, __shfl_xor(ra, off, 64), __shfl_xor(rb, off, 64));
     if (lane < R) {
-        red_m[w][lane] = m;
-        red_s[w][lane] = s;
+        red_a[w][lane] = ra;
+        red_b[w][lane] = rb;
     }
     __syncthreads();
-    m = red_m[0][rl];
-    s = red_s[0][rl];
+    ra = red_a[0][rl];
+    rb = red_b[0][rl];
 #pragma unroll
-    for (int ww = 1; ww < NW; ++ww) sm_merge(m, s, red_m[ww][rl], red_s[ww][rl]);
-    const float inv = s > 0.0f ? 1.0f / s : 0.0f;
+    for (int ww = 1; ww < NW; ++ww) OP::merge(ra, rb, red_a[ww][rl], red_b[ww][rl]);
+    op.finish(ra, rb);
     forget_derived(buf);
 
     for (int bt = 0; bt < nbatches; ++bt) {
-        const int k0b = kfirst + bt * NCH * KBSTEP * T::KB;
+        const int k0b = kfirst + bt * NCH * KINC;
         const char *xb = xp + (int64_t)bt * NCH * step;
-        char *ob = op + (int64_t)bt * NCH * step;
+        char *ob = outp + (int64_t)bt * NCH * step;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int k0 = k0b + i * KBSTEP * T::KB;
+            const int k0 = k0b + i * KINC;
             if constexpr (!CACHED) {
-                buf[i] = (u32x4){0u, 0u, 0u, 0u};
+                buf[i] = OP::template absent<T>();
                 if (k0 <= last) buf[i] = *(const u32x4 *)(xb + i * step);
+                buf[i] = OP::template admit<T, false>(buf[i], k0, last);
             }
-            float e[KV];
-#pragma unroll
-            for (int v = 0; v < KV; ++v)
-                e[v] = (k0 + 8 * (v / 4) + v % 4 <= last) ? __builtin_amdgcn_exp2f(fmaf(chunk_elem<T>(buf[i], v), sl, -m)) * inv : 0.0f;
-            u32x4 o;
-            if constexpr (T::ES == 4) {
-                o = (u32x4){__float_as_uint(e[0]), __float_as_uint(e[1]), __float_as_uint(e[2]), __float_as_uint(e[3])};
-            } else {
-                o = (u32x4){bf16_pack2(e[0], e[1]), bf16_pack2(e[2], e[3]), bf16_pack2(e[4], e[5]), bf16_pack2(e[6], e[7])};
-            }
+            const u32x4 o = op.template emit<T, false>(buf[i], k0, last, ra, rb);
             if (k0 < kend) *(u32x4 *)(ob + i * step) = o;
         }
     }
 }
 
-// The same operation on a row-major matrix: one workgroup per row, lanes along the row
-// (16-byte chunks when VEC says rows start and end on 16-byte boundaries).  The row is
-// read twice; the second read comes from cache for rows of ordinary length.
+// KV consecutive elements of a row-major row starting at column j, as one chunk (columns
+// >= cols read as zero); VEC: one 16-byte access.
 template <typename T, bool VEC>
-__global__ __launch_bounds__(256) void softmax_rows_kernel(SoftmaxArgs a)
+__device__ __forceinline__ u32x4 row_chunk_load(const typename T::raw *xp, int j, int cols)
 {
-    typedef typename T::raw raw;
-    constexpr int CH = VEC ? T::KV : 1;
-    __shared__ float red_m[4], red_s[4];
-    const int row = blockIdx.x % a.rows, b = blockIdx.x / a.rows;
-    int last = a.causal ? row + (a.cols - a.rows) : a.cols - 1;
-    last = last < a.cols - 1 ? last : a.cols - 1;
-    const int64_t base = (int64_t)b * a.slot + (int64_t)row * a.row_stride;
-    const raw *xp = (const raw *)(a.x + base);
-    raw *op = (raw *)(a.out + base);
-    const float sl = a.scale_log2e;
-    auto widen = [](raw r) {
-        if constexpr (T::ES == 4) return __uint_as_float(r); else return bf16_to_f32(r);
-    };
-
-    float m = kNegBig, s = 0.0f;
-    for (int j = threadIdx.x * CH; j <= last; j += 256 * CH) {
-        raw r[CH];
-        if constexpr (VEC) {
-            const u32x4 c = *(const u32x4 *)(xp + j);
-            __builtin_memcpy(r, &c, 16);
-        } else {
-            r[0] = xp[j];
-        }
-        float bm = m;
+    if constexpr (VEC) {
+        return *(const u32x4 *)(xp + j);
+    } else {
+        typename T::raw r[T::KV];
 #pragma unroll
-        for (int v = 0; v < CH; ++v) bm = (j + v <= last) ? fmaxf(bm, widen(r[v]) * sl) : bm;
-        float bs = 0.0f;
-#pragma unroll
-        for (int v = 0; v < CH; ++v) bs += (j + v <= last) ? __builtin_amdgcn_exp2f(fmaf(widen(r[v]), sl, -bm)) : 0.0f;
-        s = s * __builtin_amdgcn_exp2f(m - bm) + bs;
-        m = bm;
+        for (int v = 0; v < T::KV; ++v) r[v] = j + v < cols ? xp[j + v] : (typename T::raw)0;
+        u32x4 c;
+        __builtin_memcpy(&c, r, 16);
+        return c;
     }
+}
+template <typename T, bool VEC>
+__device__ __forceinline__ void row_chunk_store(typename T::raw *op, int j, int cols, const u32x4 &c)
+{
+    if constexpr (VEC) {
+        *(u32x4 *)(op + j) = c;
+    } else {
+        typename T::raw r[T::KV];
+        __builtin_memcpy(r, &c, 16);
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) sm_merge(m, s, __shfl_xor(m, off, 64), __shfl_xor(s, off, 64));
-    if ((threadIdx.x & 63) == 0) {
-        red_m[threadIdx.x >> 6] = m;
-        red_s[threadIdx.x >> 6] = s;
-    }
-    __syncthreads();
-    m = red_m[0];
-    s = red_s[0];
-#pragma unroll
-    for (int ww = 1; ww < 4; ++ww) sm_merge(m, s, red_m[ww], red_s[ww]);
-    const float inv = s > 0.0f ? 1.0f / s : 0.0f;
-
-    for (int j = threadIdx.x * CH; j < a.cols; j += 256 * CH) {
-        raw r[CH] = {};
-        if (j <= last) {
-            if constexpr (VEC) {
-                const u32x4 c = *(const u32x4 *)(xp + j);
-                __builtin_memcpy(r, &c, 16);
-            } else {
-                r[0] = xp[j];
-            }
-        }
-        float e[CH];
-#pragma unroll
-        for (int v = 0; v < CH; ++v)
-            e[v] = (j + v <= last) ? __builtin_amdgcn_exp2f(fmaf(widen(r[v]), sl, -m)) * inv : 0.0f;
-        if constexpr (!VEC) {
-            if constexpr (T::ES == 4) op[j] = __float_as_uint(e[0]); else op[j] = (raw)bf16_rne(e[0]);
-        } else if constexpr (T::ES == 4) {
-            *(u32x4 *)(op + j) = (u32x4){__float_as_uint(e[0]), __float_as_uint(e[1]), __float_as_uint(e[2]), __float_as_uint(e[3])};
-        } else {
-            *(u32x4 *)(op + j) = (u32x4){bf16_pack2(e[0], e[1]), bf16_pack2(e[2], e[3]), bf16_pack2(e[4], e[5]), bf16_pack2(e[6], e[7])};
-        }
+        for (int v = 0; v < T::KV; ++v)
+            if (j + v < cols) op[j + v] = r[v];
     }
 }
 
-template <typename T>
-static hipError_t launch_softmax_dtype(const SoftmaxArgs &a, bool packed, hipStream_t st)
+// The same operations on a row-major matrix, for the canonical-layout control: one
+// workgroup per row, lanes along the row in chunks of KV elements (one 16-byte access when
+// VEC says rows start and end on 16-byte boundaries).  The row is read twice; the second
+// read comes from cache for rows of ordinary length.
+template <typename T, typename OP, bool VEC>
+__global__ __launch_bounds__(256) void row_major_kernel(RowArgs a)
+{
+    typedef typename T::raw raw;
+    constexpr int KV = T::KV;
+    __shared__ float red_a[4], red_b[4];
+    const OP op(a);
+    const int row = blockIdx.x % a.rows, b = blockIdx.x / a.rows;
+    int last = (OP::kMasked && a.causal) ? row + (a.cols - a.rows) : a.cols - 1;
+    last = last < a.cols - 1 ? last : a.cols - 1;
+    const int64_t base = (int64_t)b * a.slot + (int64_t)row * a.row_stride;
+    const raw *xp = (const raw *)(a.x + base);
+    raw *outp = (raw *)(a.out + base);
+
+    float ra, rb;
+    OP::init(ra, rb);
+    for (int j = threadIdx.x * KV; j <= last; j += 256 * KV) {
+        u32x4 c[1] = {OP::template admit<T, true>(row_chunk_load<T, VEC>(xp, j, a.cols), j, last)};
+        op.template fold<T>(c, ra, rb);
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) OP::merge(ra, rb, __shfl_xor(ra, off, 64), __shfl_xor(rb, off, 64));
+    if ((threadIdx.x & 63) == 0) {
+        red_a[threadIdx.x >> 6] = ra;
+        red_b[threadIdx.x >> 6] = rb;
+    }
+    __syncthreads();
+    ra = red_a[0];
+    rb = red_b[0];
+#pragma unroll
+    for (int ww = 1; ww < 4; ++ww) OP::merge(ra, rb, red_a[ww], red_b[ww]);
+    op.finish(ra, rb);
+
+    for (int j = threadIdx.x * KV; j < a.cols; j += 256 * KV) {
+        u32x4 c = OP::template absent<T>();
+        if (j <= last) c = OP::template admit<T, true>(row_chunk_load<T, VEC>(xp, j, a.cols), j, last);
+        row_chunk_store<T, VEC>(outp, j, a.cols, op.template emit<T, true>(c, j, last, ra, rb));
+    }
+}
+
+template <typename T, typename OP>
+static hipError_t launch_row_dtype(const RowArgs &a, bool packed, hipStream_t st)
 {
     if (!packed) {
         const int64_t grid = (int64_t)a.batch * a.rows;
         const bool vec = ((uintptr_t)a.x | (uintptr_t)a.out | (uint64_t)a.row_stride | (uint64_t)a.slot |
                           (uint64_t)((int64_t)a.cols * T::ES)) % 16 == 0;
         if (vec)
-            hipLaunchKernelGGL((softmax_rows_kernel<T, true>), dim3((unsigned)grid), dim3(256), 0, st, a);
+            hipLaunchKernelGGL((row_major_kernel<T, OP, true>), dim3((unsigned)grid), dim3(256), 0, st, a);
         else
-            hipLaunchKernelGGL((softmax_rows_kernel<T, false>), dim3((unsigned)grid), dim3(256), 0, st, a);
+            hipLaunchKernelGGL((row_major_kernel<T, OP, false>), dim3((unsigned)grid), dim3(256), 0, st, a);
         return hipGetLastError();
     }
     // Variants: rows per workgroup, waves, cached.  A cached variant holds rows of up to
-    // 128 * waves / R K blocks (16 chunks a lane).  LPG_SOFTMAX_VARIANT=<n> pins the choice
-    // if that variant can hold the rows (a tuning aid).
+    // 128 * waves / R K blocks (16 chunks a lane).  LPG_ROW_VARIANT=<n> pins the choice if
+    // that variant can hold the rows (a tuning aid).
     struct Variant { int r, nw; bool cached; };
     static const Variant kVariants[] = {{32, 8, true}, {16, 8, true}, {8, 8, true}, {8, 16, true},
                                         {8, 8, false}};
     auto fits = [&](int v) { return !kVariants[v].cached || kVariants[v].r * a.nkb <= 128 * kVariants[v].nw; };
     int variant = fits(0) ? 0 : fits(1) ? 1 : fits(2) ? 2 : fits(3) ? 3 : 4;
-    if (const char *f = getenv("LPG_SOFTMAX_VARIANT")) {
+    if (const char *f = getenv("LPG_ROW_VARIANT")) {
         const int v = atoi(f);
         if (v >= 0 && v < 5 && fits(v)) variant = v;
     }
     const unsigned grid = (unsigned)((int64_t)a.batch * a.ngroups * (32 / kVariants[variant].r));
     const dim3 block(kVariants[variant].nw * 64);
     switch (variant) {
-        case 0: hipLaunchKernelGGL((softmax_packed_kernel<T, 32, 8, true>), dim3(grid), block, 0, st, a); break;
-        case 1: hipLaunchKernelGGL((softmax_packed_kernel<T, 16, 8, true>), dim3(grid), block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL((softmax_packed_kernel<T, 8, 8, true>), dim3(grid), block, 0, st, a); break;
-        case 3: hipLaunchKernelGGL((softmax_packed_kernel<T, 8, 16, true>), dim3(grid), block, 0, st, a); break;
-        default: hipLaunchKernelGGL((softmax_packed_kernel<T, 8, 8, false>), dim3(grid), block, 0, st, a); break;
+        case 0: hipLaunchKernelGGL((row_packed_kernel<T, OP, 32, 8, true>), dim3(grid), block, 0, st, a); break;
+        case 1: hipLaunchKernelGGL((row_packed_kernel<T, OP, 16, 8, true>), dim3(grid), block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL((row_packed_kernel<T, OP, 8, 8, true>), dim3(grid), block, 0, st, a); break;
+        case 3: hipLaunchKernelGGL((row_packed_kernel<T, OP, 8, 16, true>), dim3(grid), block, 0, st, a); break;
+        default: hipLaunchKernelGGL((row_packed_kernel<T, OP, 8, 8, false>), dim3(grid), block, 0, st, a); break;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_softmax(const SoftmaxArgs &a, int dtype, bool packed, hipStream_t st)
+hipError_t launch_row_op(const RowArgs &a, int op, int dtype, bool packed, hipStream_t st)
 {
     if (a.batch <= 0 || a.rows <= 0 || a.cols <= 0) return hipSuccess;
-    return dtype == LPG_F32 ? launch_softmax_dtype<F32>(a, packed, st) : launch_softmax_dtype<BF16>(a, packed, st);
+    if (op == kRowSoftmax)
+        return dtype == LPG_F32 ? launch_row_dtype<F32, SoftmaxRow>(a, packed, st) : launch_row_dtype<BF16, SoftmaxRow>(a, packed, st);
+    return dtype == LPG_F32 ? launch_row_dtype<F32, RmsNormRow>(a, packed, st) : launch_row_dtype<BF16, RmsNormRow>(a, packed, st);
+}
+
+// ---------------------------------------------------------------------------------
+// Rotary position embedding.  Tables: angle(t, i) = (pos0 + t) * base^(-2i/head_dim) in
+// fp64, cos and sin rounded to fp32, row-major [rows][head_dim/2].
+__global__ __launch_bounds__(256) void rope_tables_kernel(float *cos_t, float *sin_t, int64_t n, int half, double base,
+                                                          double pos0)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n) return;
+    const int64_t t = idx / half;
+    const int i = (int)(idx % half);
+    const double ang = (pos0 + (double)t) * pow(base, -(double)i / (double)half);
+    cos_t[idx] = (float)cos(ang);
+    sin_t[idx] = (float)sin(ang);
+}
+
+hipError_t launch_rope_tables(float *cos_t, float *sin_t, int64_t rows, int head_dim, double base, double pos0,
+                              hipStream_t st)
+{
+    const int64_t n = rows * (head_dim / 2);
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(rope_tables_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, cos_t, sin_t, n,
+                       head_dim / 2, base, pos0);
+    return hipGetLastError();
+}
+
+// On a packed left operand (row = position, columns = heads x head_dim).  Element i of a
+// head's first half pairs with element i of its second half, head_dim/2 columns further:
+// a whole number of fragments (the host checks head_dim % (2*KF) == 0), so the partner of
+// a lane's chunk is the same lane's chunk of another fragment, and one wave rotates a
+// fragment pair with four coalesced 1 KiB accesses.  Rows are the interleaved dimension
+// of the layout: 32 positions rotate at once, each lane with its own row of the tables.
+// Fragments numbered fk = k / KF over the whole row; a task is (slot, 32-row group, j):
+// j < nlo rotates a pair, larger j zero-fills a fragment of column padding (out != x only).
+template <typename T>
+__global__ __launch_bounds__(256) void rope_packed_kernel(RopeArgs a)
+{
+    constexpr int KV = T::KV;
+    const int lane = threadIdx.x & 63;
+    const int h = lane >> 5, fl = lane & 31;
+    const int64_t per_group = a.nlo + a.npad;
+    const int64_t ntasks = (int64_t)a.batch * a.ngroups * per_group;
+    for (int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); task < ntasks; task += (int64_t)gridDim.x * 4) {
+        const int j = (int)(task % per_group);
+        const int64_t gb = task / per_group;
+        const int g = (int)(gb % a.ngroups), b = (int)(gb / a.ngroups);
+        const int64_t base = (int64_t)b * a.slot + (int64_t)g * kBlockBytes + lane * 16;
+        if (j >= a.nlo) {
+            const int fk = 2 * a.nlo + (j - a.nlo);
+            *(u32x4 *)(a.out + base + (int64_t)(fk >> 2) * a.kbs + (fk & 3) * kFragBytes) = (u32x4){0u, 0u, 0u, 0u};
+            continue;
+        }
+        const int head = j / a.fph, wi = j % a.fph;
+        const int fk_lo = head * 2 * a.fph + wi, fk_hi = fk_lo + a.fph;
+        const int64_t off_lo = base + (int64_t)(fk_lo >> 2) * a.kbs + (fk_lo & 3) * kFragBytes;
+        const int64_t off_hi = base + (int64_t)(fk_hi >> 2) * a.kbs + (fk_hi & 3) * kFragBytes;
+        const u32x4 lo = *(const u32x4 *)(a.x + off_lo), hi = *(const u32x4 *)(a.x + off_hi);
+        const int row = 32 * g + fl;
+        const int trow = row < a.rows ? row : a.rows - 1;  // padding rows: any valid table row, result unused
+        const int i0 = wi * T::KF + 4 * h;
+        const float *cp = a.cos_t + (int64_t)trow * a.half + i0, *sp = a.sin_t + (int64_t)trow * a.half + i0;
+        float c[KV], s[KV];
+#pragma unroll
+        for (int q = 0; q < KV / 4; ++q) {
+            const f32x4 cq = *(const f32x4 *)(cp + 8 * q), sq = *(const f32x4 *)(sp + 8 * q);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                c[4 * q + v] = cq[v];
+                s[4 * q + v] = sq[v];
+            }
+        }
+        float elo[KV], ehi[KV];
+#pragma unroll
+        for (int v = 0; v < KV; ++v) {
+            const float x0 = chunk_elem<T>(lo, v), x1 = chunk_elem<T>(hi, v);
+            elo[v] = row < a.rows ? fmaf(x0, c[v], -(x1 * s[v])) : 0.0f;
+            ehi[v] = row < a.rows ? fmaf(x1, c[v], x0 * s[v]) : 0.0f;
+        }
+        *(u32x4 *)(a.out + off_lo) = chunk_from<T>(elo);
+        *(u32x4 *)(a.out + off_hi) = chunk_from<T>(ehi);
+    }
+}
+
+// Row-major twin for the control chain: one thread per pair, lanes along a head's half.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_rows_kernel(RopeArgs a)
+{
+    typedef typename T::raw raw;
+    const int64_t per_row = (int64_t)a.nheads * a.half;
+    const int64_t n = (int64_t)a.batch * a.rows * per_row;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * 256) {
+        const int64_t p = idx % per_row, rb = idx / per_row;
+        const int i = (int)(p % a.half), head = (int)(p / a.half);
+        const int row = (int)(rb % a.rows), b = (int)(rb / a.rows);
+        const int64_t base = (int64_t)b * a.slot + (int64_t)row * a.row_stride;
+        const raw *xp = (const raw *)(a.x + base) + head * 2 * a.half + i;
+        raw *outp = (raw *)(a.out + base) + head * 2 * a.half + i;
+        float x0, x1;
+        if constexpr (T::ES == 4) {
+            x0 = __uint_as_float(xp[0]);
+            x1 = __uint_as_float(xp[a.half]);
+        } else {
+            x0 = bf16_to_f32(xp[0]);
+            x1 = bf16_to_f32(xp[a.half]);
+        }
+        const float c = a.cos_t[(int64_t)row * a.half + i], s = a.sin_t[(int64_t)row * a.half + i];
+        const float y0 = fmaf(x0, c, -(x1 * s)), y1 = fmaf(x1, c, x0 * s);
+        if constexpr (T::ES == 4) {
+            outp[0] = __float_as_uint(y0);
+            outp[a.half] = __float_as_uint(y1);
+        } else {
+            outp[0] = (raw)(bf16_pack2(y0, 0.0f) & 0xffffu);
+            outp[a.half] = (raw)(bf16_pack2(y1, 0.0f) & 0xffffu);
+        }
+    }
+}
+
+hipError_t launch_rope(const RopeArgs &a, int dtype, bool packed, hipStream_t st)
+{
+    if (a.batch <= 0 || a.rows <= 0 || a.nheads <= 0) return hipSuccess;
+    int64_t work = packed ? ((int64_t)a.batch * a.ngroups * (a.nlo + a.npad) + 3) / 4
+                          : ((int64_t)a.batch * a.rows * a.nheads * a.half + 255) / 256;
+    if (work > 256 * 32) work = 256 * 32;
+    const dim3 grid((unsigned)work), block(256);
+    if (packed) {
+        if (dtype == LPG_F32) hipLaunchKernelGGL(rope_packed_kernel<F32>, grid, block, 0, st, a);
+        else hipLaunchKernelGGL(rope_packed_kernel<BF16>, grid, block, 0, st, a);
+    } else {
+        if (dtype == LPG_F32) hipLaunchKernelGGL(rope_rows_kernel<F32>, grid, block, 0, st, a);
+        else hipLaunchKernelGGL(rope_rows_kernel<BF16>, grid, block, 0, st, a);
+    }
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------

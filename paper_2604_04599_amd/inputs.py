@@ -15,6 +15,11 @@ Workloads (full sizes; every shape key can be overridden for small tests):
                  made bf16-representable by clearing the low 16 bits of the fp32
                  pattern           t=4096 hidden=2048 n_q=32 n_kv=8 ffn=8192
 Seeds are 1001..1005 in that order (numpy PCG64).
+
+A sixth workload outside the benchmark set, `llama_layer` (seed 1006), is the decoder
+layer with everything between its GEMMs present: the decoder_layer inputs plus the two
+RMS-normalisation weight vectors norm1, norm2 [hidden] ~ N(1, std 0.1); the shape dict
+also carries the integer RoPE base (500000) and 1/eps (100000).
 """
 import numpy as np
 
@@ -28,10 +33,13 @@ FULL_SHAPES = {
     "decoder_layer": {"t": 4096, "hidden": 2048, "n_q": 32, "n_kv": 8, "ffn": 8192},
 }
 
+FULL_SHAPES["llama_layer"] = dict(FULL_SHAPES["decoder_layer"], rope_base=500000, inv_eps=100000)
+
 SEEDS = {name: 1001 + i for i, name in enumerate(WORKLOADS)}
+SEEDS["llama_layer"] = 1006
 
 DTYPES = {"two_gemm": "f32", "mlp": "f32", "attention": "f32", "deep_chain": "f32",
-          "decoder_layer": "bf16"}
+          "decoder_layer": "bf16", "llama_layer": "bf16"}
 
 
 def shape_of(name, **over):
@@ -81,7 +89,7 @@ def make(name, seed=None, **over):
         n, depth = s["n"], s["depth"]
         inp = {"C0": _uniform(r, (n, n)),
                "B": [_uniform(r, (n, n)) / np.float32(np.sqrt(n)) for _ in range(depth)]}
-    elif name == "decoder_layer":
+    elif name in ("decoder_layer", "llama_layer"):
         t, hid, nq, nkv, ffn = s["t"], s["hidden"], s["n_q"], s["n_kv"], s["ffn"]
         if hid % nq or nq % nkv:
             raise ValueError("hidden must divide into n_q heads and n_q into n_kv groups")
@@ -92,6 +100,9 @@ def make(name, seed=None, **over):
                "Wg": _normal(r, (hid, ffn), 0.02), "Wu": _normal(r, (hid, ffn), 0.02),
                "Wd": _normal(r, (ffn, hid), 0.02)}
         inp = {k: _bf16_representable(v) for k, v in inp.items()}
+        if name == "llama_layer":
+            inp["norm1"] = (1.0 + _normal(r, (hid,), 0.1)).astype(np.float32)
+            inp["norm2"] = (1.0 + _normal(r, (hid,), 0.1)).astype(np.float32)
     else:
         raise KeyError(name)
     return inp, s
@@ -108,7 +119,7 @@ def gemm_flops(name, s):
         return s["heads"] * 2 * 2 * s["t"] * s["t"] * s["dh"]
     if name == "deep_chain":
         return s["depth"] * 2 * s["n"] ** 3
-    if name == "decoder_layer":
+    if name in ("decoder_layer", "llama_layer"):
         t, hid, ffn = s["t"], s["hidden"], s["ffn"]
         dh = hid // s["n_q"]
         kvw = s["n_kv"] * dh

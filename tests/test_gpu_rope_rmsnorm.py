@@ -1,0 +1,195 @@
+"""GPU parity of lpg_rope_tables / lpg_rope_packed / lpg_rmsnorm_packed against the fp64 oracle,
+and of the whole decoder-layer chain that uses them (RMSNorm, RoPE, causal softmax, residuals).
+
+Tolerances (fp32 math on the device, fp64 in the oracle):
+  tables   cos/sin computed in fp64 and rounded once: |diff| <= 1.2e-7 (one fp32 ulp at 1).
+  RoPE     one product and one fused multiply-add per output: |diff| <= 4e-7 * (|a| + |b|).
+  RMSNorm  fp32 sum of squares over up to 8300 terms (rel. error <~ 1e-6), rsqrt, two products:
+           |diff| <= 1e-5 * |want|.
+  bf16 results add half an ulp of bf16: 4e-3 * |want|.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref, workloads
+from paper_2604_04599_amd import api, chains, inputs
+from paper_2604_04599_amd.api import (LPG_BF16, LPG_CHAIN_CANONICAL, LPG_CHAIN_PROPAGATED, LPG_F32, LPG_PACKED_A,
+                                      LPG_ROW_MAJOR, desc)
+from gpu_util import NP_RAW, bf16_raw_to_f64, dev_bytes, dev_empty, host, pack_dev, stream, unpack_dev
+
+pytestmark = pytest.mark.gpu
+
+BF16_REL = 4e-3
+
+
+def dev_f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+@pytest.mark.parametrize("rows,head_dim,base,pos0", [(300, 64, 10000.0, 0), (128, 128, 500000.0, 4000), (1, 2, 2.0, 7)])
+def test_rope_tables(rows, head_dim, base, pos0):
+    cos_t = torch.full((rows, head_dim // 2), float("nan"), device="cuda")
+    sin_t = torch.full_like(cos_t, float("nan"))
+    api.lpg_rope_tables(cos_t, sin_t, rows, head_dim, base, pos0, stream())
+    th = ref.rope_angles(np.arange(rows) + pos0, head_dim, base)
+    torch.cuda.synchronize()
+    assert np.abs(cos_t.cpu().numpy().astype(np.float64) - np.cos(th)).max() <= 1.2e-7
+    assert np.abs(sin_t.cpu().numpy().astype(np.float64) - np.sin(th)).max() <= 1.2e-7
+
+
+def tables(rows, head_dim, pos0=0):
+    th = ref.rope_angles(np.arange(rows) + pos0, head_dim)
+    c, s = np.cos(th).astype(np.float32), np.sin(th).astype(np.float32)
+    return c, s
+
+
+# (rows, heads, head_dim): ragged rows, several heads, a column count that leaves whole padding
+# fragments (48 fp32 columns of 64, 96 bf16 columns of 128), head_dim 128
+ROPE_SHAPES = {LPG_F32: [(33, 3, 16), (100, 4, 64), (64, 2, 128), (70, 5, 32)],
+               LPG_BF16: [(33, 3, 32), (100, 4, 64), (64, 2, 128)]}
+
+
+@pytest.mark.parametrize("dtype", [LPG_F32, LPG_BF16])
+def test_packed_rope_matches_oracle(dtype):
+    for rows, heads, dh in ROPE_SHAPES[dtype]:
+        rng = np.random.default_rng(rows + heads + dh)
+        x = rng.standard_normal((rows, heads * dh)).astype(np.float32)
+        c, s = tables(rows, dh, pos0=3)
+        px, d = pack_dev(x, LPG_PACKED_A, dtype)
+        xin = unpack_dev(px, d)
+        out = dev_empty(api.lpg_packed_bytes(d), fill=0xA5)
+        ct, st_ = dev_f32(c), dev_f32(s)
+        api.lpg_rope_packed(px, out, d, ct, st_, dh, stream())
+        got = unpack_dev(out, d)
+        want = ref.rope(xin, c.astype(np.float64), s.astype(np.float64), dh)
+        half = dh // 2
+        mag = np.abs(xin).reshape(rows, heads, 2, half).sum(axis=2, keepdims=True).repeat(2, axis=2).reshape(rows, -1)
+        tol = 4e-7 * mag + (BF16_REL * np.abs(want) if dtype == LPG_BF16 else 0.0)
+        assert np.all(np.abs(got - want) <= tol), (rows, heads, dh)
+        raw = host(out, NP_RAW[dtype])
+        assert np.count_nonzero(raw) == np.count_nonzero(got)          # padding rows and columns are zero
+        api.lpg_rope_packed(px, px, d, ct, st_, dh, stream())             # in place: same bytes
+        assert np.array_equal(host(px, NP_RAW[dtype]), raw)
+
+
+@pytest.mark.parametrize("dtype", [LPG_F32, LPG_BF16])
+def test_row_major_rope_matches_oracle(dtype):
+    rows, heads, dh, ld = 37, 3, 24, 80
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((2, rows, ld)).astype(np.float32)
+    raw = ref.bf16_bits(x.view(np.uint32)) if dtype == LPG_BF16 else x.view(np.uint32)
+    xin = bf16_raw_to_f64(raw) if dtype == LPG_BF16 else x.astype(np.float64)
+    c, s = tables(rows, dh)
+    d = desc(LPG_ROW_MAJOR, dtype, rows, heads * dh, ld=ld, batch=2, batch_stride=rows * ld)
+    src, out = dev_bytes(raw), dev_empty(raw.nbytes, fill=0xA5)
+    api.lpg_rope_packed(src, out, d, dev_f32(c), dev_f32(s), dh, stream())
+    got_raw = host(out, NP_RAW[dtype], raw.shape)
+    got = bf16_raw_to_f64(got_raw) if dtype == LPG_BF16 else got_raw.view(np.float32).astype(np.float64)
+    for b in range(2):
+        want = ref.rope(xin[b, :, :heads * dh], c.astype(np.float64), s.astype(np.float64), dh)
+        tol = 2e-6 + (BF16_REL * np.abs(want) if dtype == LPG_BF16 else 0.0)
+        assert np.all(np.abs(got[b, :, :heads * dh] - want) <= tol)
+    assert np.all(got_raw[:, :, heads * dh:] == (0xA5A5 if dtype == LPG_BF16 else 0xA5A5A5A5))
+
+
+RMS_SHAPES = [(1, 1), (33, 70), (100, 1000), (64, 2048), (40, 3000), (33, 4200), (33, 8300)]
+
+
+@pytest.mark.parametrize("dtype", [LPG_F32, LPG_BF16])
+@pytest.mark.parametrize("rows,cols", RMS_SHAPES)
+def test_packed_rmsnorm_matches_oracle(rows, cols, dtype):
+    rng = np.random.default_rng(rows * 31 + cols)
+    x = (rng.standard_normal((rows, cols)) * 2).astype(np.float32)
+    w = (1 + 0.2 * rng.standard_normal(cols)).astype(np.float32)
+    px, d = pack_dev(x, LPG_PACKED_A, dtype)
+    xin = unpack_dev(px, d)
+    out = dev_empty(api.lpg_packed_bytes(d), fill=0xA5)
+    wt = dev_f32(w)
+    api.lpg_rmsnorm_packed(px, wt, out, d, 1e-5, stream())
+    got = unpack_dev(out, d)
+    want = ref.rmsnorm(xin, w.astype(np.float64), 1e-5)
+    rel = 1e-5 + (BF16_REL if dtype == LPG_BF16 else 0.0)
+    assert np.all(np.abs(got - want) <= rel * np.abs(want) + 1e-30)
+    raw = host(out, NP_RAW[dtype])
+    assert np.count_nonzero(raw) == np.count_nonzero(got)
+    api.lpg_rmsnorm_packed(px, wt, px, d, 1e-5, stream())
+    assert np.array_equal(host(px, NP_RAW[dtype]), raw)
+
+
+@pytest.mark.parametrize("dtype", [LPG_F32, LPG_BF16])
+@pytest.mark.parametrize("rows,cols,ld", [(5, 7, 0), (33, 1000, 1003), (16, 4096, 0)])
+def test_row_major_rmsnorm_matches_oracle(rows, cols, ld, dtype):
+    rng = np.random.default_rng(rows + cols)
+    stride = ld or cols
+    x = rng.standard_normal((2, rows, stride)).astype(np.float32)
+    w = (1 + 0.2 * rng.standard_normal(cols)).astype(np.float32)
+    raw = ref.bf16_bits(x.view(np.uint32)) if dtype == LPG_BF16 else x.view(np.uint32)
+    xin = bf16_raw_to_f64(raw) if dtype == LPG_BF16 else x.astype(np.float64)
+    d = desc(LPG_ROW_MAJOR, dtype, rows, cols, ld=ld, batch=2, batch_stride=rows * stride)
+    src, out = dev_bytes(raw), dev_empty(raw.nbytes, fill=0xA5)
+    api.lpg_rmsnorm_packed(src, dev_f32(w), out, d, 1e-6, stream())
+    got_raw = host(out, NP_RAW[dtype], raw.shape)
+    got = bf16_raw_to_f64(got_raw) if dtype == LPG_BF16 else got_raw.view(np.float32).astype(np.float64)
+    rel = 1e-5 + (BF16_REL if dtype == LPG_BF16 else 0.0)
+    for b in range(2):
+        want = ref.rmsnorm(xin[b, :, :cols], w.astype(np.float64), 1e-6)
+        assert np.all(np.abs(got[b, :, :cols] - want) <= rel * np.abs(want) + 1e-30)
+    assert np.all(got_raw[:, :, cols:] == (0xA5A5 if dtype == LPG_BF16 else 0xA5A5A5A5))
+
+
+def _check_llama(inp, shape, ch, y, rows):
+    nq, nkv = shape["n_q"], shape["n_kv"]
+    eps, base = 1.0 / shape["inv_eps"], float(shape["rope_base"])
+    sel = slice(None) if rows is None else rows
+    want = workloads.llama_layer(inp, nq, nkv, eps=eps, rope_base=base, rows=rows)
+    got = {n: ch.fetch(n) for n in ("h1", "Q", "K", "V", "O", "A", "h2", "act")}
+    for n in ("h1", "K", "V"):
+        assert ref.rel_frobenius(got[n], want[n]) <= 2e-2, n
+    for n in ("Q", "O", "A", "h2", "act"):
+        assert ref.rel_frobenius(got[n][sel], want[n]) <= 2e-2, n
+    assert ref.rel_frobenius(y[sel], want["Y"]) <= 2e-2
+    # stage-local, on the device's own (bf16-exact) intermediates
+    assert ref.rel_frobenius(got["h1"], ref.rmsnorm(inp["X"], inp["norm1"], eps)) <= 3e-3
+    assert ref.rel_frobenius(got["h2"][sel], ref.rmsnorm(got["A"][sel], inp["norm2"], eps)) <= 3e-3
+    th = ref.rope_angles(np.arange(shape["t"]), shape["hidden"] // nq, base)
+    k_local = ref.rope(ref.round_bf16(ref.gemm(got["h1"], inp["Wk"])), np.cos(th), np.sin(th), shape["hidden"] // nq)
+    assert ref.rel_frobenius(got["K"], k_local) <= 5e-3
+    assert ref.rel_frobenius(got["A"][sel], ref.gemm(got["O"][sel], inp["Wo"], beta=1.0, C=inp["X"][sel])) <= 3e-3
+    return want
+
+
+def test_llama_layer_small_both_modes():
+    inp, shape = inputs.make("llama_layer", t=192, hidden=256, n_q=4, n_kv=2, ffn=320)
+    ch = chains.build("llama_layer", inp, shape)
+    ch.run(LPG_CHAIN_PROPAGATED)
+    y = ch.output("Y").copy()
+    want = _check_llama(inp, shape, ch, y, None)
+    # the probabilities, per head, against the oracle's on the device's own Q and K
+    p, q, k = ch.fetch("S"), ch.fetch("Q"), ch.fetch("K")
+    dh = shape["hidden"] // shape["n_q"]
+    for h in range(shape["n_q"]):
+        g = h // (shape["n_q"] // shape["n_kv"])
+        s = ref.round_bf16(ref.gemm(q[:, h * dh:(h + 1) * dh].copy(), k[:, g * dh:(g + 1) * dh].T.copy()))
+        assert ref.rel_frobenius(p[h], ref.softmax_rows(s, scale=dh ** -0.5, causal=True)) <= 5e-3
+        assert np.all(np.triu(p[h], 1) == 0.0)
+    # canonical control: same result up to the summation order of its row-major kernels
+    ch.outputs["Y"].fill_(float("nan"))
+    ch.run(LPG_CHAIN_CANONICAL)
+    canon = ch.output("Y").copy()
+    assert ref.rel_frobenius(canon, want["Y"]) <= 2e-2
+    assert ref.rel_frobenius(canon, y) <= 1e-2
+    # fused SiLU epilogue variant: `up` is never rounded to bf16 there, so equal to rounding only
+    fch = chains.build("llama_layer", inp, shape, fused=True)
+    fch.run(LPG_CHAIN_PROPAGATED)
+    assert ref.rel_frobenius(fch.output("Y"), want["Y"]) <= 2e-2
+    assert ref.rel_frobenius(fch.output("Y"), y) <= 1e-2
+
+
+def test_llama_layer_full_size_sampled_rows():
+    inp, shape = inputs.make("llama_layer")
+    ch = chains.build("llama_layer", inp, shape)
+    ch.run(LPG_CHAIN_PROPAGATED)
+    y = ch.output("Y").copy()
+    rows = np.arange(11, shape["t"], 409)
+    _check_llama(inp, shape, ch, y, rows)

@@ -117,6 +117,21 @@ def test_descriptor_errors_are_caught_on_the_host():
     assert _err(api.lpg_softmax_packed, fake, fake + 8, pa, 1.0, False) == api.LPG_EALIGN
     assert _err(api.lpg_softmax_packed, fake, fake, desc(LPG_PACKED_A, LPG_F32, 32, 32, parent=(64, 64), origin=(0, 16)),
                 1.0, False) == api.LPG_EALIGN
+    assert _err(api.lpg_softmax_packed, fake, fake, pa, 0.0, False) == api.LPG_EINVAL          # scale must be > 0
+    assert _err(api.lpg_softmax_packed, fake, fake, pa, float("inf"), False) == api.LPG_EINVAL
+    # RMS normalisation and RoPE share the softmax's descriptor rules and add their own
+    assert _err(api.lpg_rmsnorm_packed, fake, None, fake, pa, 1e-5) == api.LPG_EINVAL           # no weight
+    assert _err(api.lpg_rmsnorm_packed, fake, fake, fake, pa, -1.0) == api.LPG_EINVAL
+    assert _err(api.lpg_rmsnorm_packed, fake, fake, fake, pb, 1e-5) == api.LPG_EUNSUPPORTED
+    assert _err(api.lpg_rope_packed, fake, fake, pa, fake, fake, 48) == api.LPG_EINVAL          # 64 cols, head_dim 48
+    assert _err(api.lpg_rope_packed, fake, fake, pa, fake, fake, 8) == api.LPG_EUNSUPPORTED     # halves < one fragment
+    assert _err(api.lpg_rope_packed, fake, fake, desc(LPG_PACKED_A, LPG_BF16, 64, 64), fake, fake, 16) == api.LPG_EUNSUPPORTED
+    assert _err(api.lpg_rope_packed, fake, fake, pa, fake + 4, fake, 16) == api.LPG_EALIGN
+    assert _err(api.lpg_rope_packed, fake, fake, pa, None, fake, 16) == api.LPG_EINVAL
+    assert _err(api.lpg_rope_packed, fake, fake, pa, fake, fake, 15) == api.LPG_EINVAL
+    assert _err(api.lpg_rope_tables, fake, fake, 8, 7, 10000.0, 0) == api.LPG_EINVAL
+    assert _err(api.lpg_rope_tables, fake, fake, 8, 8, -1.0, 0) == api.LPG_EINVAL
+    assert _err(api.lpg_rope_tables, None, fake, 8, 8, 10000.0, 0) == api.LPG_EINVAL
 
 
 def test_chain_link_check_and_workspace():

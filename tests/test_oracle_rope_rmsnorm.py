@@ -58,3 +58,20 @@ def test_rmsnorm_closed_forms():
     c = ref.rmsnorm(np.full((1, 8), 2.0), np.ones(8), 5.0)
     assert np.allclose(c, 2.0 / 3.0, rtol=1e-15)
     assert np.array_equal(ref.rmsnorm(np.zeros((1, 4)), np.ones(4), 1e-6), np.zeros((1, 4)))
+
+
+def test_llama_layer_row_sampling_equals_the_full_computation():
+    from oracle import workloads
+    from paper_2604_04599_amd import inputs
+    inp, shape = inputs.make("llama_layer", t=24, hidden=64, n_q=4, n_kv=2, ffn=96)
+    full = workloads.llama_layer(inp, 4, 2)
+    rows = np.array([0, 5, 23])
+    part = workloads.llama_layer(inp, 4, 2, rows=rows)
+    for n in ("Q", "O", "A", "h2", "act", "Y"):
+        assert np.allclose(part[n], full[n][rows], rtol=1e-12, atol=1e-14), n
+    assert np.array_equal(part["K"], full["K"])
+    # the layer is causal: changing a later token leaves earlier outputs alone
+    inp2 = dict(inp)
+    inp2["X"] = inp["X"].copy()
+    inp2["X"][10:] += 1.0
+    assert np.allclose(workloads.llama_layer(inp2, 4, 2)["Y"][:10], full["Y"][:10], rtol=1e-12, atol=1e-14)
