@@ -252,6 +252,13 @@ def main():
         del c2
         torch.cuda.empty_cache()
 
+    if args.workloads == "all" or "llama_layer" in args.workloads.split(","):
+        # the decoder layer with RMSNorm, RoPE, causal softmax and both residuals between its GEMMs
+        res, c2, _, _ = measure("llama_layer", args.steps, args.warmup)
+        per["llama_layer"] = res
+        del c2
+        torch.cuda.empty_cache()
+
     out = {"metric": "chained_gemm_tflops", "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
