@@ -163,6 +163,82 @@ def cpu_baseline(inp, shape, budget_s=15.0):
                       f"(fp64 triple loop, OpenMP over rows)"}
 
 
+SWEEP_GEMMS = [(n, n, n) for n in (256, 512, 1024, 2048, 4096, 8192)] + [
+    (4096, 256, 4096), (4096, 4096, 256), (256, 4096, 4096), (16384, 1024, 1024), (1024, 16384, 1024),
+    (1000, 1000, 1000), (4100, 2050, 1030)]
+SWEEP_CHAINS = [(256, (512, 512, 512, 512)), (1024, (1024, 4096, 1024, 256)), (1024, (256, 1024, 4096, 1024)),
+                (4096, (2048, 2048, 2048, 2048)), (4096, (1024, 4096, 1024, 4096)), (4096, (4096, 512, 4096, 512)),
+                (8192, (1024, 1024, 1024, 1024)), (1000, (1000, 3000, 1000, 300))]
+
+
+def _time_calls(fn, reps):
+    import torch
+    for _ in range(2):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def sweep(reps):
+    """Synthetic size sweep (the paper's single-GEMM and DNN-chain size lists are not available):
+    (1) one GEMM M x K x N (fp32, then bf16 operands) with a pre-packed weight, as the Initial kernel (row-major A in,
+    packed C out), the Intermediate kernel (packed in, packed out), the Ending kernel (packed in,
+    row-major out) and as a BLAS-style call (pack A + GEMM + unpack C; the Initial kernel exists for fp32 only); (2) three-GEMM chains of
+    unequal widths, propagated against the canonical control.  One JSON line per case."""
+    import torch
+    from paper_2604_04599_amd import api, chains
+    from paper_2604_04599_amd.api import LPG_F32, LPG_PACKED_A, LPG_PACKED_B, LPG_ROW_MAJOR, desc
+    st = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(2024)
+    for dtype, tag in ((LPG_F32, "f32"), (api.LPG_BF16, "bf16")):
+        for m, k, n in SWEEP_GEMMS:
+            a = torch.from_numpy(rng.standard_normal((m, k), dtype=np.float32)).cuda()
+            w = torch.from_numpy(rng.standard_normal((k, n), dtype=np.float32)).cuda()
+            a_rm, w_rm, c_rm = (desc(LPG_ROW_MAJOR, LPG_F32, r, c) for r, c in ((m, k), (k, n), (m, n)))
+            a_p, w_p, c_p = desc(LPG_PACKED_A, dtype, m, k), desc(LPG_PACKED_B, dtype, k, n), desc(LPG_PACKED_A, dtype, m, n)
+            pa, pw, pc = (torch.empty(api.lpg_packed_bytes(d), dtype=torch.uint8, device="cuda") for d in (a_p, w_p, c_p))
+            c = torch.empty((m, n), dtype=torch.float32, device="cuda")
+            api.lpg_pack(a, a_rm, pa, a_p, st)
+            api.lpg_pack(w, w_rm, pw, w_p, st)
+            flops = 2.0 * m * k * n
+            res = {"sweep": "gemm_" + tag, "m": m, "k": k, "n": n}
+            if k % 32 == 0 and dtype == LPG_F32:
+                res["initial_tflops"] = round(flops / _time_calls(
+                    lambda: api.lpg_gemm_packed(1.0, a, a_rm, pw, w_p, 0.0, None, pc, c_p, stream=st), reps) / 1e12, 2)
+            res["intermediate_tflops"] = round(flops / _time_calls(
+                lambda: api.lpg_gemm_packed(1.0, pa, a_p, pw, w_p, 0.0, None, pc, c_p, stream=st), reps) / 1e12, 2)
+            res["ending_tflops"] = round(flops / _time_calls(
+                lambda: api.lpg_gemm_packed(1.0, pa, a_p, pw, w_p, 0.0, None, c, c_rm, stream=st), reps) / 1e12, 2)
+
+            def blas_style():
+                api.lpg_pack(a, a_rm, pa, a_p, st)
+                api.lpg_gemm_packed(1.0, pa, a_p, pw, w_p, 0.0, None, pc, c_p, stream=st)
+                api.lpg_unpack(pc, c_p, c, c_rm, st)
+            res["pack_gemm_unpack_tflops"] = round(flops / _time_calls(blas_style, reps) / 1e12, 2)
+            res["intermediate_vs_pack_gemm_unpack"] = round(res["intermediate_tflops"] / res["pack_gemm_unpack_tflops"], 3)
+            print(json.dumps(res), flush=True)
+            del a, w, pa, pw, pc, c
+    for m, widths in SWEEP_CHAINS:
+        x = rng.standard_normal((m, widths[0]), dtype=np.float32)
+        ws = [rng.standard_normal((a, b), dtype=np.float32) / np.float32(np.sqrt(a)) for a, b in zip(widths, widths[1:])]
+        ch = chains.build_linear_chain(x, ws)
+        fch = chains.build_linear_chain(x, ws, fused=True)
+        tp, tc = compare_modes(ch, 6 * reps)
+        tf = time_chain(fch, api.LPG_CHAIN_PROPAGATED, reps, 2)
+        print(json.dumps({"sweep": "chain3_f32", "m": m, "widths": list(widths),
+                          "propagated_ms": round(tp * 1e3, 4), "canonical_ms": round(tc * 1e3, 4),
+                          "fused_boundaries_ms": round(tf * 1e3, 4), "speedup_vs_canonical": round(tc / tp, 3),
+                          "tflops": round(ch.flops / tp / 1e12, 2)}), flush=True)
+        del ch, fch
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -176,6 +252,9 @@ def main():
                          "attention_softmax_causal) and print its line")
     ap.add_argument("--mode", default="both", choices=["both", "propagated", "canonical"],
                     help="with --only: which chain mode(s) to run")
+    ap.add_argument("--sweep", action="store_true",
+                    help="run the synthetic single-GEMM / three-GEMM-chain size sweep instead (--steps = "
+                         "repetitions per case) and print one JSON line per case")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="profiling aid: run the elementwise SCALE kernel over a buffer of MIB MiB "
                          "(reads MIB, writes MIB per launch) --steps times, to scale HBM counters")
@@ -191,6 +270,10 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     from paper_2604_04599_amd import inputs
+
+    if args.sweep:
+        sweep(max(args.steps, 5))
+        return
 
     if args.copy_calibration:
         from paper_2604_04599_amd import api

@@ -319,6 +319,39 @@ def build_decoder_layer(inp, shape, fused=False):
     return ch
 
 
+def build_linear_chain(x, weights, dtype=LPG_F32, fused=False):
+    """X [m x k0] times weights[i] [k_i x k_{i+1}] in sequence (the DNN-style chains of section V:
+    a few dependent GEMMs of unequal widths).  x and weights are numpy float32 arrays.  The result
+    (fp32, row-major) is output "Y"; intermediates are buffers "C1", "C2", ..."""
+    m = x.shape[0]
+    widths = [x.shape[1]] + [w.shape[1] for w in weights]
+    ch = Chain("linear_chain", {"m": m, "widths": widths}, sum(2 * m * a * b for a, b in zip(widths, widths[1:])))
+    xs = ch.inputs["X"] = device_array(x)
+    for i, w in enumerate(weights):
+        ch.pack_weight(f"W{i}", w, LPG_PACKED_B, dtype)
+    out = ch.outputs["Y"] = torch.empty((m, widths[-1]), dtype=torch.float32, device=_dev())
+    rm_in = desc(LPG_ROW_MAJOR, LPG_F32, m, widths[0])
+    rm_out = desc(LPG_ROW_MAJOR, LPG_F32, m, widths[-1])
+    fuse_in = fused and dtype == LPG_F32 and widths[0] % 32 == 0
+    cur, cur_d = xs, rm_in
+    if not fuse_in:
+        cur_d = desc(LPG_PACKED_A, dtype, m, widths[0])
+        cur = ch.new_packed("C0", cur_d)
+        ch.add(api.stage_pack(xs, rm_in, cur, cur_d))
+    for i in range(len(weights)):
+        last = i == len(weights) - 1
+        if last and fused:
+            nxt, nxt_d = out, rm_out
+        else:
+            nxt_d = desc(LPG_PACKED_A, LPG_F32 if last else dtype, m, widths[i + 1])
+            nxt = ch.new_packed(f"C{i + 1}", nxt_d)
+        ch.add(api.stage_gemm(1.0, cur, cur_d, ch.bufs[f"W{i}"][0], ch.bufs[f"W{i}"][1], 0.0, None, nxt, nxt_d))
+        cur, cur_d = nxt, nxt_d
+    if not fused:
+        ch.add(api.stage_unpack(cur, cur_d, out, rm_out))
+    return ch
+
+
 def build_llama_layer(inp, shape, fused=False):
     """The decoder layer with every step between its GEMMs on the packed layout: RMSNorm, Q/K/V
     projections, RoPE on Q and K, causal softmax attention with grouped keys/values, output

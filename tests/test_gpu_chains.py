@@ -189,3 +189,26 @@ def test_fused_initial_and_ending_kernels_give_the_same_bits(name, over, out):
     fus.outputs[out].fill_(float("nan"))
     fus.run(LPG_CHAIN_CANONICAL)
     assert np.array_equal(fus.output(out).view(np.uint32), b.view(np.uint32))
+
+
+@pytest.mark.parametrize("dtype", [api.LPG_F32, api.LPG_BF16])
+@pytest.mark.parametrize("m,widths", [(70, (33, 100, 65, 17)), (256, (512, 512, 512, 512)), (1000, (1000, 3000, 1000, 300))])
+def test_three_gemm_chains_of_unequal_widths(m, widths, dtype):
+    """The DNN-style chains of the size sweep (section V): propagated = canonical bit for bit,
+    both against the fp64 chain; the fused-boundary form gives the same bits."""
+    rng = np.random.default_rng(m + sum(widths))
+    x = rng.standard_normal((m, widths[0]), dtype=np.float32)
+    ws = [rng.standard_normal((a, b), dtype=np.float32) / np.float32(np.sqrt(a)) for a, b in zip(widths, widths[1:])]
+    if dtype == api.LPG_BF16:
+        x = inputs._bf16_representable(x)
+        ws = [inputs._bf16_representable(w) for w in ws]
+    ch = chains.build_linear_chain(x, ws, dtype)
+    prop, canon = run_both_modes(ch, "Y")
+    assert np.array_equal(prop.view(np.uint32), canon.view(np.uint32))
+    tol = F32_TOL if dtype == api.LPG_F32 else BF16_TOL
+    assert ref.rel_frobenius(prop, ref.chain(x, ws)) <= 3 * tol
+    c2 = ch.fetch("C2")
+    assert ref.rel_frobenius(prop, ref.gemm(c2, ws[2])) <= F32_TOL           # last stage, fp32 out, stage-local
+    fch = chains.build_linear_chain(x, ws, dtype, fused=True)
+    fch.run()
+    assert np.array_equal(fch.output("Y").view(np.uint32), prop.view(np.uint32))
