@@ -140,6 +140,10 @@ def measure(name, steps, warmup, shape_over=None, modes="both", options=None):
         res["fused_boundaries_ms_per_step"] = round(t_f * 1e3, 4)
         res["fused_boundaries_tflops"] = round(flops / t_f / 1e12, 2)
         del fch
+        if name == "two_gemm":
+            # launch-bound: the same chain replayed from a HIP graph
+            replay = ch.capture(api.LPG_CHAIN_PROPAGATED)
+            res["graph_replay_ms_per_step"] = round(_time_calls(replay, max(steps, 20)) * 1e3, 4)
     return res, ch, inp, shape
 
 

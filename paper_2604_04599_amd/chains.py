@@ -103,6 +103,21 @@ class Chain:
         else:
             api.lpg_chain(self.stage_array(), mode, None, 0, _stream())
 
+    def capture(self, mode=LPG_CHAIN_PROPAGATED):
+        """Record the chain once into a HIP graph and return a callable that replays it on
+        torch's current stream.  Every launch of lpg_chain is a plain kernel on the stream it
+        is given and the call neither allocates nor synchronises, so stream capture sees the
+        whole chain; for launch-bound chains (a few small GEMMs) a replay costs one graph
+        launch instead of one launch per stage."""
+        if mode == LPG_CHAIN_CANONICAL:
+            self.workspace()                       # allocate before capture starts
+        self.run(mode)                             # warm up outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.run(mode)
+        return graph.replay
+
     def fetch(self, name):
         """Unpack a named packed buffer to a numpy float32 array (for checks)."""
         t, d = self.bufs[name]
