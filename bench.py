@@ -259,6 +259,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="run the synthetic single-GEMM / three-GEMM-chain size sweep instead (--steps = "
                          "repetitions per case) and print one JSON line per case")
+    ap.add_argument("--gemm", default=None, metavar="M,N,K,DTYPE",
+                    help="profiling aid: run one packed-in, packed-out GEMM C[MxN] = A[MxK] B[KxN] (DTYPE f32 or "
+                         "bf16) --steps times and print its rate")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="profiling aid: run the elementwise SCALE kernel over a buffer of MIB MiB "
                          "(reads MIB, writes MIB per launch) --steps times, to scale HBM counters")
@@ -277,6 +280,19 @@ def main():
 
     if args.sweep:
         sweep(max(args.steps, 5))
+        return
+
+    if args.gemm:
+        from paper_2604_04599_amd import api
+        m, n, k, dt = args.gemm.split(",")
+        m, n, k = int(m), int(n), int(k)
+        dtype = {"f32": api.LPG_F32, "bf16": api.LPG_BF16}[dt]
+        a_p, w_p, c_p = (api.desc(kind, dtype, r, c) for kind, r, c in
+                         ((api.LPG_PACKED_A, m, k), (api.LPG_PACKED_B, k, n), (api.LPG_PACKED_A, m, n)))
+        pa, pw, pc = (torch.zeros(api.lpg_packed_bytes(d), dtype=torch.uint8, device="cuda") for d in (a_p, w_p, c_p))
+        st = torch.cuda.current_stream().cuda_stream
+        t = _time_calls(lambda: api.lpg_gemm_packed(1.0, pa, a_p, pw, w_p, 0.0, None, pc, c_p, stream=st), args.steps)
+        print(json.dumps({"gemm": args.gemm, "us": round(t * 1e6, 2), "tflops": round(2.0 * m * n * k / t / 1e12, 2)}))
         return
 
     if args.copy_calibration:
