@@ -1211,6 +1211,15 @@ constexpr int ring_ns(bool bf16, int tlg, int trg, int nw)
     return 4 * stage <= 80 * 1024 ? 4 : 3;
 }
 
+// fp32 with small tiles and no more tiles than compute units: a step's MFMAs (2048 cycles
+// for a 128 x 64 tile) are shorter than the memory latency under load, and no second
+// workgroup shares the compute unit to cover for it, so the ring is made deeper instead.
+constexpr int ring_ns_lone(int tlg, int trg)
+{
+    const int stage = (tlg + trg) * 4 * kFragBytes;
+    return 4 * stage <= 96 * 1024 ? 4 : (3 * stage <= 96 * 1024 ? 3 : 2);
+}
+
 static int lds_bytes(const TileCfg &c, bool bf16)
 {
     return ring_ns(bf16, c.tlg, c.trg, c.wl * c.wr) * (c.tlg + c.trg) * ring_fs(bf16) * kFragBytes;
@@ -1255,22 +1264,14 @@ static double estimate_cost(const GemmArgs &a, const TileCfg &c, bool bf16)
     return mfma + traffic + fixed;
 }
 
-template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR>
-static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
+template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR, int NS>
+static hipError_t launch_gemm_ring(const GemmArgs &a, int64_t grid, hipStream_t st)
 {
     constexpr int NT = WL * WR * 64;
     constexpr bool BF = IN::ES == 2;
-    constexpr int FS = ring_fs(BF), NS = ring_ns(BF, TLG, TRG, WL * WR);
+    constexpr int FS = ring_fs(BF);
     constexpr size_t lds = (size_t)NS * (TLG + TRG) * FS * kFragBytes;
     static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
-    a.tiles_l = (a.FLg + TLG - 1) / TLG;
-    a.tiles_r = (a.FRg_out + TRG - 1) / TRG;
-    const int64_t total = (int64_t)a.tiles_l * a.tiles_r * a.batch;
-    if (total <= 0) return hipSuccess;
-    if (total > 0x7fffffff) return hipErrorInvalidValue;
-    const TileCfg c = {TLG, TRG, WL, WR};
-    int64_t grid = (int64_t)256 * workgroups_per_cu(c, IN::ES == 2);
-    if (grid > total) grid = total;
     auto kern = gemm_kernel<IN, OUT, TLG, TRG, WL, WR, FS, NS, BF>;
     if (lds > 64 * 1024) {
         static bool done = false;  // per instantiation
@@ -1282,6 +1283,25 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, st, a);
     return hipGetLastError();
+}
+
+template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR>
+static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
+{
+    constexpr bool BF = IN::ES == 2;
+    constexpr int NS = ring_ns(BF, TLG, TRG, WL * WR), NS_LONE = BF ? NS : ring_ns_lone(TLG, TRG);
+    a.tiles_l = (a.FLg + TLG - 1) / TLG;
+    a.tiles_r = (a.FRg_out + TRG - 1) / TRG;
+    const int64_t total = (int64_t)a.tiles_l * a.tiles_r * a.batch;
+    if (total <= 0) return hipSuccess;
+    if (total > 0x7fffffff) return hipErrorInvalidValue;
+    const TileCfg c = {TLG, TRG, WL, WR};
+    int64_t grid = (int64_t)256 * workgroups_per_cu(c, BF);
+    if (grid > total) grid = total;
+    if constexpr (NS_LONE != NS) {
+        if (total <= 256) return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS_LONE>(a, grid, st);
+    }
+    return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS>(a, grid, st);
 }
 
 template <typename IN, typename OUT>
