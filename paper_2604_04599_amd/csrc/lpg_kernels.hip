@@ -616,12 +616,12 @@ static hipError_t launch_row_dtype(const RowArgs &a, bool packed, hipStream_t st
     // that variant can hold the rows (a tuning aid).
     struct Variant { int r, nw; bool cached; };
     static const Variant kVariants[] = {{32, 8, true}, {16, 8, true}, {8, 8, true}, {8, 16, true},
-                                        {8, 8, false}};
+                                        {8, 8, false}, {32, 4, true}};
     auto fits = [&](int v) { return !kVariants[v].cached || kVariants[v].r * a.nkb <= 128 * kVariants[v].nw; };
-    int variant = fits(0) ? 0 : fits(1) ? 1 : fits(2) ? 2 : fits(3) ? 3 : 4;
+    int variant = fits(5) ? 5 : fits(0) ? 0 : fits(1) ? 1 : fits(2) ? 2 : fits(3) ? 3 : 4;  // short rows: 4 waves
     if (const char *f = getenv("LPG_ROW_VARIANT")) {
         const int v = atoi(f);
-        if (v >= 0 && v < 5 && fits(v)) variant = v;
+        if (v >= 0 && v < 6 && fits(v)) variant = v;
     }
     const unsigned grid = (unsigned)((int64_t)a.batch * a.ngroups * (32 / kVariants[variant].r));
     const dim3 block(kVariants[variant].nw * 64);
@@ -630,7 +630,8 @@ static hipError_t launch_row_dtype(const RowArgs &a, bool packed, hipStream_t st
         case 1: hipLaunchKernelGGL((row_packed_kernel<T, OP, 16, 8, true>), dim3(grid), block, 0, st, a); break;
         case 2: hipLaunchKernelGGL((row_packed_kernel<T, OP, 8, 8, true>), dim3(grid), block, 0, st, a); break;
         case 3: hipLaunchKernelGGL((row_packed_kernel<T, OP, 8, 16, true>), dim3(grid), block, 0, st, a); break;
-        default: hipLaunchKernelGGL((row_packed_kernel<T, OP, 8, 8, false>), dim3(grid), block, 0, st, a); break;
+        case 4: hipLaunchKernelGGL((row_packed_kernel<T, OP, 8, 8, false>), dim3(grid), block, 0, st, a); break;
+        default: hipLaunchKernelGGL((row_packed_kernel<T, OP, 32, 4, true>), dim3(grid), block, 0, st, a); break;
     }
     return hipGetLastError();
 }
