@@ -15,6 +15,7 @@ bounded row sample of the same workload.
 """
 import argparse
 import json
+import statistics
 import sys
 import time
 
@@ -83,6 +84,54 @@ def time_gemm_launches(ch, steps):
     return total_ms * 1e-3 / len(pairs), nflops / ngemm
 
 
+STAGE_NAMES = {0: "pack", 1: "gemm", 2: "elementwise", 3: "unpack", 4: "softmax", 5: "rmsnorm", 6: "rope"}
+
+
+def stage_breakdown(ch, steps):
+    """Per stage of the chain (propagated mode, each stage issued through its own lpg_chain call
+    with an event pair around it): median microseconds, and the rate it stands for: GEMM flops and
+    algorithmic bytes ((m*k + k*n + m*n (+ m*n with beta)) * element size per matrix of the
+    batch); other stages the bytes they read and write once."""
+    import torch
+    from paper_2604_04599_amd import api
+    st = torch.cuda.current_stream().cuda_stream
+    es = api.ELEM_SIZE
+    pairs = [[] for _ in ch.stages]
+    for _ in range(steps):
+        for i, s in enumerate(ch.stages):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            api.lpg_chain([s], api.LPG_CHAIN_PROPAGATED, None, 0, st)
+            e1.record()
+            pairs[i].append((e0, e1))
+    torch.cuda.synchronize()
+    out = []
+    for i, s in enumerate(ch.stages):
+        us = statistics.median(a.elapsed_time(b) for a, b in pairs[i]) * 1e3
+        o = s.out_d
+        nb = max(o.batch, 1)
+        row = {"stage": i, "kind": STAGE_NAMES[s.type], "us": round(us, 2)}
+        if s.type == api.LPG_STAGE_GEMM:
+            m, k, n = s.in0_d.rows, s.in0_d.cols, s.in1_d.cols
+            nbytes = nb * ((m * k * es[s.in0_d.dtype]) // max(s.in0_d.batch_div, 1)
+                           + (k * n * es[s.in1_d.dtype]) // max(s.in1_d.batch_div, 1)
+                           + m * n * es[o.dtype] * (2 if s.beta != 0 else 1))
+            row.update({"m": m, "n": n, "k": k, "batch": nb, "tflops": round(2.0 * m * n * k * nb / us / 1e6, 1)})
+        elif s.type in (api.LPG_STAGE_PACK, api.LPG_STAGE_UNPACK):
+            nbytes = nb * o.rows * o.cols * (es[s.in0_d.dtype] + es[o.dtype])
+        elif s.type == api.LPG_STAGE_ELEMENTWISE:
+            nbytes = nb * o.rows * o.cols * es[o.dtype] * (3 if s.in1 else 2)
+        elif s.type == api.LPG_STAGE_SOFTMAX:
+            r, c = o.rows, o.cols
+            kept = r * c if not s.op else sum(min(c, max(0, j + c - r + 1)) for j in range(r))
+            nbytes = nb * (kept + r * c) * es[o.dtype]
+        else:
+            nbytes = nb * o.rows * o.cols * es[o.dtype] * 2
+        row["hbm_gbps"] = round(nbytes / us / 1e3, 1)
+        out.append(row)
+    return out
+
+
 def time_softmax_launches(ch, steps):
     """Average duration of the chain's softmax launch (event pair around each), with the bytes
     it has to move: the kept scores read once, the whole score matrix written once."""
@@ -140,6 +189,7 @@ def measure(name, steps, warmup, shape_over=None, modes="both", options=None):
         res["fused_boundaries_ms_per_step"] = round(t_f * 1e3, 4)
         res["fused_boundaries_tflops"] = round(flops / t_f / 1e12, 2)
         del fch
+        res["stages"] = stage_breakdown(ch, max(3, steps // 2))
         if name == "two_gemm":
             # launch-bound: the same chain replayed from a HIP graph
             replay = ch.capture(api.LPG_CHAIN_PROPAGATED)
