@@ -232,6 +232,28 @@ int lpg_rope_tables(float *cos_t, float *sin_t, int64_t rows, int32_t head_dim, 
 int lpg_rope_packed(const void *x, void *out, const lpg_desc *d, const float *cos_t,
                     const float *sin_t, int32_t head_dim, void *stream);
 
+/*
+ * lpg_attention_packed - the attention block of Alg. 2 (score GEMM, scale, optional causal
+ * mask, softmax, weighted sum) as one kernel in which the scores stay in registers:
+ *     O = softmax(scale * Q K^T [causal]) V        per matrix of the batch (head).
+ * The paper keeps the scores as a matrix in the propagated layout between two GEMMs; on this
+ * hardware the accumulator tile the score MFMA leaves is already the operand fragment the
+ * second MFMA consumes, so the propagated intermediate need not be stored at all.  Same
+ * values as lpg_gemm_packed + lpg_softmax_packed + lpg_gemm_packed up to rounding (the
+ * probabilities are not rounded to the storage type before the row sum).
+ *   q_d, o_d: LPG_PACKED_A, queries x head_dim (views of the projections' outputs are fine).
+ *   k_d: the keys as a left-operand image, LPG_PACKED_A keys x head_dim, or the same bytes
+ *        described as LPG_PACKED_B head_dim x keys (K^T as a right operand).
+ *   v_d: LPG_PACKED_B keys x head_dim (or LPG_PACKED_A head_dim x keys).
+ *   One dtype for all four (f32 or bf16; fp32 accumulation and softmax); head_dim 64 or 128;
+ *   batch counts equal; batch_div on k_d / v_d shares a key/value head among query heads.
+ *   causal != 0: query i sees keys j <= i + (keys - queries).  scale > 0.  O must not alias
+ *   an input.  Padding rows of O are written as zeros.
+ */
+int lpg_attention_packed(const void *Q, const lpg_desc *q_d, const void *K, const lpg_desc *k_d,
+                         const void *V, const lpg_desc *v_d, void *O, const lpg_desc *o_d,
+                         float scale, int causal, void *stream);
+
 /* One stage of a chain. */
 typedef enum {
     LPG_STAGE_PACK = 0,
@@ -240,26 +262,29 @@ typedef enum {
     LPG_STAGE_UNPACK = 3,
     LPG_STAGE_SOFTMAX = 4,
     LPG_STAGE_RMSNORM = 5,
-    LPG_STAGE_ROPE = 6
+    LPG_STAGE_ROPE = 6,
+    LPG_STAGE_ATTENTION = 7
 } lpg_stage_type;
 
 typedef struct lpg_stage {
     int32_t type;       /* lpg_stage_type                                               */
-    int32_t op;         /* GEMM: lpg_epilogue_op; ELEMENTWISE: lpg_ew_op; SOFTMAX: causal;
-                           ROPE: head_dim                                                */
+    int32_t op;         /* GEMM: lpg_epilogue_op; ELEMENTWISE: lpg_ew_op; SOFTMAX,
+                           ATTENTION: causal; ROPE: head_dim                             */
     float alpha, beta;  /* GEMM                                                         */
-    float scalar;       /* ELEMENTWISE: s; SOFTMAX: scale; RMSNORM: eps                 */
+    float scalar;       /* ELEMENTWISE: s; SOFTMAX, ATTENTION: scale; RMSNORM: eps      */
     int32_t reserved;
     const void *in0;    /* PACK/UNPACK: src; GEMM: A; ELEMENTWISE: x0; SOFTMAX, RMSNORM,
-                           ROPE: x                                                       */
-    const void *in1;    /* GEMM: B; ELEMENTWISE: x1; RMSNORM: weight; ROPE: cos table   */
-    const void *in2;    /* GEMM: C_in (or NULL); ROPE: sin table                        */
+                           ROPE: x; ATTENTION: Q                                         */
+    const void *in1;    /* GEMM: B; ELEMENTWISE: x1; RMSNORM: weight; ROPE: cos table;
+                           ATTENTION: K                                                  */
+    const void *in2;    /* GEMM: C_in (or NULL); ROPE: sin table; ATTENTION: V          */
     const void *epi_arg;/* GEMM: epilogue argument (or NULL)                            */
     void *out;
     lpg_desc in0_d;     /* descriptor of in0                                            */
     lpg_desc in1_d;     /* GEMM: descriptor of B                                        */
     lpg_desc out_d;     /* descriptor of out (and of in2, epi_arg, and of the x inputs of
                            ELEMENTWISE / SOFTMAX / RMSNORM / ROPE)                       */
+    lpg_desc in2_d;     /* ATTENTION: descriptor of V                                   */
 } lpg_stage;
 
 typedef enum {

@@ -18,7 +18,7 @@ LPG_ROW_MAJOR, LPG_COL_MAJOR, LPG_PACKED_A, LPG_PACKED_B = 0, 1, 2, 3
 LPG_EW_SCALE, LPG_EW_ADD, LPG_EW_SILU_MUL = 0, 1, 2
 LPG_EPI_NONE, LPG_EPI_SILU, LPG_EPI_GATE_SILU = 0, 1, 2
 LPG_STAGE_PACK, LPG_STAGE_GEMM, LPG_STAGE_ELEMENTWISE, LPG_STAGE_UNPACK, LPG_STAGE_SOFTMAX = 0, 1, 2, 3, 4
-LPG_STAGE_RMSNORM, LPG_STAGE_ROPE = 5, 6
+LPG_STAGE_RMSNORM, LPG_STAGE_ROPE, LPG_STAGE_ATTENTION = 5, 6, 7
 LPG_CHAIN_PROPAGATED, LPG_CHAIN_CANONICAL = 0, 1
 
 ELEM_SIZE = {LPG_F32: 4, LPG_BF16: 2}
@@ -46,7 +46,7 @@ class lpg_stage(ctypes.Structure):
         ("reserved", ctypes.c_int32),
         ("in0", ctypes.c_void_p), ("in1", ctypes.c_void_p), ("in2", ctypes.c_void_p),
         ("epi_arg", ctypes.c_void_p), ("out", ctypes.c_void_p),
-        ("in0_d", lpg_desc), ("in1_d", lpg_desc), ("out_d", lpg_desc),
+        ("in0_d", lpg_desc), ("in1_d", lpg_desc), ("out_d", lpg_desc), ("in2_d", lpg_desc),
     ]
 
 
@@ -85,6 +85,8 @@ def lib():
         L.lpg_elementwise_packed.restype = ctypes.c_int
         L.lpg_softmax_packed.argtypes = [vp, vp, dp, ctypes.c_float, ctypes.c_int, vp]
         L.lpg_softmax_packed.restype = ctypes.c_int
+        L.lpg_attention_packed.argtypes = [vp, dp, vp, dp, vp, dp, vp, dp, ctypes.c_float, ctypes.c_int, vp]
+        L.lpg_attention_packed.restype = ctypes.c_int
         L.lpg_rmsnorm_packed.argtypes = [vp, vp, vp, dp, ctypes.c_float, vp]
         L.lpg_rmsnorm_packed.restype = ctypes.c_int
         L.lpg_rope_tables.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_double, ctypes.c_int64, vp]
@@ -102,7 +104,7 @@ def lib():
 
 
 EXPORTS = ("lpg_packed_bytes", "lpg_layout_offset", "lpg_pack", "lpg_unpack", "lpg_gemm_packed",
-           "lpg_elementwise_packed", "lpg_softmax_packed", "lpg_rmsnorm_packed", "lpg_rope_tables", "lpg_rope_packed",
+           "lpg_elementwise_packed", "lpg_softmax_packed", "lpg_attention_packed", "lpg_rmsnorm_packed", "lpg_rope_tables", "lpg_rope_packed",
            "lpg_chain_workspace_bytes", "lpg_chain", "lpg_last_error",
            "lpg_version")
 
@@ -172,6 +174,12 @@ def lpg_elementwise_packed(op, x0, x1, s, out, d, stream=None):
 
 def lpg_softmax_packed(x, out, d, scale=1.0, causal=False, stream=None):
     return _check(lib().lpg_softmax_packed(_ptr(x), _ptr(out), ctypes.byref(d), scale, int(bool(causal)), stream))
+
+
+def lpg_attention_packed(Q, q_d, K, k_d, V, v_d, O, o_d, scale, causal=False, stream=None):
+    return _check(lib().lpg_attention_packed(_ptr(Q), ctypes.byref(q_d), _ptr(K), ctypes.byref(k_d), _ptr(V),
+                                             ctypes.byref(v_d), _ptr(O), ctypes.byref(o_d), scale, int(bool(causal)),
+                                             stream))
 
 
 def lpg_rmsnorm_packed(x, weight, out, d, eps, stream=None):
@@ -253,4 +261,12 @@ def stage_rope(x, out, d, cos_t, sin_t, head_dim):
     s = lpg_stage()
     s.type, s.op = LPG_STAGE_ROPE, head_dim
     s.in0, s.in1, s.in2, s.out, s.out_d = _ptr(x), _ptr(cos_t), _ptr(sin_t), _ptr(out), d
+    return s
+
+
+def stage_attention(Q, q_d, K, k_d, V, v_d, O, o_d, scale, causal=False):
+    s = lpg_stage()
+    s.type, s.op, s.scalar = LPG_STAGE_ATTENTION, int(bool(causal)), scale
+    s.in0, s.in0_d, s.in1, s.in1_d, s.in2, s.in2_d = _ptr(Q), q_d, _ptr(K), k_d, _ptr(V), v_d
+    s.out, s.out_d = _ptr(O), o_d
     return s

@@ -198,10 +198,11 @@ def build_mlp(inp, shape, fused=False):
     return ch
 
 
-def build_attention(inp, shape, fused=False, softmax=False, causal=False):
+def build_attention(inp, shape, fused=False, softmax=False, causal=False, flash=False):
     """softmax=False: O = (Q K^T / sqrt(dh)) V, the two chained GEMMs alone.  softmax=True: the
     scale moves into a softmax stage (optionally causally masked) that runs in place on the
-    packed scores between the two GEMMs."""
+    packed scores between the two GEMMs.  flash=True (implies softmax): one lpg_attention_packed
+    stage replaces the three, and the scores are never stored."""
     nh, t, dh = shape["heads"], shape["t"], shape["dh"]
     scale = 1.0 / float(np.sqrt(dh))
     alpha = 1.0 if softmax else scale
@@ -219,7 +220,8 @@ def build_attention(inp, shape, fused=False, softmax=False, causal=False):
     sd = desc(LPG_PACKED_A, LPG_F32, t, t, batch=nh, batch_stride=_packed_elems(LPG_F32, t, t))
     od = desc(LPG_PACKED_A, LPG_F32, t, dh, batch=nh, batch_stride=pe)
     pq, pk, pv = ch.new_packed("Q", qd), ch.new_packed("Kt", ktd), ch.new_packed("V", vd)
-    ps, po = ch.new_packed("S", sd), ch.new_packed("O", od)
+    po = ch.new_packed("O", od)
+    ps = None if flash else ch.new_packed("S", sd)
     out = ch.outputs["O"] = torch.empty((nh, t, dh), dtype=torch.float32, device=_dev())
     if fused:
         # Q_h and K_h^T are contiguous along the contraction index as they stand; V_h (a right
@@ -233,6 +235,10 @@ def build_attention(inp, shape, fused=False, softmax=False, causal=False):
     ch.add(api.stage_pack(q, rm, pq, qd))
     ch.add(api.stage_pack(k, ktd_src, pk, ktd))
     ch.add(api.stage_pack(v, rm, pv, vd))
+    if flash:
+        ch.add(api.stage_attention(pq, qd, pk, ktd, pv, vd, po, od, scale, causal))
+        ch.add(api.stage_unpack(po, od, out, rm))
+        return ch
     ch.add(api.stage_gemm(alpha, pq, qd, pk, ktd, 0.0, None, ps, sd))
     if softmax:
         ch.add(api.stage_softmax(ps, ps, sd, scale, causal))
@@ -367,11 +373,12 @@ def build_linear_chain(x, weights, dtype=LPG_F32, fused=False):
     return ch
 
 
-def build_llama_layer(inp, shape, fused=False):
+def build_llama_layer(inp, shape, fused=False, flash=False):
     """The decoder layer with every step between its GEMMs on the packed layout: RMSNorm, Q/K/V
     projections, RoPE on Q and K, causal softmax attention with grouped keys/values, output
     projection + residual, RMSNorm, gated MLP + residual.  bf16 intermediates, fp32 math.
-    fused=True folds SiLU(gate)*up into the up projection's epilogue."""
+    fused=True folds SiLU(gate)*up into the up projection's epilogue; flash=True runs the attention
+    block as one lpg_attention_packed stage (no score matrix)."""
     t, hid, nq, nkv, ffn = shape["t"], shape["hidden"], shape["n_q"], shape["n_kv"], shape["ffn"]
     eps, base = 1.0 / shape["inv_eps"], float(shape["rope_base"])
     dh = hid // nq
@@ -399,7 +406,8 @@ def build_llama_layer(inp, shape, fused=False):
     gd = desc(LPG_PACKED_A, B, t, ffn)
     sd = desc(LPG_PACKED_A, B, t, t, batch=nq, batch_stride=_packed_elems(B, t, t))
     px, ph1, pq, po, pa, ph2, py = (ch.new_packed(n_, hd) for n_ in ("X", "h1", "Q", "O", "A", "h2", "Y"))
-    pk, pv, ps = ch.new_packed("K", kd), ch.new_packed("V", vd), ch.new_packed("S", sd)
+    pk, pv = ch.new_packed("K", kd), ch.new_packed("V", vd)
+    ps = None if flash else ch.new_packed("S", sd)
     pg, pact = ch.new_packed("gate", gd), ch.new_packed("act", gd)
     out = ch.outputs["Y"] = torch.empty((t, hid), dtype=torch.float32, device=_dev())
     rm = desc(LPG_ROW_MAJOR, LPG_F32, t, hid)
@@ -415,9 +423,12 @@ def build_llama_layer(inp, shape, fused=False):
     kt_view = desc(LPG_PACKED_B, B, dh, t, parent=(kvw, t), batch=nq, batch_div=rep, batch_step=(dh, 0))
     v_view = desc(LPG_PACKED_B, B, t, dh, parent=(t, kvw), batch=nq, batch_div=rep, batch_step=(0, dh))
     o_view = desc(LPG_PACKED_A, B, t, dh, parent=(t, hid), batch=nq, batch_step=(0, dh))
-    ch.add(api.stage_gemm(1.0, pq, q_view, pk, kt_view, 0.0, None, ps, sd))
-    ch.add(api.stage_softmax(ps, ps, sd, 1.0 / float(np.sqrt(dh)), True))
-    ch.add(api.stage_gemm(1.0, ps, sd, pv, v_view, 0.0, None, po, o_view))
+    if flash:
+        ch.add(api.stage_attention(pq, q_view, pk, kt_view, pv, v_view, po, o_view, 1.0 / float(np.sqrt(dh)), True))
+    else:
+        ch.add(api.stage_gemm(1.0, pq, q_view, pk, kt_view, 0.0, None, ps, sd))
+        ch.add(api.stage_softmax(ps, ps, sd, 1.0 / float(np.sqrt(dh)), True))
+        ch.add(api.stage_gemm(1.0, ps, sd, pv, v_view, 0.0, None, po, o_view))
     ch.add(api.stage_gemm(1.0, po, hd, wt["Wo"], wd["Wo"], 1.0, px, pa, hd))           # + residual X
     ch.add(api.stage_rmsnorm(pa, n2, ph2, hd, eps))
     ch.add(api.stage_gemm(1.0, ph2, hd, wt["Wg"], wd["Wg"], 0.0, None, pg, gd))

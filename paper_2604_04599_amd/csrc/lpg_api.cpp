@@ -504,6 +504,63 @@ static int do_rope(const void *x, void *out, const lpg_desc *d, const void *cos_
     return LPG_OK;
 }
 
+// -------------------------------------------------------------------------- attention
+
+static int do_attention(const void *Q, const lpg_desc *q_d, const void *K, const lpg_desc *k_d, const void *V,
+                        const lpg_desc *v_d, void *O, const lpg_desc *o_d, float scale, int causal, hipStream_t st,
+                        bool launch)
+{
+    const char *what = "lpg_attention_packed";
+    PView q, k, v, o;
+    int rc = make_pview(q_d, what, &q);
+    if (rc) return rc;
+    if ((rc = make_pview(k_d, what, &k))) return rc;
+    if ((rc = make_pview(v_d, what, &v))) return rc;
+    if ((rc = make_pview(o_d, what, &o))) return rc;
+    if (q_d->kind != LPG_PACKED_A || o_d->kind != LPG_PACKED_A)
+        return fail(LPG_ELAYOUT, "%s: Q and O must be PACKED_A (queries x head_dim)", what);
+    if (q.dtype != k.dtype || q.dtype != v.dtype || q.dtype != o.dtype)
+        return fail(LPG_EUNSUPPORTED, "%s: Q, K, V, O must share one dtype", what);
+    const int64_t dh = q.K, tq = q.F, tk = k.F;
+    if (dh != 64 && dh != 128) return fail(LPG_EUNSUPPORTED, "%s: head_dim %lld (64 and 128 are built)", what, (long long)dh);
+    // K: free index = key, contraction = head_dim (PACKED_A of K, or PACKED_B of K^T: same bytes);
+    // V: free index = head_dim, contraction = key (PACKED_B of V, or PACKED_A of V^T)
+    if (k.K != dh || v.F != dh || v.K != tk || o.F != tq || o.K != dh)
+        return fail(LPG_EINVAL, "%s: shapes do not fit (Q %lldx%lld, K keys %lld x %lld, V %lld keys x %lld, O %lldx%lld)", what,
+                    (long long)tq, (long long)dh, (long long)tk, (long long)k.K, (long long)v.K, (long long)v.F,
+                    (long long)o.F, (long long)o.K);
+    if (q.batch != o.batch || k.batch != q.batch || v.batch != q.batch)
+        return fail(LPG_EINVAL, "%s: batch counts differ", what);
+    if (q.bdiv != 1 || o.bdiv != 1) return fail(LPG_EUNSUPPORTED, "%s: batch_div applies to K and V only", what);
+    if (!(scale > 0.0f && scale <= 3.0e38f)) return fail(LPG_EINVAL, "%s: scale must be positive and finite", what);
+    if (tq > 0 && tk <= 0) return fail(LPG_EINVAL, "%s: no keys", what);
+    if ((rc = check_ptr16(Q, what)) || (rc = check_ptr16(K, what)) || (rc = check_ptr16(V, what)) || (rc = check_ptr16(O, what)))
+        return rc;
+    if (O == Q || O == K || O == V) return fail(LPG_EINVAL, "%s: O must not alias an input", what);
+    if ((int64_t)q.batch * ((tq + 127) / 128) > 0x7fffffff) return fail(LPG_EUNSUPPORTED, "%s: too many query blocks", what);
+    if (!launch) return LPG_OK;
+    AttnArgs a{};
+    a.Q = (const char *)Q + q.origin;
+    a.K = (const char *)K + k.origin;
+    a.V = (const char *)V + v.origin;
+    a.O = (char *)O + o.origin;
+    a.q_kbs = q.kb_stride; a.k_kbs = k.kb_stride; a.v_kbs = v.kb_stride; a.o_kbs = o.kb_stride;
+    a.q_slot = q.slot_step; a.k_slot = k.slot_step; a.v_slot = v.slot_step; a.o_slot = o.slot_step;
+    a.k_div = k.bdiv;
+    a.v_div = v.bdiv;
+    a.tq = (int32_t)tq;
+    a.tk = (int32_t)tk;
+    a.q_groups = (int32_t)((tq + 31) / 32);
+    a.k_groups = (int32_t)((tk + 31) / 32);
+    a.v_nkb = (int32_t)((tk + kb_of(q.dtype) - 1) / kb_of(q.dtype));
+    a.batch = q.batch;
+    a.causal = causal != 0;
+    a.sl = (float)((double)scale * 1.4426950408889634);
+    hipError_t e = launch_attention(a, q.dtype, (int)dh, st);
+    if (e != hipSuccess) return fail(LPG_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return LPG_OK;
+}
+
 // ------------------------------------------------------------------------------ chain
 
 // Packed geometry two descriptors must share to address the same bytes the same way.
@@ -575,6 +632,7 @@ static bool later_reads(const lpg_stage *st, int n, int from, const void *buf, b
     for (int i = from; i < n; ++i) {
         const lpg_stage &s = st[i];
         const bool reads = s.in0 == buf || (s.type == LPG_STAGE_GEMM && (s.in1 == buf || s.in2 == buf || s.epi_arg == buf)) ||
+                           (s.type == LPG_STAGE_ATTENTION && (s.in1 == buf || s.in2 == buf)) ||
                            (s.type == LPG_STAGE_ELEMENTWISE && s.in1 == buf);
         if (reads) {
             any = true;
@@ -609,6 +667,9 @@ static int validate_stage(const lpg_stage &s, int i)
         case LPG_STAGE_RMSNORM:
         case LPG_STAGE_ROPE:
             return run_row_stage(s, s.in0, s.out, &s.out_d, nullptr, false);
+        case LPG_STAGE_ATTENTION:
+            return do_attention(s.in0, &s.in0_d, s.in1, &s.in1_d, s.in2, &s.in2_d, s.out, &s.out_d, s.scalar, s.op,
+                                nullptr, false);
         default:
             return fail(LPG_EINVAL, "lpg_chain: stage %d has unknown type %d", i, s.type);
     }
@@ -630,6 +691,10 @@ static int check_links(const lpg_stage *st, int n)
         } else if (s.type == LPG_STAGE_ELEMENTWISE) {
             ins[ni++] = {s.in0, &s.out_d};
             if (s.in1) ins[ni++] = {s.in1, &s.out_d};
+        } else if (s.type == LPG_STAGE_ATTENTION) {
+            ins[ni++] = {s.in0, &s.in0_d};
+            ins[ni++] = {s.in1, &s.in1_d};
+            ins[ni++] = {s.in2, &s.in2_d};
         } else if (is_row_stage(s.type)) {
             ins[ni++] = {s.in0, &s.out_d};
         } else if (s.type == LPG_STAGE_UNPACK) {
@@ -667,6 +732,9 @@ static int run_stage(const lpg_stage &s, hipStream_t hs)
         case LPG_STAGE_SOFTMAX:
         case LPG_STAGE_RMSNORM:
         case LPG_STAGE_ROPE: return run_row_stage(s, s.in0, s.out, &s.out_d, hs, true);
+        case LPG_STAGE_ATTENTION:
+            return do_attention(s.in0, &s.in0_d, s.in1, &s.in1_d, s.in2, &s.in2_d, s.out, &s.out_d, s.scalar, s.op, hs,
+                                true);
         default: return do_elementwise(s.op, s.in0, s.in1, s.scalar, s.out, &s.out_d, hs, true);
     }
 }
@@ -756,7 +824,7 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
             int rc = repack(s.in0);
             if (rc) return rc;
             if (!sm && s.in1) { rc = repack(s.in1); if (rc) return rc; }
-        } else if (s.type == LPG_STAGE_GEMM) {
+        } else if (s.type == LPG_STAGE_GEMM || s.type == LPG_STAGE_ATTENTION) {
             int rc = repack(s.in0);
             if (rc) return rc;
             rc = repack(s.in1);
@@ -858,6 +926,12 @@ int lpg_elementwise_packed(int op, const void *x0, const void *x1, float s, void
 int lpg_softmax_packed(const void *x, void *out, const lpg_desc *d, float scale, int causal, void *stream)
 {
     return do_row_op(kRowSoftmax, x, nullptr, out, d, scale, causal, (hipStream_t)stream, true);
+}
+
+int lpg_attention_packed(const void *Q, const lpg_desc *q_d, const void *K, const lpg_desc *k_d, const void *V,
+                         const lpg_desc *v_d, void *O, const lpg_desc *o_d, float scale, int causal, void *stream)
+{
+    return do_attention(Q, q_d, K, k_d, V, v_d, O, o_d, scale, causal, (hipStream_t)stream, true);
 }
 
 int lpg_rmsnorm_packed(const void *x, const float *weight, void *out, const lpg_desc *d, float eps, void *stream)

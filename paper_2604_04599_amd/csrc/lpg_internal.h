@@ -122,6 +122,19 @@ struct RopeArgs {
     int32_t npad;        // packed: fragments of column padding to zero-fill (0 when in place)
 };
 
+struct AttnArgs {
+    const char *Q, *K, *V;  // buffers + origins (bytes applied)
+    char *O;
+    int64_t q_kbs, k_kbs, v_kbs, o_kbs;      // bytes between K blocks
+    int64_t q_slot, k_slot, v_slot, o_slot;  // bytes per slot
+    int32_t k_div, v_div;                    // query heads per key / value head
+    int32_t tq, tk;                          // queries, keys
+    int32_t q_groups, k_groups;              // ceil(tq/32), ceil(tk/32)
+    int32_t v_nkb;                           // ceil(tk/KB): contraction blocks of V
+    int32_t batch, causal;
+    float sl;                                // scale * log2(e)
+};
+
 // Launchers (lpg_kernels.hip).  Return hipError_t of the launch.
 hipError_t launch_pack(const PackArgs &a, int src_dtype, int dst_dtype, hipStream_t st);
 hipError_t launch_unpack(const PackArgs &a, int src_dtype, int dst_dtype, hipStream_t st);
@@ -133,5 +146,6 @@ hipError_t launch_row_op(const RowArgs &a, int op, int dtype, bool packed, hipSt
 hipError_t launch_rope_tables(float *cos_t, float *sin_t, int64_t rows, int head_dim, double base, double pos0,
                               hipStream_t st);
 hipError_t launch_rope(const RopeArgs &a, int dtype, bool packed, hipStream_t st);
+hipError_t launch_attention(const AttnArgs &a, int dtype, int head_dim, hipStream_t st);
 
 }  // namespace lpg

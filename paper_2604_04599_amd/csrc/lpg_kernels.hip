@@ -1183,6 +1183,227 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
 }
 
+// ---------------------------------------------------------------------------------
+// Fused attention on packed operands: O = softmax(scale * Q K^T [causal]) V per (batch, head),
+// with the scores kept in registers.  This is layout propagation at register level: with K's
+// fragment in the A slot and Q's in the B slot the MFMA leaves S^T tiles with lanes on the
+// query index and registers on the key index, which (after exp and, for bf16, pairwise
+// rounding) already are the fragments of P as a left operand of P V, so nothing is
+// transposed or staged between the two products.  The row maximum and sum are per lane (one
+// query) over registers, plus one exchange between the two half waves.
+//
+// Operands: Q = P(Q; tq, DH), K = P(K; tk, DH) (a left-operand image of K, i.e. the
+// right-operand image of K^T), V = P(V; DH, tk) (right operand), O = P(O; tq, DH).
+// A workgroup of four waves owns 128 queries (one 32-group per wave) of one (batch, head)
+// and walks the keys 64 at a time; the 64 keys' fragments of K and V go through a two-stage
+// LDS ring with the direct global->LDS transfer, one barrier per step.  Groups or K blocks
+// that do not exist (ragged tk) are replaced by the last existing one; their keys are masked.
+struct AttnFrag {
+    // source of stage fragment f (0 <= f < NF) of key step j, for this lane
+    template <typename T, int DH>
+    __device__ __forceinline__ static const char *src(const AttnArgs &a, const char *Kb, const char *Vb, int f, int j,
+                                                      int lane)
+    {
+        constexpr int FD = DH / T::KF, FK = 32 / T::KF, NFK = 2 * FD;
+        if (f < NFK) {
+            const int kg = f / FD, fd = f % FD;
+            int grp = 2 * j + kg;
+            grp = grp < a.k_groups ? grp : a.k_groups - 1;
+            return Kb + (int64_t)(fd / 4) * a.k_kbs + (int64_t)grp * kBlockBytes + (fd % 4) * kFragBytes + lane * 16;
+        }
+        const int fv = f - NFK;
+        const int dg = fv / (2 * FK), st = fv % (2 * FK);
+        const int kidx = 64 * j + T::KF * st;
+        int vkb = kidx / T::KB;
+        vkb = vkb < a.v_nkb ? vkb : a.v_nkb - 1;
+        return Vb + (int64_t)vkb * a.v_kbs + (int64_t)dg * kBlockBytes + ((kidx % T::KB) / T::KF) * kFragBytes + lane * 16;
+    }
+};
+
+template <typename T, int DH>
+__global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
+{
+    constexpr int NW = 4;
+    constexpr int FD = DH / T::KF;  // fragments along d of a 32-row group of Q or K
+    constexpr int FK = 32 / T::KF;  // fragments along the keys of a 32-key group (P and V)
+    constexpr int DG = DH / 32;     // 32-groups of d
+    constexpr int NFK = 2 * FD, NFV = DG * 2 * FK, NF = NFK + NFV, FPW = NF / NW;
+    constexpr int STAGE = NF * kFragBytes;
+    static_assert(NF % NW == 0, "stage must divide over the waves");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane >> 5;
+    // heaviest query blocks (most keys under a causal mask) first
+    const int nqb = (a.q_groups + NW - 1) / NW;
+    const int qb = nqb - 1 - (int)(blockIdx.x / (uint32_t)a.batch);
+    const int b = (int)(blockIdx.x % (uint32_t)a.batch);
+    const int g = qb * NW + w;
+    const bool have_g = g < a.q_groups;
+    const int q = 32 * g + (lane & 31);
+    const int shift = a.tk - a.tq;
+    int last = a.causal ? q + shift : a.tk - 1;  // last key this lane's query sees
+    last = last < a.tk - 1 ? last : a.tk - 1;
+    if (q >= a.tq) last = -1;
+    // keys the workgroup has to walk, and whether this wave can skip masking in a step
+    int wg_last = a.causal ? 32 * (qb * NW + NW) - 1 + shift : a.tk - 1;
+    wg_last = wg_last < a.tk - 1 ? wg_last : a.tk - 1;
+    const int nsteps = wg_last < 0 ? 0 : wg_last / 64 + 1;
+    int wave_min_last = a.causal ? 32 * g + shift : a.tk - 1;  // smallest `last` among this wave's lanes
+    wave_min_last = wave_min_last < a.tk - 1 ? wave_min_last : a.tk - 1;
+    if (32 * g + 31 >= a.tq) wave_min_last = -1;
+
+    const char *Kb = a.K + (int64_t)(b / a.k_div) * a.k_slot;
+    const char *Vb = a.V + (int64_t)(b / a.v_div) * a.v_slot;
+    auto issue = [&](int j) {
+#pragma unroll
+        for (int i = 0; i < FPW; ++i) {
+            const int f = i * NW + w;
+            lds_dma16(AttnFrag::src<T, DH>(a, Kb, Vb, f, j, lane), sbase + (j & 1) * STAGE + f * kFragBytes);
+        }
+    };
+
+    uint4 qf[FD];
+#pragma unroll
+    for (int fd = 0; fd < FD; ++fd) {
+        qf[fd] = make_uint4(0u, 0u, 0u, 0u);
+        if (have_g)
+            qf[fd] = *(const uint4 *)(a.Q + (int64_t)b * a.q_slot + (int64_t)(fd / 4) * a.q_kbs + (int64_t)g * kBlockBytes +
+                                      (fd % 4) * kFragBytes + lane * 16);
+    }
+    f32x16 o[DG];
+#pragma unroll
+    for (int dg = 0; dg < DG; ++dg)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[dg][e] = 0.0f;
+    float m = kNegBig, lsum = 0.0f;  // running maximum (shared by the half waves) and this lane's part of the sum
+    const float sl = a.sl;
+
+    if (nsteps > 0) issue(0);
+    for (int j = 0; j < nsteps; ++j) {
+        wait_vmcnt<0>();
+        __syncthreads();  // step j's fragments are in LDS; everyone is done reading the other stage
+        if (j + 1 < nsteps) issue(j + 1);
+        const char *sb = smem + (j & 1) * STAGE + lane * 16;
+
+        // S^T tiles: registers run along 32 keys, lanes along the wave's 32 queries
+        f32x16 s[2];
+#pragma unroll
+        for (int kg = 0; kg < 2; ++kg) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[kg][e] = 0.0f;
+#pragma unroll
+            for (int fd = 0; fd < FD; ++fd)
+                mma_frag<T>(s[kg], *(const uint4 *)(sb + (kg * FD + fd) * kFragBytes), qf[fd]);
+        }
+        // online softmax; key of register e of tile kg: 64j + 32kg + 8(e/4) + 4h + e%4
+        const int key0 = 64 * j + 4 * h;
+        const bool masked = 64 * j + 63 > wave_min_last;  // wave-uniform
+        float bm = m;
+        if (masked) {
+#pragma unroll
+            for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    s[kg][e] = (key0 + 32 * kg + 8 * (e >> 2) + (e & 3) <= last) ? s[kg][e] : -__builtin_inff();
+        }
+#pragma unroll
+        for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) bm = fmaxf(bm, s[kg][e] * sl);
+        bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+        const float alpha = __builtin_amdgcn_exp2f(m - bm);
+        m = bm;
+        float psum = 0.0f;
+#pragma unroll
+        for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                s[kg][e] = __builtin_amdgcn_exp2f(fmaf(s[kg][e], sl, -m));
+                psum += s[kg][e];
+            }
+        lsum = lsum * alpha + psum;
+#pragma unroll
+        for (int dg = 0; dg < DG; ++dg)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[dg][e] *= alpha;
+        // P's fragments are the registers as they stand (bf16: rounded in pairs); O^T += V^T P^T
+#pragma unroll
+        for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+            for (int c = 0; c < FK; ++c) {
+                uint4 pf;
+                if constexpr (T::ES == 4) {
+                    pf = make_uint4(__float_as_uint(s[kg][4 * c]), __float_as_uint(s[kg][4 * c + 1]),
+                                    __float_as_uint(s[kg][4 * c + 2]), __float_as_uint(s[kg][4 * c + 3]));
+                } else {
+                    pf = make_uint4(bf16_pack2(s[kg][8 * c], s[kg][8 * c + 1]), bf16_pack2(s[kg][8 * c + 2], s[kg][8 * c + 3]),
+                                    bf16_pack2(s[kg][8 * c + 4], s[kg][8 * c + 5]), bf16_pack2(s[kg][8 * c + 6], s[kg][8 * c + 7]));
+                }
+#pragma unroll
+                for (int dg = 0; dg < DG; ++dg)
+                    mma_frag<T>(o[dg], *(const uint4 *)(sb + (NFK + dg * 2 * FK + kg * FK + c) * kFragBytes), pf);
+            }
+    }
+    wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
+
+    if (!have_g) return;
+    const float l = lsum + __shfl_xor(lsum, 32, 64);
+    const float inv = (l > 0.0f && q < a.tq) ? 1.0f / l : 0.0f;  // padding rows and rows without keys: zeros
+    char *Ob = a.O + (int64_t)b * a.o_slot + (int64_t)g * kBlockBytes + lane * 16;
+#pragma unroll
+    for (int dg = 0; dg < DG; ++dg) {
+        float v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = o[dg][e] * inv;
+        if constexpr (T::ES == 4) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                *(uint4 *)(Ob + (int64_t)dg * a.o_kbs + c * kFragBytes) =
+                    make_uint4(__float_as_uint(v[4 * c]), __float_as_uint(v[4 * c + 1]), __float_as_uint(v[4 * c + 2]),
+                               __float_as_uint(v[4 * c + 3]));
+        } else {
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                *(uint4 *)(Ob + (int64_t)(dg >> 1) * a.o_kbs + (2 * (dg & 1) + c) * kFragBytes) =
+                    make_uint4(bf16_pack2(v[8 * c], v[8 * c + 1]), bf16_pack2(v[8 * c + 2], v[8 * c + 3]),
+                               bf16_pack2(v[8 * c + 4], v[8 * c + 5]), bf16_pack2(v[8 * c + 6], v[8 * c + 7]));
+        }
+    }
+}
+
+template <typename T, int DH>
+static hipError_t launch_attention_dh(const AttnArgs &a, hipStream_t st)
+{
+    constexpr int NF = 2 * (DH / T::KF) + (DH / 32) * 2 * (32 / T::KF);
+    constexpr size_t lds = 2 * (size_t)NF * kFragBytes;
+    static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
+    auto kern = attention_kernel<T, DH>;
+    if (lds > 64 * 1024) {
+        static bool done = false;
+        if (!done) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            done = true;
+        }
+    }
+    const int64_t grid = (int64_t)((a.q_groups + 3) / 4) * a.batch;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention(const AttnArgs &a, int dtype, int head_dim, hipStream_t st)
+{
+    if (a.batch <= 0 || a.tq <= 0) return hipSuccess;
+    if (head_dim == 64)
+        return dtype == LPG_F32 ? launch_attention_dh<F32, 64>(a, st) : launch_attention_dh<BF16, 64>(a, st);
+    if (head_dim == 128)
+        return dtype == LPG_F32 ? launch_attention_dh<F32, 128>(a, st) : launch_attention_dh<BF16, 128>(a, st);
+    return hipErrorInvalidValue;
+}
+
 // Tile configurations (TLG, TRG, WL, WR) in 32-groups; index = position in this list.
 struct TileCfg {
     int tlg, trg, wl, wr;

@@ -1,0 +1,135 @@
+"""GPU parity of lpg_attention_packed (score GEMM, scale, causal mask, softmax, weighted sum in
+one kernel; Alg. 2) against the fp64 oracle, and against the three-stage chain it replaces.
+
+Tolerance: fp32 - two chained contractions (head_dim, then up to 4200 keys) with an fp32
+softmax between them, relative Frobenius error per head <= 3e-5 (three stages of 1e-5);
+bf16 - probabilities rounded to bf16 before the second product, <= 2e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref, workloads
+from paper_2604_04599_amd import api, chains, inputs
+from paper_2604_04599_amd.api import (LPG_BF16, LPG_CHAIN_CANONICAL, LPG_CHAIN_PROPAGATED, LPG_F32, LPG_PACKED_A,
+                                      LPG_PACKED_B, LPG_ROW_MAJOR, desc)
+from gpu_util import NP_RAW, dev_empty, host, pack_dev, stream, unpack_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL = {LPG_F32: 3e-5, LPG_BF16: 2e-2}
+
+
+def run_attention(q, k, v, dtype, scale, causal):
+    """q [tq x dh], k, v [tk x dh] float32 -> O [tq x dh] as float64, plus the operand values the
+    kernel saw (bf16-rounded for bf16)."""
+    pq, qd = pack_dev(q, LPG_PACKED_A, dtype)
+    pk, kd = pack_dev(k, LPG_PACKED_A, dtype)           # left-operand image of K
+    pv, vd = pack_dev(v, LPG_PACKED_B, dtype)
+    od = desc(LPG_PACKED_A, dtype, q.shape[0], q.shape[1])
+    po = dev_empty(api.lpg_packed_bytes(od), fill=0xA5)
+    api.lpg_attention_packed(pq, qd, pk, kd, pv, vd, po, od, scale, causal, stream())
+    got = unpack_dev(po, od)
+    raw = host(po, NP_RAW[dtype])
+    assert np.count_nonzero(raw) == np.count_nonzero(got)          # padding rows of O are zero
+    return got, unpack_dev(pq, qd), unpack_dev(pk, kd), unpack_dev(pv, vd)
+
+
+def oracle_attention(q, k, v, scale, causal):
+    p = ref.softmax_rows(ref.gemm(q, k.T.copy()), scale=scale, causal=causal)
+    return ref.gemm(p, v)
+
+
+# (queries, keys, head_dim): one step, ragged tails, more queries than keys and the reverse,
+# several 128-query blocks, a long row
+SHAPES = [(32, 64, 64), (1, 1, 64), (70, 70, 64), (200, 333, 64), (300, 100, 64), (130, 4200, 64), (257, 257, 128)]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", [LPG_F32, LPG_BF16])
+@pytest.mark.parametrize("tq,tk,dh", SHAPES)
+def test_attention_matches_oracle(tq, tk, dh, dtype, causal):
+    rng = np.random.default_rng(tq * 7 + tk + dh)
+    q, k, v = (rng.standard_normal((n, dh)).astype(np.float32) for n in (tq, tk, tk))
+    got, qs, ks, vs = run_attention(q, k, v, dtype, dh ** -0.5, causal)
+    want = oracle_attention(qs, ks, vs, dh ** -0.5, causal)
+    assert ref.rel_frobenius(got, want) <= TOL[dtype]
+    if causal and tq > tk:
+        assert np.all(got[:tq - tk] == 0.0)                        # queries before the first key see nothing
+
+
+def test_attention_with_sharp_scores():
+    """Large logits (one key dominates each row) and a row of equal logits."""
+    rng = np.random.default_rng(5)
+    q = rng.standard_normal((64, 64)).astype(np.float32) * 6
+    k = rng.standard_normal((96, 64)).astype(np.float32) * 6
+    v = rng.standard_normal((96, 64)).astype(np.float32)
+    q[3] = 0.0                                                     # uniform attention for this query
+    got, qs, ks, vs = run_attention(q, k, v, LPG_F32, 1.0, False)
+    want = oracle_attention(qs, ks, vs, 1.0, False)
+    assert ref.rel_frobenius(got, want) <= TOL[LPG_F32]
+    assert np.allclose(got[3], vs.mean(axis=0), rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("dtype", [LPG_F32, LPG_BF16])
+def test_attention_heads_views_and_shared_kv(dtype):
+    """Four query heads over two key/value heads, all as views of [t x heads*dh] parents, the
+    keys described as K^T (PACKED_B), the way the decoder layer calls it."""
+    t, dh, nq, nkv = 160, 64, 4, 2
+    rng = np.random.default_rng(11)
+    q = rng.standard_normal((t, nq * dh)).astype(np.float32)
+    k = rng.standard_normal((t, nkv * dh)).astype(np.float32)
+    v = rng.standard_normal((t, nkv * dh)).astype(np.float32)
+    pq, qd = pack_dev(q, LPG_PACKED_A, dtype)
+    pk, kd = pack_dev(k, LPG_PACKED_A, dtype)
+    pv, vd = pack_dev(v, LPG_PACKED_B, dtype)
+    od = desc(LPG_PACKED_A, dtype, t, nq * dh)
+    po = dev_empty(api.lpg_packed_bytes(od), fill=0)
+    rep = nq // nkv
+    q_view = desc(LPG_PACKED_A, dtype, t, dh, parent=(t, nq * dh), batch=nq, batch_step=(0, dh))
+    kt_view = desc(LPG_PACKED_B, dtype, dh, t, parent=(nkv * dh, t), batch=nq, batch_div=rep, batch_step=(dh, 0))
+    v_view = desc(LPG_PACKED_B, dtype, t, dh, parent=(t, nkv * dh), batch=nq, batch_div=rep, batch_step=(0, dh))
+    o_view = desc(LPG_PACKED_A, dtype, t, dh, parent=(t, nq * dh), batch=nq, batch_step=(0, dh))
+    api.lpg_attention_packed(pq, q_view, pk, kt_view, pv, v_view, po, o_view, dh ** -0.5, True, stream())
+    got = unpack_dev(po, od)
+    qs, ks, vs = unpack_dev(pq, qd), unpack_dev(pk, kd), unpack_dev(pv, vd)
+    for h in range(nq):
+        g = h // rep
+        want = oracle_attention(qs[:, h * dh:(h + 1) * dh].copy(), ks[:, g * dh:(g + 1) * dh].copy(),
+                                vs[:, g * dh:(g + 1) * dh].copy(), dh ** -0.5, True)
+        assert ref.rel_frobenius(got[:, h * dh:(h + 1) * dh], want) <= TOL[dtype], h
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_chain_flash_against_three_stage_chain(causal):
+    inp, shape = inputs.make("attention", heads=3, t=200, dh=64)
+    ch3 = chains.build("attention", inp, shape, softmax=True, causal=causal)
+    ch1 = chains.build("attention", inp, shape, softmax=True, causal=causal, flash=True)
+    ch3.run()
+    ch1.run()
+    three, one = ch3.output("O").copy(), ch1.output("O").copy()
+    want = workloads.attention(inp, softmax=True, causal=causal)
+    for h in range(shape["heads"]):
+        assert ref.rel_frobenius(one[h], want["O"][h]) <= TOL[LPG_F32]
+        assert ref.rel_frobenius(one[h], three[h]) <= TOL[LPG_F32]
+    ch1.outputs["O"].fill_(float("nan"))
+    ch1.run(LPG_CHAIN_CANONICAL)                                   # nothing to unpack between stages: same kernels
+    assert np.array_equal(ch1.output("O").view(np.uint32), one.view(np.uint32))
+
+
+def test_llama_layer_flash_small_and_full():
+    inp, shape = inputs.make("llama_layer", t=192, hidden=256, n_q=4, n_kv=2, ffn=320)
+    ch = chains.build("llama_layer", inp, shape, flash=True)
+    ch.run()
+    want = workloads.llama_layer(inp, 4, 2, eps=1.0 / shape["inv_eps"], rope_base=float(shape["rope_base"]))
+    assert ref.rel_frobenius(ch.fetch("O"), want["O"]) <= 2e-2
+    assert ref.rel_frobenius(ch.output("Y"), want["Y"]) <= 2e-2
+    del ch
+    inp, shape = inputs.make("llama_layer")
+    ch = chains.build("llama_layer", inp, shape, flash=True)
+    ch.run()
+    rows = np.arange(11, shape["t"], 409)
+    want = workloads.llama_layer(inp, shape["n_q"], shape["n_kv"], eps=1.0 / shape["inv_eps"],
+                                 rope_base=float(shape["rope_base"]), rows=rows)
+    assert ref.rel_frobenius(ch.fetch("O")[rows], want["O"]) <= 2e-2
+    assert ref.rel_frobenius(ch.output("Y")[rows], want["Y"]) <= 2e-2

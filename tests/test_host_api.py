@@ -4,6 +4,7 @@ caught on the host (no compute call is made here)."""
 import ctypes
 import os
 import re
+import subprocess
 
 import numpy as np
 import pytest
@@ -27,10 +28,27 @@ def test_library_exports_every_declared_symbol():
     assert "gfx950" in api.lpg_version()
 
 
-def test_struct_sizes_match_header():
+def test_struct_layouts_match_header(tmp_path):
+    """The ctypes mirrors against what a C compiler makes of include/lpg.h: sizes and the
+    offset of every field."""
     # lpg_desc: 2 int32 + 7 int64 + 2 int32 + 3 int64
     assert ctypes.sizeof(api.lpg_desc) == 8 + 7 * 8 + 8 + 3 * 8
-    assert ctypes.sizeof(api.lpg_stage) == 24 + 5 * 8 + 3 * ctypes.sizeof(api.lpg_desc)
+    fields = {"lpg_desc": [n for n, _ in api.lpg_desc._fields_], "lpg_stage": [n for n, _ in api.lpg_stage._fields_]}
+    src = ['#include <stdio.h>', '#include <stddef.h>', '#include "lpg.h"', 'int main(void) {']
+    for st, names in fields.items():
+        src.append(f'printf("{st} %zu\\n", sizeof({st}));')
+        for n in names:
+            src.append(f'printf("{st}.{n} %zu\\n", offsetof({st}, {n}));')
+    src += ['return 0; }']
+    c = tmp_path / "layout.c"
+    c.write_text("\n".join(src))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(c), "-o", str(exe)], check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for st, cls in (("lpg_desc", api.lpg_desc), ("lpg_stage", api.lpg_stage)):
+        assert int(got[st]) == ctypes.sizeof(cls)
+        for n in fields[st]:
+            assert int(got[f"{st}.{n}"]) == getattr(cls, n).offset, (st, n)
 
 
 @pytest.mark.parametrize("dtype,es", [(LPG_F32, 4), (LPG_BF16, 2)])
@@ -132,6 +150,19 @@ def test_descriptor_errors_are_caught_on_the_host():
     assert _err(api.lpg_rope_tables, fake, fake, 8, 7, 10000.0, 0) == api.LPG_EINVAL
     assert _err(api.lpg_rope_tables, fake, fake, 8, 8, -1.0, 0) == api.LPG_EINVAL
     assert _err(api.lpg_rope_tables, None, fake, 8, 8, 10000.0, 0) == api.LPG_EINVAL
+    # fused attention: roles, head_dim, shapes, dtype, aliasing
+    qd, kd, vd = desc(LPG_PACKED_A, LPG_F32, 96, 64), desc(LPG_PACKED_A, LPG_F32, 80, 64), desc(LPG_PACKED_B, LPG_F32, 80, 64)
+    od = desc(LPG_PACKED_A, LPG_F32, 96, 64)
+    q, k, v, o = fake, 2 * fake, 3 * fake, 4 * fake
+    assert _err(api.lpg_attention_packed, q, desc(LPG_PACKED_B, LPG_F32, 96, 64), k, kd, v, vd, o, od, 1.0) == api.LPG_ELAYOUT
+    assert _err(api.lpg_attention_packed, q, desc(LPG_PACKED_A, LPG_F32, 96, 32), k, desc(LPG_PACKED_A, LPG_F32, 80, 32), v,
+                desc(LPG_PACKED_B, LPG_F32, 80, 32), o, desc(LPG_PACKED_A, LPG_F32, 96, 32), 1.0) == api.LPG_EUNSUPPORTED
+    assert _err(api.lpg_attention_packed, q, qd, k, kd, v, desc(LPG_PACKED_B, LPG_F32, 64, 64), o, od, 1.0) == api.LPG_EINVAL
+    assert _err(api.lpg_attention_packed, q, qd, k, kd, v, desc(LPG_PACKED_A, LPG_F32, 80, 64), o, od, 1.0) == api.LPG_EINVAL
+    assert _err(api.lpg_attention_packed, q, qd, k, desc(LPG_PACKED_A, LPG_BF16, 80, 64), v, vd, o, od, 1.0) == api.LPG_EUNSUPPORTED
+    assert _err(api.lpg_attention_packed, q, qd, k, kd, v, vd, q, od, 1.0) == api.LPG_EINVAL
+    assert _err(api.lpg_attention_packed, q, qd, k, kd, v, vd, o, od, -1.0) == api.LPG_EINVAL
+    assert _err(api.lpg_attention_packed, q, qd, k, kd, v, vd, o, desc(LPG_PACKED_A, LPG_F32, 96, 64, batch=2), 1.0) == api.LPG_EINVAL
 
 
 def test_chain_link_check_and_workspace():
