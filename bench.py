@@ -84,7 +84,7 @@ def time_gemm_launches(ch, steps):
     return total_ms * 1e-3 / len(pairs), nflops / ngemm
 
 
-STAGE_NAMES = {0: "pack", 1: "gemm", 2: "elementwise", 3: "unpack", 4: "softmax", 5: "rmsnorm", 6: "rope"}
+STAGE_NAMES = {0: "pack", 1: "gemm", 2: "elementwise", 3: "unpack", 4: "softmax", 5: "rmsnorm", 6: "rope", 7: "attention"}
 
 
 def stage_breakdown(ch, steps):
@@ -125,6 +125,12 @@ def stage_breakdown(ch, steps):
             r, c = o.rows, o.cols
             kept = r * c if not s.op else sum(min(c, max(0, j + c - r + 1)) for j in range(r))
             nbytes = nb * (kept + r * c) * es[o.dtype]
+        elif s.type == api.LPG_STAGE_ATTENTION:
+            tq, dh, tk = o.rows, o.cols, s.in2_d.rows
+            pairs_kept = tq * tk if not s.op else sum(min(tk, max(0, j + tk - tq + 1)) for j in range(tq))
+            nbytes = nb * (2 * tq * dh + 2 * tk * dh // max(s.in1_d.batch_div, 1)) * es[o.dtype]
+            row.update({"queries": tq, "keys": tk, "head_dim": dh, "batch": nb,
+                        "tflops": round(4.0 * pairs_kept * dh * nb / us / 1e6, 1)})
         else:
             nbytes = nb * o.rows * o.cols * es[o.dtype] * 2
         row["hbm_gbps"] = round(nbytes / us / 1e3, 1)
@@ -189,6 +195,14 @@ def measure(name, steps, warmup, shape_over=None, modes="both", options=None):
         res["fused_boundaries_ms_per_step"] = round(t_f * 1e3, 4)
         res["fused_boundaries_tflops"] = round(flops / t_f / 1e12, 2)
         del fch
+        if name == "llama_layer" or options.get("softmax"):
+            # the attention block as one kernel that keeps the scores in registers
+            ach = chains.build(name, inp, shape, flash=True, **options)
+            t_a = time_chain(ach, api.LPG_CHAIN_PROPAGATED, steps, warmup)
+            res["fused_attention_ms_per_step"] = round(t_a * 1e3, 4)
+            res["fused_attention_tflops"] = round(flops / t_a / 1e12, 2)
+            res["fused_attention_stages"] = stage_breakdown(ach, max(3, steps // 2))
+            del ach
         res["stages"] = stage_breakdown(ch, max(3, steps // 2))
         if name == "two_gemm":
             # launch-bound: the same chain replayed from a HIP graph
@@ -299,7 +313,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workloads", default="all",
-                    help="comma list of extra workloads to report beside the headline, 'all' or 'none'")
+                    help="comma list of extra workloads to report beside the headline (the five configs' names, "
+                         "attention_softmax, llama_layer), 'all' or 'none'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default=None,
                     help="profiling aid: time just this workload (a workload name, or "
@@ -379,7 +394,7 @@ def main():
     elif args.workloads == "none":
         names = []
     else:
-        names = [w for w in args.workloads.split(",") if w and w != HEADLINE]
+        names = [w for w in args.workloads.split(",") if w in inputs.WORKLOADS and w != HEADLINE]
     per = {HEADLINE: head}
     cpu = None
     if not args.no_cpu_baseline:

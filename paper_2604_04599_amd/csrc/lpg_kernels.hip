@@ -1236,142 +1236,159 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = lane >> 5;
-    // heaviest query blocks (most keys under a causal mask) first
+    // Under a causal mask a query block's work grows with its position, so a workgroup takes
+    // a pair: block p from the end, then block p from the start (the middle one alone when the
+    // count is odd); every workgroup then walks the same number of key steps.
     const int nqb = (a.q_groups + NW - 1) / NW;
-    const int qb = nqb - 1 - (int)(blockIdx.x / (uint32_t)a.batch);
+    const int pair = (int)(blockIdx.x / (uint32_t)a.batch);
     const int b = (int)(blockIdx.x % (uint32_t)a.batch);
-    const int g = qb * NW + w;
-    const bool have_g = g < a.q_groups;
-    const int q = 32 * g + (lane & 31);
+    const int nparts = (a.causal && pair != nqb - 1 - pair) ? 2 : 1;
     const int shift = a.tk - a.tq;
-    int last = a.causal ? q + shift : a.tk - 1;  // last key this lane's query sees
-    last = last < a.tk - 1 ? last : a.tk - 1;
-    if (q >= a.tq) last = -1;
-    // keys the workgroup has to walk, and whether this wave can skip masking in a step
-    int wg_last = a.causal ? 32 * (qb * NW + NW) - 1 + shift : a.tk - 1;
-    wg_last = wg_last < a.tk - 1 ? wg_last : a.tk - 1;
-    const int nsteps = wg_last < 0 ? 0 : wg_last / 64 + 1;
-    int wave_min_last = a.causal ? 32 * g + shift : a.tk - 1;  // smallest `last` among this wave's lanes
-    wave_min_last = wave_min_last < a.tk - 1 ? wave_min_last : a.tk - 1;
-    if (32 * g + 31 >= a.tq) wave_min_last = -1;
-
+    const float sl = a.sl;
     const char *Kb = a.K + (int64_t)(b / a.k_div) * a.k_slot;
     const char *Vb = a.V + (int64_t)(b / a.v_div) * a.v_slot;
-    auto issue = [&](int j) {
+    int ring = 0;  // steps issued so far: the ring stage alternates across the parts too
+    auto issue = [&](int j, int stage) {
 #pragma unroll
         for (int i = 0; i < FPW; ++i) {
             const int f = i * NW + w;
-            lds_dma16(AttnFrag::src<T, DH>(a, Kb, Vb, f, j, lane), sbase + (j & 1) * STAGE + f * kFragBytes);
+            lds_dma16(AttnFrag::src<T, DH>(a, Kb, Vb, f, j, lane), sbase + stage * STAGE + f * kFragBytes);
         }
     };
 
-    uint4 qf[FD];
-#pragma unroll
-    for (int fd = 0; fd < FD; ++fd) {
-        qf[fd] = make_uint4(0u, 0u, 0u, 0u);
-        if (have_g)
-            qf[fd] = *(const uint4 *)(a.Q + (int64_t)b * a.q_slot + (int64_t)(fd / 4) * a.q_kbs + (int64_t)g * kBlockBytes +
-                                      (fd % 4) * kFragBytes + lane * 16);
-    }
-    f32x16 o[DG];
-#pragma unroll
-    for (int dg = 0; dg < DG; ++dg)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[dg][e] = 0.0f;
-    float m = kNegBig, lsum = 0.0f;  // running maximum (shared by the half waves) and this lane's part of the sum
-    const float sl = a.sl;
+    for (int part = 0; part < nparts; ++part) {
+        const int qb = a.causal ? (part == 0 ? nqb - 1 - pair : pair) : pair;
+        const int g = qb * NW + w;
+        const bool have_g = g < a.q_groups;
+        const int q = 32 * g + (lane & 31);
+        int last = a.causal ? q + shift : a.tk - 1;  // last key this lane's query sees
+        last = last < a.tk - 1 ? last : a.tk - 1;
+        if (q >= a.tq) last = -1;
+        // keys the workgroup has to walk, and whether this wave can skip masking in a step
+        int wg_last = a.causal ? 32 * (qb * NW + NW) - 1 + shift : a.tk - 1;
+        wg_last = wg_last < a.tk - 1 ? wg_last : a.tk - 1;
+        const int nsteps = wg_last < 0 ? 0 : wg_last / 64 + 1;
+        int wave_min_last = a.causal ? 32 * g + shift : a.tk - 1;  // smallest `last` among this wave's lanes
+        wave_min_last = wave_min_last < a.tk - 1 ? wave_min_last : a.tk - 1;
+        if (32 * g + 31 >= a.tq) wave_min_last = -1;
 
-    if (nsteps > 0) issue(0);
-    for (int j = 0; j < nsteps; ++j) {
-        wait_vmcnt<0>();
-        __syncthreads();  // step j's fragments are in LDS; everyone is done reading the other stage
-        if (j + 1 < nsteps) issue(j + 1);
-        const char *sb = smem + (j & 1) * STAGE + lane * 16;
-
-        // S^T tiles: registers run along 32 keys, lanes along the wave's 32 queries
-        f32x16 s[2];
+        uint4 qf[FD];
 #pragma unroll
-        for (int kg = 0; kg < 2; ++kg) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s[kg][e] = 0.0f;
-#pragma unroll
-            for (int fd = 0; fd < FD; ++fd)
-                mma_frag<T>(s[kg], *(const uint4 *)(sb + (kg * FD + fd) * kFragBytes), qf[fd]);
+        for (int fd = 0; fd < FD; ++fd) {
+            qf[fd] = make_uint4(0u, 0u, 0u, 0u);
+            if (have_g)
+                qf[fd] = *(const uint4 *)(a.Q + (int64_t)b * a.q_slot + (int64_t)(fd / 4) * a.q_kbs + (int64_t)g * kBlockBytes +
+                                          (fd % 4) * kFragBytes + lane * 16);
         }
-        // online softmax; key of register e of tile kg: 64j + 32kg + 8(e/4) + 4h + e%4
-        const int key0 = 64 * j + 4 * h;
-        const bool masked = 64 * j + 63 > wave_min_last;  // wave-uniform
-        float bm = m;
-        if (masked) {
-#pragma unroll
-            for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    s[kg][e] = (key0 + 32 * kg + 8 * (e >> 2) + (e & 3) <= last) ? s[kg][e] : -__builtin_inff();
-        }
-#pragma unroll
-        for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) bm = fmaxf(bm, s[kg][e] * sl);
-        bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-        const float alpha = __builtin_amdgcn_exp2f(m - bm);
-        m = bm;
-        float psum = 0.0f;
-#pragma unroll
-        for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                s[kg][e] = __builtin_amdgcn_exp2f(fmaf(s[kg][e], sl, -m));
-                psum += s[kg][e];
-            }
-        lsum = lsum * alpha + psum;
+        f32x16 o[DG];
 #pragma unroll
         for (int dg = 0; dg < DG; ++dg)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) o[dg][e] *= alpha;
-        // P's fragments are the registers as they stand (bf16: rounded in pairs); O^T += V^T P^T
+            for (int e = 0; e < 16; ++e) o[dg][e] = 0.0f;
+        float m = kNegBig, lsum = 0.0f;  // reference maximum (shared by the half waves) and this lane's part of the sum
+
+        // The stage written here was last read two steps ago (possibly by the previous part),
+        // and every wave has passed the barrier of the step in between.
+        if (nsteps > 0) issue(0, ring & 1);
+        for (int j = 0; j < nsteps; ++j, ++ring) {
+            wait_vmcnt<0>();
+            __syncthreads();  // step j's fragments are in LDS; everyone is done reading the other stage
+            if (j + 1 < nsteps) issue(j + 1, (ring + 1) & 1);
+            const char *sb = smem + (ring & 1) * STAGE + lane * 16;
+
+            // S^T tiles: registers run along 32 keys, lanes along the wave's 32 queries
+            f32x16 s[2];
 #pragma unroll
-        for (int kg = 0; kg < 2; ++kg)
+            for (int kg = 0; kg < 2; ++kg) {
 #pragma unroll
-            for (int c = 0; c < FK; ++c) {
-                uint4 pf;
-                if constexpr (T::ES == 4) {
-                    pf = make_uint4(__float_as_uint(s[kg][4 * c]), __float_as_uint(s[kg][4 * c + 1]),
-                                    __float_as_uint(s[kg][4 * c + 2]), __float_as_uint(s[kg][4 * c + 3]));
-                } else {
-                    pf = make_uint4(bf16_pack2(s[kg][8 * c], s[kg][8 * c + 1]), bf16_pack2(s[kg][8 * c + 2], s[kg][8 * c + 3]),
-                                    bf16_pack2(s[kg][8 * c + 4], s[kg][8 * c + 5]), bf16_pack2(s[kg][8 * c + 6], s[kg][8 * c + 7]));
-                }
+                for (int e = 0; e < 16; ++e) s[kg][e] = 0.0f;
+#pragma unroll
+                for (int fd = 0; fd < FD; ++fd)
+                    mma_frag<T>(s[kg], *(const uint4 *)(sb + (kg * FD + fd) * kFragBytes), qf[fd]);
+            }
+            // online softmax; key of register e of tile kg: 64j + 32kg + 8(e/4) + 4h + e%4
+            const int key0 = 64 * j + 4 * h;
+            const bool masked = 64 * j + 63 > wave_min_last;  // wave-uniform
+            if (masked) {
+#pragma unroll
+                for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        s[kg][e] = (key0 + 32 * kg + 8 * (e >> 2) + (e & 3) <= last) ? s[kg][e] : -__builtin_inff();
+            }
+            float bmx = -__builtin_inff();
+#pragma unroll
+            for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) bmx = fmaxf(bmx, s[kg][e]);
+            bmx = fmaxf(bmx, __shfl_xor(bmx, 32, 64));
+            // The reference point m of the exponentials only has to stay within 2^8 of the true
+            // running maximum (the final division cancels it), so O and the sum are rescaled only
+            // in the steps where some query of the wave moved further than that.
+            const float bm = bmx * sl;
+            if (__any(bm > m + 8.0f)) {
+                const float mn = fmaxf(m, bm);
+                const float alpha = __builtin_amdgcn_exp2f(m - mn);
+                m = mn;
+                lsum *= alpha;
 #pragma unroll
                 for (int dg = 0; dg < DG; ++dg)
-                    mma_frag<T>(o[dg], *(const uint4 *)(sb + (NFK + dg * 2 * FK + kg * FK + c) * kFragBytes), pf);
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) o[dg][e] *= alpha;
             }
-    }
-    wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
-
-    if (!have_g) return;
-    const float l = lsum + __shfl_xor(lsum, 32, 64);
-    const float inv = (l > 0.0f && q < a.tq) ? 1.0f / l : 0.0f;  // padding rows and rows without keys: zeros
-    char *Ob = a.O + (int64_t)b * a.o_slot + (int64_t)g * kBlockBytes + lane * 16;
+            float psum = 0.0f;
 #pragma unroll
-    for (int dg = 0; dg < DG; ++dg) {
-        float v[16];
+            for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] = o[dg][e] * inv;
-        if constexpr (T::ES == 4) {
+                for (int e = 0; e < 16; ++e) {
+                    s[kg][e] = __builtin_amdgcn_exp2f(fmaf(s[kg][e], sl, -m));
+                    psum += s[kg][e];
+                }
+            lsum += psum;
+            // P's fragments are the registers as they stand (bf16: rounded in pairs); O^T += V^T P^T
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                *(uint4 *)(Ob + (int64_t)dg * a.o_kbs + c * kFragBytes) =
-                    make_uint4(__float_as_uint(v[4 * c]), __float_as_uint(v[4 * c + 1]), __float_as_uint(v[4 * c + 2]),
-                               __float_as_uint(v[4 * c + 3]));
-        } else {
+            for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
-                *(uint4 *)(Ob + (int64_t)(dg >> 1) * a.o_kbs + (2 * (dg & 1) + c) * kFragBytes) =
-                    make_uint4(bf16_pack2(v[8 * c], v[8 * c + 1]), bf16_pack2(v[8 * c + 2], v[8 * c + 3]),
-                               bf16_pack2(v[8 * c + 4], v[8 * c + 5]), bf16_pack2(v[8 * c + 6], v[8 * c + 7]));
+                for (int c = 0; c < FK; ++c) {
+                    uint4 pf;
+                    if constexpr (T::ES == 4) {
+                        pf = make_uint4(__float_as_uint(s[kg][4 * c]), __float_as_uint(s[kg][4 * c + 1]),
+                                        __float_as_uint(s[kg][4 * c + 2]), __float_as_uint(s[kg][4 * c + 3]));
+                    } else {
+                        pf = make_uint4(bf16_pack2(s[kg][8 * c], s[kg][8 * c + 1]), bf16_pack2(s[kg][8 * c + 2], s[kg][8 * c + 3]),
+                                        bf16_pack2(s[kg][8 * c + 4], s[kg][8 * c + 5]), bf16_pack2(s[kg][8 * c + 6], s[kg][8 * c + 7]));
+                    }
+#pragma unroll
+                    for (int dg = 0; dg < DG; ++dg)
+                        mma_frag<T>(o[dg], *(const uint4 *)(sb + (NFK + dg * 2 * FK + kg * FK + c) * kFragBytes), pf);
+                }
+        }
+        if (have_g) {
+        const float l = lsum + __shfl_xor(lsum, 32, 64);
+        const float inv = (l > 0.0f && q < a.tq) ? 1.0f / l : 0.0f;  // padding rows and rows without keys: zeros
+        char *Ob = a.O + (int64_t)b * a.o_slot + (int64_t)g * kBlockBytes + lane * 16;
+#pragma unroll
+        for (int dg = 0; dg < DG; ++dg) {
+            float v[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) v[e] = o[dg][e] * inv;
+            if constexpr (T::ES == 4) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    *(uint4 *)(Ob + (int64_t)dg * a.o_kbs + c * kFragBytes) =
+                        make_uint4(__float_as_uint(v[4 * c]), __float_as_uint(v[4 * c + 1]), __float_as_uint(v[4 * c + 2]),
+                                   __float_as_uint(v[4 * c + 3]));
+            } else {
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+                    *(uint4 *)(Ob + (int64_t)(dg >> 1) * a.o_kbs + (2 * (dg & 1) + c) * kFragBytes) =
+                        make_uint4(bf16_pack2(v[8 * c], v[8 * c + 1]), bf16_pack2(v[8 * c + 2], v[8 * c + 3]),
+                                   bf16_pack2(v[8 * c + 4], v[8 * c + 5]), bf16_pack2(v[8 * c + 6], v[8 * c + 7]));
+            }
+        }
         }
     }
+    wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
 }
 
 template <typename T, int DH>
@@ -1389,7 +1406,8 @@ static hipError_t launch_attention_dh(const AttnArgs &a, hipStream_t st)
             done = true;
         }
     }
-    const int64_t grid = (int64_t)((a.q_groups + 3) / 4) * a.batch;
+    const int nqb = (a.q_groups + 3) / 4;
+    const int64_t grid = (int64_t)(a.causal ? (nqb + 1) / 2 : nqb) * a.batch;  // causal: query blocks in pairs
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a);
     return hipGetLastError();
 }
