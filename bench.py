@@ -195,7 +195,7 @@ def measure(name, steps, warmup, shape_over=None, modes="both", options=None):
         res["fused_boundaries_ms_per_step"] = round(t_f * 1e3, 4)
         res["fused_boundaries_tflops"] = round(flops / t_f / 1e12, 2)
         del fch
-        if name == "llama_layer" or options.get("softmax"):
+        if (name == "llama_layer" or options.get("softmax")) and not options.get("flash"):
             # the attention block as one kernel that keeps the scores in registers
             ach = chains.build(name, inp, shape, flash=True, **options)
             t_a = time_chain(ach, api.LPG_CHAIN_PROPAGATED, steps, warmup)
@@ -317,8 +317,8 @@ def main():
                          "attention_softmax, llama_layer), 'all' or 'none'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default=None,
-                    help="profiling aid: time just this workload (a workload name, or "
-                         "attention_softmax_causal) and print its line")
+                    help="profiling aid: time just this workload (a workload name, attention_softmax_causal, "
+                         "llama_layer or llama_layer_fused_attention) and print its line")
     ap.add_argument("--mode", default="both", choices=["both", "propagated", "canonical"],
                     help="with --only: which chain mode(s) to run")
     ap.add_argument("--sweep", action="store_true",
@@ -376,6 +376,8 @@ def main():
         name, options = args.only, None
         if name == "attention_softmax_causal":
             name, options = "attention", {"softmax": True, "causal": True}
+        elif name == "llama_layer_fused_attention":
+            name, options = "llama_layer", {"flash": True}
         res, _, _, _ = measure(name, args.steps, args.warmup, modes=args.mode, options=options)
         print(json.dumps({"workload": args.only, **res}))
         return
