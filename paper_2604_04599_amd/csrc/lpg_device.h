@@ -1,0 +1,573 @@
+// Device code shared by the translation units of the GPU path: element types, bf16
+// conversions, the MFMA GEMM kernel with its tile configurations and launchers.
+#pragma once
+
+#include <cstdio>
+#include <cstdlib>
+#include <utility>
+
+#include "lpg_internal.h"
+
+namespace lpg {
+
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+struct F32 {
+    typedef uint32_t raw;
+    static constexpr int ES = 4, KV = 4, KF = 8, KB = 32;
+};
+struct BF16 {
+    typedef uint16_t raw;
+    static constexpr int ES = 2, KV = 8, KF = 16, KB = 64;
+};
+
+// fp32 -> bf16 bit pattern, round to nearest, ties to even; NaN stays NaN.
+__device__ __forceinline__ uint32_t bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+// two fp32 -> packed bf16 pair with the hardware converter (round to nearest even); used
+// where results are judged by tolerance, the bit-pattern routine above where bytes are
+__device__ __forceinline__ uint32_t bf16_pack2(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+template <typename S, typename D>
+__device__ __forceinline__ typename D::raw convert_raw(typename S::raw x)
+{
+    if constexpr (S::ES == D::ES) {
+        return x;
+    } else if constexpr (S::ES == 4 && D::ES == 2) {
+        return (typename D::raw)bf16_rne(__uint_as_float(x));
+    } else {
+        return (typename D::raw)((uint32_t)x << 16);
+    }
+}
+
+__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+
+// ---------------------------------------------------------------------------------
+// GEMM.  out[fl][fr] = epilogue(alpha * sum_k L[fl][k] * R[fr][k] + beta * Cin[fl][fr]),
+// L = P(L; FL, K), R = P(R; FR, K), out = P(out; free = FL, contraction = FR).
+//
+// The MFMA computes a 32x32 tile D[i][j] = sum_k Aop[i][k] * Bop[k][j]; lane l of the
+// A operand carries row i = l%32, lane l of the B operand carries column j = l%32, and
+// lane l, register r of D holds D[8*(r/4) + 4*(l/32) + r%4][l%32].  With R's fragment
+// in the A slot and L's fragment in the B slot, lanes run along out's free index and
+// each group of four registers is four consecutive contraction indices of out: the
+// accumulators already are fragments of P(out; FL, FR) and are stored as they stand.
+//
+// Workgroup tile: TLG x TRG 32-groups; WL x WR waves, each owning (TLG/WL) x (TRG/WR)
+// 32x32 tiles.  A step stages FS fragments per group (FS = 4: a whole K block, FS = 2:
+// half of one) into one of NS LDS stages used as a ring; NS-1 steps are in flight ahead of
+// the one being multiplied.  The packed block already is the register image, so the copy
+// is verbatim: each wave moves whole 1 KiB fragments with the direct global->LDS load (no
+// VGPR round trip), and every ds_read_b128 at lane*16 is conflict free.
+//
+// Workgroups are persistent: workgroup j walks the virtual tile ids j, j + G, j + 2G, ...
+// (G = grid size) and the staging ring runs across tile boundaries, so the next tile's
+// first steps are in flight while the current tile's epilogue stores drain.  Every
+// workgroup runs a fixed, finite number of steps; there is no queue and no atomics.
+
+// 16 bytes per lane, global -> LDS at lds_addr + lane*16 (lds_addr wave-uniform).  Written
+// as inline asm so that the compiler does not serialise later LDS reads of the OTHER stage
+// behind this transfer; completion is awaited explicitly (vmcnt) before the stage is read.
+__device__ __forceinline__ void lds_dma16(const void *g, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
+}
+
+template <typename IN>
+__device__ __forceinline__ void mma_frag(f32x16 &acc, const uint4 &r, const uint4 &l)
+{
+    if constexpr (IN::ES == 4) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(r.x), __uint_as_float(l.x), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(r.y), __uint_as_float(l.y), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(r.z), __uint_as_float(l.z), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(r.w), __uint_as_float(l.w), acc, 0, 0, 0);
+    } else {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, r),
+                                                      __builtin_bit_cast(bf16x8, l), acc, 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ float epi_apply(int epi, float v, float g)
+{
+    if (epi == LPG_EPI_SILU) return silu_f(v);
+    if (epi == LPG_EPI_GATE_SILU) return silu_f(g) * v;
+    return v;
+}
+
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a
+// constant in every iteration whatever the optimiser's unrolling limits are.  The epilogue
+// walks the accumulator tiles with it: one dynamically indexed use would make the whole
+// accumulator array live in memory, with a store behind every MFMA of the main loop.
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+struct TileInfo {
+    const char *Lp, *Rp;  // first block of the tile's L / R slab at K block 0
+    int gl0, gr0;         // first 32-group of the tile in out's free / contraction dimension
+    int nlg, nrg;         // groups of the tile that exist in L / R
+    int b;                // batch index
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int MASK, int N>
+__device__ __forceinline__ void sched_group()
+{
+    if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
+}
+
+// registers -> fragments of P(out; FL, FR) for one 32x32 accumulator tile
+template <typename OUT>
+__device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane,
+                                           char *Ob, const char *Cb, const char *Eb, bool use_c, bool use_e)
+{
+    const int h = lane >> 5;
+    const int fl = grL * 32 + (lane & 31);
+    const bool have = grR < p.FRg;
+    float v[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) v[e] = have ? acc[e] : 0.0f;
+    if (p.alpha != 1.0f) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] *= p.alpha;
+    }
+    if (p.o_canon) {
+        // Ending kernel: straight to row/column-major.  Lanes run along out's free index, so
+        // for each register the 32 lanes of a half wave write one contiguous run.
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+            if (fl >= p.FL || fr >= p.FR) continue;
+            const int64_t off = (int64_t)fl * p.o_sf + (int64_t)fr * p.o_sk;
+            float x = v[e];
+            if (use_c) {
+                if constexpr (OUT::ES == 4) x += p.beta * *(const float *)(Cb + off);
+                else x += p.beta * bf16_to_f32(*(const uint16_t *)(Cb + off));
+            }
+            float gte = 0.0f;
+            if (use_e) {
+                if constexpr (OUT::ES == 4) gte = *(const float *)(Eb + off);
+                else gte = bf16_to_f32(*(const uint16_t *)(Eb + off));
+            }
+            x = epi_apply(p.epi, x, gte);
+            if constexpr (OUT::ES == 4) *(float *)(Ob + off) = x;
+            else *(uint16_t *)(Ob + off) = (uint16_t)bf16_rne(x);
+        }
+        return;
+    }
+    int64_t obase;  // byte offset of this tile's first fragment inside out
+    if constexpr (OUT::ES == 4)
+        obase = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
+    else
+        obase = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes + (grR & 1) * 2 * kFragBytes + lane * 16;
+    constexpr int NF = (OUT::ES == 4) ? 4 : 2;  // fragments this tile spans
+    constexpr int PER = 16 / NF;
+    if (use_c || use_e) {
+#pragma unroll
+        for (int fgi = 0; fgi < NF; ++fgi) {
+            float cv[PER], ev[PER];
+            if (use_c) {
+                const uint4 t4 = *(const uint4 *)(Cb + obase + fgi * kFragBytes);
+                const uint32_t w[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    if constexpr (OUT::ES == 4) cv[j] = __uint_as_float(w[j]);
+                    else cv[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
+                }
+            }
+            if (use_e) {
+                const uint4 t4 = *(const uint4 *)(Eb + obase + fgi * kFragBytes);
+                const uint32_t w[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    if constexpr (OUT::ES == 4) ev[j] = __uint_as_float(w[j]);
+                    else ev[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                float x = v[fgi * PER + j];
+                if (use_c) x += p.beta * cv[j];
+                v[fgi * PER + j] = epi_apply(p.epi, x, use_e ? ev[j] : 0.0f);
+            }
+        }
+    } else if (p.epi == LPG_EPI_SILU) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = silu_f(v[e]);
+    }
+    // zero the padding of ragged edge tiles
+    if (grL * 32 + 32 > p.FL || grR * 32 + 32 > p.FR) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+            if (fl >= p.FL || fr >= p.FR) v[e] = 0.0f;
+        }
+    }
+    if constexpr (OUT::ES == 4) {
+#pragma unroll
+        for (int fgi = 0; fgi < 4; ++fgi)
+            *(uint4 *)(Ob + obase + fgi * kFragBytes) =
+                make_uint4(__float_as_uint(v[4 * fgi]), __float_as_uint(v[4 * fgi + 1]),
+                           __float_as_uint(v[4 * fgi + 2]), __float_as_uint(v[4 * fgi + 3]));
+    } else {
+#pragma unroll
+        for (int fgi = 0; fgi < 2; ++fgi) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = bf16_pack2(v[8 * fgi + 2 * j], v[8 * fgi + 2 * j + 1]);
+            *(uint4 *)(Ob + obase + fgi * kFragBytes) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
+// XPF (needs NS >= 3): the first fragment of the NEXT step is read into registers while the
+// last fragment of the current step is multiplied, so no LDS latency is exposed after the
+// barrier; the barrier of a step then also publishes the step after it.
+template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR, int FS, int NS, bool XPF>
+__global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
+{
+    static_assert(!XPF || NS >= 3, "cross-step prefetch needs a landed stage beyond the current one");
+    constexpr int NW = WL * WR;
+    constexpr int WTL = TLG / WL, WTR = TRG / WR;
+    constexpr int NFRAG = (TLG + TRG) * FS;  // fragments per stage
+    constexpr int FPW = NFRAG / NW;          // fragments each wave copies per stage
+    constexpr int FPW_L = TLG * FS / NW;     // ... of which the first FPW_L come from L
+    constexpr int STAGE = NFRAG * kFragBytes;
+    constexpr int SPB = kFragsPerBlock / FS;  // steps per K block
+    static_assert(NFRAG % NW == 0 && (TLG * FS) % NW == 0, "stage must divide over the waves");
+    static_assert(TLG % WL == 0 && TRG % WR == 0, "tile must divide over the waves");
+    static_assert(FS == 2 || FS == 4, "a step is a whole or half K block");
+    static_assert(NS >= 2 && NS <= 5 && (NS - 2) * FPW <= 63, "ring depth limited by the vmcnt field");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wl = wave % WL, wr = wave / WL;
+
+    const uint32_t ntile = (uint32_t)(p.tiles_l * p.tiles_r);
+    const uint32_t total = ntile * (uint32_t)p.batch;
+    const uint32_t G = gridDim.x;
+    const int spt = p.nkb * SPB;  // steps per tile
+    if (blockIdx.x >= total) return;
+    const uint32_t my_tiles = (total - blockIdx.x + G - 1) / G;
+
+    // virtual block id -> (batch, tile).  Hardware deals consecutive workgroups round-robin
+    // to the 8 XCDs; ids congruent mod 8 get one contiguous range of tile ids, walked in
+    // bands of GM tile-rows, so the tiles an XCD works on share L and R panels in its L2.
+    auto decode = [&](uint32_t vb) -> TileInfo {
+        const uint32_t per = total / 8, rem = total % 8, x = vb % 8, idx = vb / 8;
+        const uint32_t pid = (x < rem) ? x * (per + 1) + idx : rem * (per + 1) + (x - rem) * per + idx;
+        TileInfo t;
+        t.b = (int)(pid / ntile);
+        const int tp = (int)(pid % ntile);
+        constexpr int GM = 8;
+        const int width = GM * p.tiles_r;
+        const int first_l = (tp / width) * GM;
+        const int gsz = min(p.tiles_l - first_l, GM);
+        const int tl = first_l + (tp % width) % gsz;
+        const int tr = (tp % width) / gsz;
+        t.gl0 = tl * TLG;
+        t.gr0 = tr * TRG;
+        t.nlg = min(TLG, p.FLg - t.gl0);
+        t.nrg = max(0, min(TRG, p.FRg - t.gr0));
+        // packed: first block of the tile; canonical: the operand's (slot's) first element
+        t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (p.l_canon ? 0 : (int64_t)t.gl0 * kBlockBytes);
+        t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (p.r_canon ? 0 : (int64_t)t.gr0 * kBlockBytes);
+        return t;
+    };
+
+    // ---- copy side.  Wave w copies fragments w, w + NW, ... of a stage; src[i] is this
+    // lane's address of its i-th fragment at the step the copy cursor stands on.  Every wave
+    // always issues exactly FPW transfers per step, so outstanding-transfer counts agree
+    // across waves: a group the tile does not have is replaced by the tile's last existing
+    // group (its data is never used), which keeps every address inside the operand.
+    const char *src[FPW];
+    auto aim = [&](const TileInfo &t) {
+#pragma unroll
+        for (int i = 0; i < FPW; ++i) {
+            const int fid = i * NW + wave;
+            const int grp = fid / FS, c = fid % FS;
+            const bool is_l = i < FPW_L;
+            if (is_l ? p.l_canon : p.r_canon) {
+                // Initial kernel: gather the fragment straight from the canonical matrix.  Lane
+                // (fl, h) of fragment c needs k = KF*c + 4*h .. +3 of free index fl: 16
+                // contiguous bytes of a k-contiguous fp32 row, which the transfer drops at
+                // lane*16 of the stage, i.e. in fragment order.  Rows past the end are
+                // replaced by the last row (never used).
+                const int g0 = is_l ? t.gl0 + grp : t.gr0 + grp - TLG;
+                const int row = min(g0 * 32 + (lane & 31), (is_l ? p.FL : p.FR) - 1);
+                const char *base = is_l ? t.Lp + (int64_t)row * p.l_ld : t.Rp + (int64_t)row * p.r_ld;
+                src[i] = base + c * (IN::KF * IN::ES) + (lane >> 5) * 16;
+            } else {
+                const char *base = is_l ? t.Lp + min(grp, t.nlg - 1) * kBlockBytes
+                                        : t.Rp + max(0, min(grp - TLG, t.nrg - 1)) * kBlockBytes;
+                src[i] = base + c * kFragBytes + lane * 16;
+            }
+        }
+    };
+    uint32_t c_tiles_left = my_tiles;  // tiles the copy cursor still has to start or finish
+    uint32_t c_vb = blockIdx.x;
+    int c_s = 0;                       // step of its tile the copy cursor stands on
+    int c_st = 0;                      // ring stage it fills next
+    int pending = 0;                   // steps copied (or in flight) and not yet multiplied
+    bool c_live = spt > 0;
+    // fragment i of the step the copy cursor stands on -> ring stage c_st
+    auto copy_issue = [&](int i) {
+        lds_dma16(src[i], sbase + c_st * STAGE + (i * NW + wave) * kFragBytes);
+    };
+    // move the copy cursor one step on
+    auto copy_advance = [&]() {
+        c_st = (c_st + 1 == NS) ? 0 : c_st + 1;
+        ++pending;
+        if (++c_s == spt) {  // next tile
+            c_s = 0;
+            c_vb += G;
+            if (--c_tiles_left == 0) c_live = false;
+            else aim(decode(c_vb));
+        } else {             // next step of the same tile
+            int64_t dl, dr;
+            if (FS == 4 || (c_s & 1) == 0) {  // first fragments of the next K block
+                dl = p.l_kbs - (kFragsPerBlock - FS) * kFragBytes;
+                dr = p.r_kbs - (kFragsPerBlock - FS) * kFragBytes;
+            } else {                          // second half of the same K block
+                dl = dr = FS * kFragBytes;
+            }
+            if (p.l_canon) dl = FS * IN::KF * IN::ES;  // canonical rows are contiguous along k
+            if (p.r_canon) dr = FS * IN::KF * IN::ES;
+#pragma unroll
+            for (int i = 0; i < FPW; ++i) src[i] += (i < FPW_L) ? dl : dr;
+        }
+    };
+    auto copy_step = [&]() {
+#pragma unroll
+        for (int i = 0; i < FPW; ++i) copy_issue(i);
+        copy_advance();
+    };
+    aim(decode(c_vb));
+#pragma unroll
+    for (int j = 0; j < NS - 1; ++j)
+        if (c_live) copy_step();
+
+    const bool use_c = (p.beta != 0.0f) && p.Cin;
+    const bool use_e = (p.epi == LPG_EPI_GATE_SILU) && p.Epi;
+
+    // ---- multiply side
+    int st = 0;
+    const char *sLw = smem + (wl * WTL) * (FS * kFragBytes) + lane * 16;
+    const char *sRw = smem + (TLG + wr * WTR) * (FS * kFragBytes) + lane * 16;
+    uint4 lf[2][WTL], rf[2][WTR];
+    if constexpr (XPF) {
+        // prime: fragment 0 of the very first step
+        if (pending == NS - 1) wait_vmcnt<(NS - 2) * FPW>();
+        else wait_vmcnt<0>();
+        __syncthreads();
+#pragma unroll
+        for (int a = 0; a < WTL; ++a) lf[0][a] = *(const uint4 *)(sLw + a * (FS * kFragBytes));
+#pragma unroll
+        for (int q = 0; q < WTR; ++q) rf[0][q] = *(const uint4 *)(sRw + q * (FS * kFragBytes));
+    }
+    uint32_t vb = blockIdx.x;
+    for (uint32_t ti = 0; ti < my_tiles; ++ti, vb += G) {
+        f32x16 acc[WTL][WTR];
+#pragma unroll
+        for (int a = 0; a < WTL; ++a)
+#pragma unroll
+            for (int q = 0; q < WTR; ++q)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[a][q][e] = 0.0f;
+
+        for (int s = 0; s < spt; ++s) {
+            // Wait until this wave's transfers of the step that must be readable have landed
+            // (XPF: the step after the current one; otherwise the current one); later steps
+            // stay in flight (transfers complete in issue order).
+            constexpr int KEEP = XPF ? NS - 3 : NS - 2;
+            if (pending == NS - 1) wait_vmcnt<KEEP * FPW>();
+            else wait_vmcnt<0>();
+            __syncthreads();  // everyone's transfers landed; the stage multiplied last step is free
+
+            const char *sL = sLw + st * STAGE;
+            const char *sR = sRw + st * STAGE;
+            const int stn = (st + 1 == NS) ? 0 : st + 1;
+            if constexpr (!XPF) {
+#pragma unroll
+                for (int a = 0; a < WTL; ++a) lf[0][a] = *(const uint4 *)(sL + a * (FS * kFragBytes));
+#pragma unroll
+                for (int q = 0; q < WTR; ++q) rf[0][q] = *(const uint4 *)(sR + q * (FS * kFragBytes));
+            }
+            // The step is cut into FS*WTL phases (one row of the wave's tiles each).  A phase
+            // reads its share of the NEXT fragment from LDS, multiplies one row of the current
+            // fragment, and issues its share of this step's global->LDS transfers, so that
+            // neither LDS reads nor transfer issue ever pile up in front of the MFMAs.  After
+            // the last real step the transfers go on as harmless refills of the one ring
+            // stage nobody reads again (their sources stay valid), which keeps this loop free
+            // of branches.
+            constexpr int SLOTS = FS * WTL;
+#pragma unroll
+            for (int c = 0; c < FS; ++c) {
+                const int cb = c & 1, nb = (c + 1) & 1;
+                const bool more = c + 1 < FS;
+                const char *nL = more ? sL + (c + 1) * kFragBytes : sLw + stn * STAGE;
+                const char *nR = more ? sR + (c + 1) * kFragBytes : sRw + stn * STAGE;
+#pragma unroll
+                for (int a = 0; a < WTL; ++a) {
+                    if (more || XPF) {
+                        lf[nb][a] = *(const uint4 *)(nL + a * (FS * kFragBytes));
+                        if (a < WTR) rf[nb][a] = *(const uint4 *)(nR + a * (FS * kFragBytes));
+                        if (a == WTL - 1) {
+#pragma unroll
+                            for (int q = WTL; q < WTR; ++q) rf[nb][q] = *(const uint4 *)(nR + q * (FS * kFragBytes));
+                        }
+                    }
+#pragma unroll
+                    for (int q = 0; q < WTR; ++q) mma_frag<IN>(acc[a][q], rf[cb][q], lf[cb][a]);
+                    const int slot = c * WTL + a;
+#pragma unroll
+                    for (int i = (slot * FPW) / SLOTS; i < ((slot + 1) * FPW) / SLOTS; ++i) copy_issue(i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            st = stn;
+            --pending;
+            if (c_live) copy_advance();
+        }
+
+        // ---- epilogue
+        const TileInfo cur = decode(vb);
+        const int64_t oslot = (int64_t)cur.b * p.o_slot;
+        static_for<WTL * WTR>([&](auto I) {
+            constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
+            const int grL = cur.gl0 + wl * WTL + a;
+            const int grR = cur.gr0 + wr * WTR + q;
+            if (grL < p.FLg && grR < p.FRg_out)
+                store_tile<OUT>(p, acc[a][q], grL, grR, lane, p.Out + oslot, p.Cin + oslot, p.Epi + oslot, use_c,
+                                use_e);
+        });
+    }
+    wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
+}
+
+// Tile configurations (TLG, TRG, WL, WR) in 32-groups; index = position in this list.
+struct TileCfg {
+    int tlg, trg, wl, wr;
+};
+static const TileCfg kCfgs[] = {
+    {2, 2, 2, 2},  // 0:  64 x  64, 4 waves of 1x1
+    {4, 2, 2, 2},  // 1: 128 x  64, 4 waves of 2x1
+    {2, 4, 2, 2},  // 2:  64 x 128, 4 waves of 1x2
+    {4, 4, 2, 2},  // 3: 128 x 128, 4 waves of 2x2
+    {8, 4, 2, 2},  // 4: 256 x 128, 4 waves of 4x2
+    {4, 8, 2, 2},  // 5: 128 x 256, 4 waves of 2x4
+    {8, 8, 2, 4},  // 6: 256 x 256, 8 waves of 4x2
+    {8, 2, 4, 1},  // 7: 256 x  64, 4 waves of 2x2
+};
+constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
+
+// Staging ring per input type and tile: fp32 moves whole K blocks through two stages (its
+// MFMAs are slow enough to cover memory latency); bf16 moves half blocks through a ring of
+// four stages (three where four would keep a second workgroup off the compute unit) and
+// reads the next step's first fragment ahead.
+constexpr int ring_fs(bool bf16) { return bf16 ? 2 : 4; }
+constexpr int ring_ns(bool bf16, int tlg, int trg, int nw)
+{
+    if (!bf16) return 2;
+    const int stage = (tlg + trg) * 2 * kFragBytes;
+    if (nw == 8) return 5 * stage <= 160 * 1024 ? 5 : 4;  // one workgroup per compute unit: use all the LDS
+    return 4 * stage <= 80 * 1024 ? 4 : 3;
+}
+
+// fp32 with small tiles and no more tiles than compute units: a step's MFMAs (2048 cycles
+// for a 128 x 64 tile) are shorter than the memory latency under load, and no second
+// workgroup shares the compute unit to cover for it, so the ring is made deeper instead.
+constexpr int ring_ns_lone(int tlg, int trg)
+{
+    const int stage = (tlg + trg) * 4 * kFragBytes;
+    return 4 * stage <= 96 * 1024 ? 4 : (3 * stage <= 96 * 1024 ? 3 : 2);
+}
+
+static int lds_bytes(const TileCfg &c, bool bf16)
+{
+    return ring_ns(bf16, c.tlg, c.trg, c.wl * c.wr) * (c.tlg + c.trg) * ring_fs(bf16) * kFragBytes;
+}
+
+static int workgroups_per_cu(const TileCfg &c, bool bf16)
+{
+    int occ = (160 * 1024) / lds_bytes(c, bf16);
+    const int waves = c.wl * c.wr;
+    // accumulators + operand registers per lane decide how many waves fit a SIMD
+    const int regs = (c.tlg / c.wl) * (c.trg / c.wr) * 16 + 64;
+    const int waves_per_simd = regs > 256 ? 1 : (regs > 128 ? 2 : 4);
+    const int by_regs = waves_per_simd * 4 / waves;
+    if (occ > by_regs) occ = by_regs;
+    if (occ > 4) occ = 4;
+    return occ < 1 ? 1 : occ;
+}
+
+template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR, int NS>
+static hipError_t launch_gemm_ring(const GemmArgs &a, int64_t grid, hipStream_t st)
+{
+    constexpr int NT = WL * WR * 64;
+    constexpr bool BF = IN::ES == 2;
+    constexpr int FS = ring_fs(BF);
+    constexpr size_t lds = (size_t)NS * (TLG + TRG) * FS * kFragBytes;
+    static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
+    auto kern = gemm_kernel<IN, OUT, TLG, TRG, WL, WR, FS, NS, BF>;
+    if (lds > 64 * 1024) {
+        static bool done = false;  // per instantiation
+        if (!done) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            done = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, st, a);
+    return hipGetLastError();
+}
+
+template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR>
+static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
+{
+    constexpr bool BF = IN::ES == 2;
+    constexpr int NS = ring_ns(BF, TLG, TRG, WL * WR), NS_LONE = BF ? NS : ring_ns_lone(TLG, TRG);
+    a.tiles_l = (a.FLg + TLG - 1) / TLG;
+    a.tiles_r = (a.FRg_out + TRG - 1) / TRG;
+    const int64_t total = (int64_t)a.tiles_l * a.tiles_r * a.batch;
+    if (total <= 0) return hipSuccess;
+    if (total > 0x7fffffff) return hipErrorInvalidValue;
+    const TileCfg c = {TLG, TRG, WL, WR};
+    int64_t grid = (int64_t)256 * workgroups_per_cu(c, BF);
+    if (grid > total) grid = total;
+    if constexpr (NS_LONE != NS) {
+        if (total <= 256) return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS_LONE>(a, grid, st);
+    }
+    return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS>(a, grid, st);
+}
+
+}  // namespace lpg
