@@ -145,7 +145,7 @@ def stage_breakdown(ch, steps):
             nbytes = nb * (kept + r * c) * es[o.dtype]
         elif s.type == api.LPG_STAGE_ATTENTION:
             tq, dh, tk = o.rows, o.cols, s.in2_d.rows
-            pairs_kept = tq * tk if not s.op else sum(min(tk, max(0, j + tk - tq + 1)) for j in range(tq))
+            pairs_kept = tq * tk if not (s.op & 1) else sum(min(tk, max(0, j + tk - tq + 1)) for j in range(tq))
             nbytes = nb * (2 * tq * dh + 2 * tk * dh // max(s.in1_d.batch_div, 1)) * es[o.dtype]
             row.update({"queries": tq, "keys": tk, "head_dim": dh, "batch": nb,
                         "tflops": round(4.0 * pairs_kept * dh * nb / us / 1e6, 1)})
@@ -213,7 +213,7 @@ def measure(name, steps, warmup, shape_over=None, modes="both", options=None):
         res["fused_boundaries_ms_per_step"] = round(t_f * 1e3, 4)
         res["fused_boundaries_tflops"] = round(flops / t_f / 1e12, 2)
         del fch
-        if (name == "llama_layer" or options.get("softmax")) and not options.get("flash"):
+        if name in ("llama_layer", "attention", "decoder_layer") and not options.get("flash"):
             # the attention block as one kernel that keeps the scores in registers
             ach = chains.build(name, inp, shape, flash=True, **options)
             t_a = time_chain(ach, api.LPG_CHAIN_PROPAGATED, steps, warmup)

@@ -247,12 +247,17 @@ int lpg_rope_packed(const void *x, void *out, const lpg_desc *d, const float *co
  *   v_d: LPG_PACKED_B keys x head_dim (or LPG_PACKED_A head_dim x keys).
  *   One dtype for all four (f32 or bf16; fp32 accumulation and softmax); head_dim 64 or 128;
  *   batch counts equal; batch_div on k_d / v_d shares a key/value head among query heads.
- *   causal != 0: query i sees keys j <= i + (keys - queries).  scale > 0.  O must not alias
- *   an input.  Padding rows of O are written as zeros.
+ *   flags: LPG_ATTN_CAUSAL - query i sees keys j <= i + (keys - queries);
+ *          LPG_ATTN_NO_SOFTMAX - O = (scale * Q K^T [causal]) V, the two chained GEMMs of the
+ *          GEMM-only attention workloads with the intermediate kept in registers (bf16: it is
+ *          rounded to bf16 where the first GEMM would have stored it; any finite scale).
+ *   With the softmax scale must be positive.  O must not alias an input.  Padding rows of O
+ *   are written as zeros.
  */
+typedef enum { LPG_ATTN_CAUSAL = 1, LPG_ATTN_NO_SOFTMAX = 2 } lpg_attention_flags;
 int lpg_attention_packed(const void *Q, const lpg_desc *q_d, const void *K, const lpg_desc *k_d,
                          const void *V, const lpg_desc *v_d, void *O, const lpg_desc *o_d,
-                         float scale, int causal, void *stream);
+                         float scale, int flags, void *stream);
 
 /* One stage of a chain. */
 typedef enum {
@@ -268,8 +273,8 @@ typedef enum {
 
 typedef struct lpg_stage {
     int32_t type;       /* lpg_stage_type                                               */
-    int32_t op;         /* GEMM: lpg_epilogue_op; ELEMENTWISE: lpg_ew_op; SOFTMAX,
-                           ATTENTION: causal; ROPE: head_dim                             */
+    int32_t op;         /* GEMM: lpg_epilogue_op; ELEMENTWISE: lpg_ew_op; SOFTMAX: causal;
+                           ATTENTION: lpg_attention_flags; ROPE: head_dim                */
     float alpha, beta;  /* GEMM                                                         */
     float scalar;       /* ELEMENTWISE: s; SOFTMAX, ATTENTION: scale; RMSNORM: eps      */
     int32_t reserved;

@@ -20,6 +20,7 @@ LPG_EPI_NONE, LPG_EPI_SILU, LPG_EPI_GATE_SILU = 0, 1, 2
 LPG_STAGE_PACK, LPG_STAGE_GEMM, LPG_STAGE_ELEMENTWISE, LPG_STAGE_UNPACK, LPG_STAGE_SOFTMAX = 0, 1, 2, 3, 4
 LPG_STAGE_RMSNORM, LPG_STAGE_ROPE, LPG_STAGE_ATTENTION = 5, 6, 7
 LPG_CHAIN_PROPAGATED, LPG_CHAIN_CANONICAL = 0, 1
+LPG_ATTN_CAUSAL, LPG_ATTN_NO_SOFTMAX = 1, 2
 
 ELEM_SIZE = {LPG_F32: 4, LPG_BF16: 2}
 
@@ -176,10 +177,14 @@ def lpg_softmax_packed(x, out, d, scale=1.0, causal=False, stream=None):
     return _check(lib().lpg_softmax_packed(_ptr(x), _ptr(out), ctypes.byref(d), scale, int(bool(causal)), stream))
 
 
-def lpg_attention_packed(Q, q_d, K, k_d, V, v_d, O, o_d, scale, causal=False, stream=None):
+def attention_flags(causal=False, softmax=True):
+    return (LPG_ATTN_CAUSAL if causal else 0) | (0 if softmax else LPG_ATTN_NO_SOFTMAX)
+
+
+def lpg_attention_packed(Q, q_d, K, k_d, V, v_d, O, o_d, scale, causal=False, stream=None, softmax=True):
     return _check(lib().lpg_attention_packed(_ptr(Q), ctypes.byref(q_d), _ptr(K), ctypes.byref(k_d), _ptr(V),
-                                             ctypes.byref(v_d), _ptr(O), ctypes.byref(o_d), scale, int(bool(causal)),
-                                             stream))
+                                             ctypes.byref(v_d), _ptr(O), ctypes.byref(o_d), scale,
+                                             attention_flags(causal, softmax), stream))
 
 
 def lpg_rmsnorm_packed(x, weight, out, d, eps, stream=None):
@@ -264,9 +269,9 @@ def stage_rope(x, out, d, cos_t, sin_t, head_dim):
     return s
 
 
-def stage_attention(Q, q_d, K, k_d, V, v_d, O, o_d, scale, causal=False):
+def stage_attention(Q, q_d, K, k_d, V, v_d, O, o_d, scale, causal=False, softmax=True):
     s = lpg_stage()
-    s.type, s.op, s.scalar = LPG_STAGE_ATTENTION, int(bool(causal)), scale
+    s.type, s.op, s.scalar = LPG_STAGE_ATTENTION, attention_flags(causal, softmax), scale
     s.in0, s.in0_d, s.in1, s.in1_d, s.in2, s.in2_d = _ptr(Q), q_d, _ptr(K), k_d, _ptr(V), v_d
     s.out, s.out_d = _ptr(O), o_d
     return s

@@ -201,8 +201,8 @@ def build_mlp(inp, shape, fused=False):
 def build_attention(inp, shape, fused=False, softmax=False, causal=False, flash=False):
     """softmax=False: O = (Q K^T / sqrt(dh)) V, the two chained GEMMs alone.  softmax=True: the
     scale moves into a softmax stage (optionally causally masked) that runs in place on the
-    packed scores between the two GEMMs.  flash=True (implies softmax): one lpg_attention_packed
-    stage replaces the three, and the scores are never stored."""
+    packed scores between the two GEMMs.  flash=True: one lpg_attention_packed stage replaces the
+    two or three stages (with or without the softmax), and the scores are never stored."""
     nh, t, dh = shape["heads"], shape["t"], shape["dh"]
     scale = 1.0 / float(np.sqrt(dh))
     alpha = 1.0 if softmax else scale
@@ -236,7 +236,7 @@ def build_attention(inp, shape, fused=False, softmax=False, causal=False, flash=
     ch.add(api.stage_pack(k, ktd_src, pk, ktd))
     ch.add(api.stage_pack(v, rm, pv, vd))
     if flash:
-        ch.add(api.stage_attention(pq, qd, pk, ktd, pv, vd, po, od, scale, causal))
+        ch.add(api.stage_attention(pq, qd, pk, ktd, pv, vd, po, od, scale, causal, softmax=softmax))
         ch.add(api.stage_unpack(po, od, out, rm))
         return ch
     ch.add(api.stage_gemm(alpha, pq, qd, pk, ktd, 0.0, None, ps, sd))
@@ -279,7 +279,7 @@ def build_deep_chain(inp, shape, fused=False):
     return ch
 
 
-def build_decoder_layer(inp, shape, fused=False):
+def build_decoder_layer(inp, shape, fused=False, flash=False):
     t, hid, nq, nkv, ffn = shape["t"], shape["hidden"], shape["n_q"], shape["n_kv"], shape["ffn"]
     dh = hid // nq
     kvw = nkv * dh
@@ -300,7 +300,7 @@ def build_decoder_layer(inp, shape, fused=False):
     vd = desc(LPG_PACKED_B, B, t, kvw)          # V written as a right operand
     px, pq, pk, pv = (ch.new_packed(n_, d_) for n_, d_ in (("X", xd), ("Q", qd), ("K", kd), ("V", vd)))
     sd = desc(LPG_PACKED_A, B, t, t, batch=nq, batch_stride=_packed_elems(B, t, t))
-    ps = ch.new_packed("S", sd)
+    ps = None if flash else ch.new_packed("S", sd)
     od_full = desc(LPG_PACKED_A, B, t, hid)
     po = ch.new_packed("O", od_full)
     ad = desc(LPG_PACKED_A, B, t, hid)
@@ -320,10 +320,15 @@ def build_decoder_layer(inp, shape, fused=False):
     q_view = desc(LPG_PACKED_A, B, t, dh, parent=(t, hid), batch=nq, batch_step=(0, dh))
     # ... and read here as the right operand K_g^T: rows [g*dh, (g+1)*dh) of K^T [kvw x t]
     kt_view = desc(LPG_PACKED_B, B, dh, t, parent=(kvw, t), batch=nq, batch_div=rep, batch_step=(dh, 0))
-    ch.add(api.stage_gemm(1.0 / float(np.sqrt(dh)), pq, q_view, pk, kt_view, 0.0, None, ps, sd))
     v_view = desc(LPG_PACKED_B, B, t, dh, parent=(t, kvw), batch=nq, batch_div=rep, batch_step=(0, dh))
     o_view = desc(LPG_PACKED_A, B, t, dh, parent=(t, hid), batch=nq, batch_step=(0, dh))
-    ch.add(api.stage_gemm(1.0, ps, sd, pv, v_view, 0.0, None, po, o_view))
+    if flash:
+        # the two attention GEMMs as one kernel, S_h kept in registers (no softmax in this workload)
+        ch.add(api.stage_attention(pq, q_view, pk, kt_view, pv, v_view, po, o_view, 1.0 / float(np.sqrt(dh)),
+                                   causal=False, softmax=False))
+    else:
+        ch.add(api.stage_gemm(1.0 / float(np.sqrt(dh)), pq, q_view, pk, kt_view, 0.0, None, ps, sd))
+        ch.add(api.stage_gemm(1.0, ps, sd, pv, v_view, 0.0, None, po, o_view))
     ch.add(api.stage_gemm(1.0, po, od_full, wt["Wo"], wd["Wo"], 0.0, None, pattn, ad))
     ch.add(api.stage_gemm(1.0, pattn, ad, wt["Wg"], wd["Wg"], 0.0, None, pg, gd))
     if fused:

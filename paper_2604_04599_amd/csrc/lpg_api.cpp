@@ -507,10 +507,12 @@ static int do_rope(const void *x, void *out, const lpg_desc *d, const void *cos_
 // -------------------------------------------------------------------------- attention
 
 static int do_attention(const void *Q, const lpg_desc *q_d, const void *K, const lpg_desc *k_d, const void *V,
-                        const lpg_desc *v_d, void *O, const lpg_desc *o_d, float scale, int causal, hipStream_t st,
+                        const lpg_desc *v_d, void *O, const lpg_desc *o_d, float scale, int flags, hipStream_t st,
                         bool launch)
 {
     const char *what = "lpg_attention_packed";
+    if (flags & ~(LPG_ATTN_CAUSAL | LPG_ATTN_NO_SOFTMAX)) return fail(LPG_EINVAL, "%s: unknown flag bits in %d", what, flags);
+    const bool softmax = !(flags & LPG_ATTN_NO_SOFTMAX);
     PView q, k, v, o;
     int rc = make_pview(q_d, what, &q);
     if (rc) return rc;
@@ -532,7 +534,8 @@ static int do_attention(const void *Q, const lpg_desc *q_d, const void *K, const
     if (q.batch != o.batch || k.batch != q.batch || v.batch != q.batch)
         return fail(LPG_EINVAL, "%s: batch counts differ", what);
     if (q.bdiv != 1 || o.bdiv != 1) return fail(LPG_EUNSUPPORTED, "%s: batch_div applies to K and V only", what);
-    if (!(scale > 0.0f && scale <= 3.0e38f)) return fail(LPG_EINVAL, "%s: scale must be positive and finite", what);
+    if (softmax && !(scale > 0.0f && scale <= 3.0e38f)) return fail(LPG_EINVAL, "%s: scale must be positive and finite", what);
+    if (!softmax && !(scale >= -3.0e38f && scale <= 3.0e38f)) return fail(LPG_EINVAL, "%s: scale must be finite", what);
     if (tq > 0 && tk <= 0) return fail(LPG_EINVAL, "%s: no keys", what);
     if ((rc = check_ptr16(Q, what)) || (rc = check_ptr16(K, what)) || (rc = check_ptr16(V, what)) || (rc = check_ptr16(O, what)))
         return rc;
@@ -554,8 +557,10 @@ static int do_attention(const void *Q, const lpg_desc *q_d, const void *K, const
     a.k_groups = (int32_t)((tk + 31) / 32);
     a.v_nkb = (int32_t)((tk + kb_of(q.dtype) - 1) / kb_of(q.dtype));
     a.batch = q.batch;
-    a.causal = causal != 0;
+    a.causal = (flags & LPG_ATTN_CAUSAL) != 0;
+    a.softmax = softmax;
     a.sl = (float)((double)scale * 1.4426950408889634);
+    a.scale = scale;
     hipError_t e = launch_attention(a, q.dtype, (int)dh, st);
     if (e != hipSuccess) return fail(LPG_EHIP, "%s: %s", what, hipGetErrorString(e));
     return LPG_OK;
@@ -929,9 +934,9 @@ int lpg_softmax_packed(const void *x, void *out, const lpg_desc *d, float scale,
 }
 
 int lpg_attention_packed(const void *Q, const lpg_desc *q_d, const void *K, const lpg_desc *k_d, const void *V,
-                         const lpg_desc *v_d, void *O, const lpg_desc *o_d, float scale, int causal, void *stream)
+                         const lpg_desc *v_d, void *O, const lpg_desc *o_d, float scale, int flags, void *stream)
 {
-    return do_attention(Q, q_d, K, k_d, V, v_d, O, o_d, scale, causal, (hipStream_t)stream, true);
+    return do_attention(Q, q_d, K, k_d, V, v_d, O, o_d, scale, flags, (hipStream_t)stream, true);
 }
 
 int lpg_rmsnorm_packed(const void *x, const float *weight, void *out, const lpg_desc *d, float eps, void *stream)

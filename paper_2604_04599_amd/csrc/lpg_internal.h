@@ -131,8 +131,9 @@ struct AttnArgs {
     int32_t tq, tk;                          // queries, keys
     int32_t q_groups, k_groups;              // ceil(tq/32), ceil(tk/32)
     int32_t v_nkb;                           // ceil(tk/KB): contraction blocks of V
-    int32_t batch, causal;
-    float sl;                                // scale * log2(e)
+    int32_t batch, causal, softmax;
+    float sl;                                // scale * log2(e) (softmax)
+    float scale;                             // scale (no softmax)
 };
 
 // Launchers (lpg_kernels.hip).  Return hipError_t of the launch.

@@ -768,7 +768,10 @@ struct AttnFrag {
     }
 };
 
-template <typename T, int DH>
+// SOFTMAX = false is the same walk without the softmax, O = (scale * Q K^T [causal]) V: the two
+// chained GEMMs of the GEMM-only attention workloads with their intermediate in registers
+// (bf16: rounded to bf16 exactly where the first GEMM's epilogue would have stored it).
+template <typename T, int DH, bool SOFTMAX>
 __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
 {
     constexpr int NW = 4;
@@ -858,41 +861,49 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
             const int key0 = 64 * j + 4 * h;
             const bool masked = 64 * j + 63 > wave_min_last;  // wave-uniform
             if (masked) {
+                const float gone = SOFTMAX ? -__builtin_inff() : 0.0f;
 #pragma unroll
                 for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
-                        s[kg][e] = (key0 + 32 * kg + 8 * (e >> 2) + (e & 3) <= last) ? s[kg][e] : -__builtin_inff();
+                        s[kg][e] = (key0 + 32 * kg + 8 * (e >> 2) + (e & 3) <= last) ? s[kg][e] : gone;
             }
-            float bmx = -__builtin_inff();
+            if constexpr (SOFTMAX) {
+                float bmx = -__builtin_inff();
 #pragma unroll
-            for (int kg = 0; kg < 2; ++kg)
+                for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) bmx = fmaxf(bmx, s[kg][e]);
-            bmx = fmaxf(bmx, __shfl_xor(bmx, 32, 64));
-            // The reference point m of the exponentials only has to stay within 2^8 of the true
-            // running maximum (the final division cancels it), so O and the sum are rescaled only
-            // in the steps where some query of the wave moved further than that.
-            const float bm = bmx * sl;
-            if (__any(bm > m + 8.0f)) {
-                const float mn = fmaxf(m, bm);
-                const float alpha = __builtin_amdgcn_exp2f(m - mn);
-                m = mn;
-                lsum *= alpha;
+                    for (int e = 0; e < 16; ++e) bmx = fmaxf(bmx, s[kg][e]);
+                bmx = fmaxf(bmx, __shfl_xor(bmx, 32, 64));
+                // The reference point m of the exponentials only has to stay within 2^8 of the true
+                // running maximum (the final division cancels it), so O and the sum are rescaled only
+                // in the steps where some query of the wave moved further than that.
+                const float bm = bmx * sl;
+                if (__any(bm > m + 8.0f)) {
+                    const float mn = fmaxf(m, bm);
+                    const float alpha = __builtin_amdgcn_exp2f(m - mn);
+                    m = mn;
+                    lsum *= alpha;
 #pragma unroll
-                for (int dg = 0; dg < DG; ++dg)
+                    for (int dg = 0; dg < DG; ++dg)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) o[dg][e] *= alpha;
-            }
-            float psum = 0.0f;
-#pragma unroll
-            for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    s[kg][e] = __builtin_amdgcn_exp2f(fmaf(s[kg][e], sl, -m));
-                    psum += s[kg][e];
+                        for (int e = 0; e < 16; ++e) o[dg][e] *= alpha;
                 }
-            lsum += psum;
+                float psum = 0.0f;
+#pragma unroll
+                for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        s[kg][e] = __builtin_amdgcn_exp2f(fmaf(s[kg][e], sl, -m));
+                        psum += s[kg][e];
+                    }
+                lsum += psum;
+            } else if (a.scale != 1.0f) {
+#pragma unroll
+                for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) s[kg][e] *= a.scale;
+            }
             // P's fragments are the registers as they stand (bf16: rounded in pairs); O^T += V^T P^T
 #pragma unroll
             for (int kg = 0; kg < 2; ++kg)
@@ -912,7 +923,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
                 }
         }
         if (have_g) {
-            const float l = lsum + __shfl_xor(lsum, 32, 64);
+            const float l = SOFTMAX ? lsum + __shfl_xor(lsum, 32, 64) : 1.0f;
             const float inv = (l > 0.0f && q < a.tq) ? 1.0f / l : 0.0f;  // padding rows and rows without keys: zeros
             char *Ob = a.O + (int64_t)b * a.o_slot + (int64_t)g * kBlockBytes + lane * 16;
 #pragma unroll
@@ -939,13 +950,13 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
     wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
 }
 
-template <typename T, int DH>
+template <typename T, int DH, bool SOFTMAX>
 static hipError_t launch_attention_dh(const AttnArgs &a, hipStream_t st)
 {
     constexpr int NF = 2 * (DH / T::KF) + (DH / 32) * 2 * (32 / T::KF);
     constexpr size_t lds = 2 * (size_t)NF * kFragBytes;
     static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
-    auto kern = attention_kernel<T, DH>;
+    auto kern = attention_kernel<T, DH, SOFTMAX>;
     if (lds > 64 * 1024) {
         static bool done = false;
         if (!done) {
@@ -960,13 +971,19 @@ static hipError_t launch_attention_dh(const AttnArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
+template <typename T, int DH>
+static hipError_t launch_attention_mode(const AttnArgs &a, hipStream_t st)
+{
+    return a.softmax ? launch_attention_dh<T, DH, true>(a, st) : launch_attention_dh<T, DH, false>(a, st);
+}
+
 hipError_t launch_attention(const AttnArgs &a, int dtype, int head_dim, hipStream_t st)
 {
     if (a.batch <= 0 || a.tq <= 0) return hipSuccess;
     if (head_dim == 64)
-        return dtype == LPG_F32 ? launch_attention_dh<F32, 64>(a, st) : launch_attention_dh<BF16, 64>(a, st);
+        return dtype == LPG_F32 ? launch_attention_mode<F32, 64>(a, st) : launch_attention_mode<BF16, 64>(a, st);
     if (head_dim == 128)
-        return dtype == LPG_F32 ? launch_attention_dh<F32, 128>(a, st) : launch_attention_dh<BF16, 128>(a, st);
+        return dtype == LPG_F32 ? launch_attention_mode<F32, 128>(a, st) : launch_attention_mode<BF16, 128>(a, st);
     return hipErrorInvalidValue;
 }
 

@@ -133,3 +133,45 @@ def test_llama_layer_flash_small_and_full():
                                  rope_base=float(shape["rope_base"]), rows=rows)
     assert ref.rel_frobenius(ch.fetch("O")[rows], want["O"]) <= 2e-2
     assert ref.rel_frobenius(ch.output("Y")[rows], want["Y"]) <= 2e-2
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", [LPG_F32, LPG_BF16])
+@pytest.mark.parametrize("tq,tk,dh", [(70, 70, 64), (200, 333, 64), (257, 257, 128)])
+def test_attention_without_softmax_is_the_two_gemm_chain(tq, tk, dh, dtype, causal):
+    """LPG_ATTN_NO_SOFTMAX: O = (scale Q K^T [causal]) V; the oracle stores the intermediate in
+    the operand dtype as the first GEMM of the chain would."""
+    rng = np.random.default_rng(tq + tk)
+    q, k, v = (rng.standard_normal((n, dh)).astype(np.float32) for n in (tq, tk, tk))
+    pq, qd = pack_dev(q, LPG_PACKED_A, dtype)
+    pk, kd = pack_dev(k, LPG_PACKED_A, dtype)
+    pv, vd = pack_dev(v, LPG_PACKED_B, dtype)
+    od = desc(LPG_PACKED_A, dtype, tq, dh)
+    po = dev_empty(api.lpg_packed_bytes(od), fill=0xA5)
+    api.lpg_attention_packed(pq, qd, pk, kd, pv, vd, po, od, 0.125, causal, stream(), softmax=False)
+    got = unpack_dev(po, od)
+    qs, ks, vs = unpack_dev(pq, qd), unpack_dev(pk, kd), unpack_dev(pv, vd)
+    s = ref.gemm(qs, ks.T.copy(), alpha=0.125)
+    if causal:
+        i, j = np.indices(s.shape)
+        s[j > i + tk - tq] = 0.0
+    s = ref.round_bf16(s) if dtype == LPG_BF16 else s
+    assert ref.rel_frobenius(got, ref.gemm(s, vs)) <= (2e-5 if dtype == LPG_F32 else 5e-3)
+
+
+def test_decoder_layer_with_fused_attention_matches_the_chain():
+    inp, shape = inputs.make("decoder_layer", t=192, hidden=256, n_q=4, n_kv=2, ffn=320)
+    ch2 = chains.build("decoder_layer", inp, shape)
+    ch1 = chains.build("decoder_layer", inp, shape, flash=True)
+    ch2.run()
+    ch1.run()
+    want = workloads.decoder_layer(inp, 4, 2)
+    assert ref.rel_frobenius(ch1.output("Y"), want["Y"]) <= 2e-2
+    assert ref.rel_frobenius(ch1.fetch("O"), ch2.fetch("O")) <= 5e-3      # same roundings, other summation order
+    inp, shape = inputs.make("decoder_layer")
+    ch1 = chains.build("decoder_layer", inp, shape, flash=True)
+    ch1.run()
+    rows = np.arange(11, shape["t"], 409)
+    want = workloads.decoder_layer(inp, shape["n_q"], shape["n_kv"], rows=rows)
+    assert ref.rel_frobenius(ch1.fetch("O")[rows], want["O"]) <= 2e-2
+    assert ref.rel_frobenius(ch1.output("Y")[rows], want["Y"]) <= 2e-2

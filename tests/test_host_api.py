@@ -162,6 +162,8 @@ def test_descriptor_errors_are_caught_on_the_host():
     assert _err(api.lpg_attention_packed, q, qd, k, desc(LPG_PACKED_A, LPG_BF16, 80, 64), v, vd, o, od, 1.0) == api.LPG_EUNSUPPORTED
     assert _err(api.lpg_attention_packed, q, qd, k, kd, v, vd, q, od, 1.0) == api.LPG_EINVAL
     assert _err(api.lpg_attention_packed, q, qd, k, kd, v, vd, o, od, -1.0) == api.LPG_EINVAL
+    assert api.lib().lpg_attention_packed(q, ctypes.byref(qd), k, ctypes.byref(kd), v, ctypes.byref(vd), o,
+                                          ctypes.byref(od), 1.0, 4, None) == api.LPG_EINVAL   # unknown flag bit
     assert _err(api.lpg_attention_packed, q, qd, k, kd, v, vd, o, desc(LPG_PACKED_A, LPG_F32, 96, 64, batch=2), 1.0) == api.LPG_EINVAL
 
 
