@@ -771,7 +771,9 @@ struct AttnFrag {
 // SOFTMAX = false is the same walk without the softmax, O = (scale * Q K^T [causal]) V: the two
 // chained GEMMs of the GEMM-only attention workloads with their intermediate in registers
 // (bf16: rounded to bf16 exactly where the first GEMM's epilogue would have stored it).
-template <typename T, int DH, bool SOFTMAX>
+// QG = 32-query groups per wave (a workgroup owns 128*QG queries): with two groups every K and
+// V fragment read from LDS feeds two MFMAs instead of one, at twice the accumulator registers.
+template <typename T, int DH, bool SOFTMAX, int QG>
 __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
 {
     constexpr int NW = 4;
@@ -780,6 +782,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
     constexpr int DG = DH / 32;     // 32-groups of d
     constexpr int NFK = 2 * FD, NFV = DG * 2 * FK, NF = NFK + NFV, FPW = NF / NW;
     constexpr int STAGE = NF * kFragBytes;
+    constexpr int GPB = NW * QG;    // query groups per block
     static_assert(NF % NW == 0, "stage must divide over the waves");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
@@ -790,7 +793,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
     // Under a causal mask a query block's work grows with its position, so a workgroup takes
     // a pair: block p from the end, then block p from the start (the middle one alone when the
     // count is odd); every workgroup then walks the same number of key steps.
-    const int nqb = (a.q_groups + NW - 1) / NW;
+    const int nqb = (a.q_groups + GPB - 1) / GPB;
     const int pair = (int)(blockIdx.x / (uint32_t)a.batch);
     const int b = (int)(blockIdx.x % (uint32_t)a.batch);
     const int nparts = (a.causal && pair != nqb - 1 - pair) ? 2 : 1;
@@ -809,34 +812,40 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
 
     for (int part = 0; part < nparts; ++part) {
         const int qb = a.causal ? (part == 0 ? nqb - 1 - pair : pair) : pair;
-        const int g = qb * NW + w;
-        const bool have_g = g < a.q_groups;
-        const int q = 32 * g + (lane & 31);
-        int last = a.causal ? q + shift : a.tk - 1;  // last key this lane's query sees
-        last = last < a.tk - 1 ? last : a.tk - 1;
-        if (q >= a.tq) last = -1;
-        // keys the workgroup has to walk, and whether this wave can skip masking in a step
-        int wg_last = a.causal ? 32 * (qb * NW + NW) - 1 + shift : a.tk - 1;
+        const int g0 = (qb * NW + w) * QG;  // this wave's first query group
+        // keys the workgroup has to walk
+        int wg_last = a.causal ? 32 * (qb * GPB + GPB) - 1 + shift : a.tk - 1;
         wg_last = wg_last < a.tk - 1 ? wg_last : a.tk - 1;
         const int nsteps = wg_last < 0 ? 0 : wg_last / 64 + 1;
-        int wave_min_last = a.causal ? 32 * g + shift : a.tk - 1;  // smallest `last` among this wave's lanes
+        // smallest `last` among this wave's lanes: steps wholly below it need no masking
+        int wave_min_last = a.causal ? 32 * g0 + shift : a.tk - 1;
         wave_min_last = wave_min_last < a.tk - 1 ? wave_min_last : a.tk - 1;
-        if (32 * g + 31 >= a.tq) wave_min_last = -1;
+        if (32 * (g0 + QG) - 1 >= a.tq) wave_min_last = -1;
 
-        uint4 qf[FD];
+        int last[QG];  // last key this lane's query of group x sees
+        uint4 qf[QG][FD];
+        f32x16 o[QG][DG];
+        float m[QG], lsum[QG];  // reference maximum (shared by the half waves), this lane's part of the sum
 #pragma unroll
-        for (int fd = 0; fd < FD; ++fd) {
-            qf[fd] = make_uint4(0u, 0u, 0u, 0u);
-            if (have_g)
-                qf[fd] = *(const uint4 *)(a.Q + (int64_t)b * a.q_slot + (int64_t)(fd / 4) * a.q_kbs + (int64_t)g * kBlockBytes +
-                                          (fd % 4) * kFragBytes + lane * 16);
+        for (int x = 0; x < QG; ++x) {
+            const int g = g0 + x, q = 32 * g + (lane & 31);
+            last[x] = a.causal ? q + shift : a.tk - 1;
+            last[x] = last[x] < a.tk - 1 ? last[x] : a.tk - 1;
+            if (q >= a.tq) last[x] = -1;
+#pragma unroll
+            for (int fd = 0; fd < FD; ++fd) {
+                qf[x][fd] = make_uint4(0u, 0u, 0u, 0u);
+                if (g < a.q_groups)
+                    qf[x][fd] = *(const uint4 *)(a.Q + (int64_t)b * a.q_slot + (int64_t)(fd / 4) * a.q_kbs +
+                                                 (int64_t)g * kBlockBytes + (fd % 4) * kFragBytes + lane * 16);
+            }
+#pragma unroll
+            for (int dg = 0; dg < DG; ++dg)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[x][dg][e] = 0.0f;
+            m[x] = kNegBig;
+            lsum[x] = 0.0f;
         }
-        f32x16 o[DG];
-#pragma unroll
-        for (int dg = 0; dg < DG; ++dg)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o[dg][e] = 0.0f;
-        float m = kNegBig, lsum = 0.0f;  // reference maximum (shared by the half waves) and this lane's part of the sum
 
         // The stage written here was last read two steps ago (possibly by the previous part),
         // and every wave has passed the barrier of the step in between.
@@ -847,90 +856,108 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
             if (j + 1 < nsteps) issue(j + 1, (ring + 1) & 1);
             const char *sb = smem + (ring & 1) * STAGE + lane * 16;
 
-            // S^T tiles: registers run along 32 keys, lanes along the wave's 32 queries
-            f32x16 s[2];
+            // S^T tiles: registers run along 32 keys, lanes along 32 queries
+            f32x16 s[QG][2];
 #pragma unroll
             for (int kg = 0; kg < 2; ++kg) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) s[kg][e] = 0.0f;
+                for (int x = 0; x < QG; ++x)
 #pragma unroll
-                for (int fd = 0; fd < FD; ++fd)
-                    mma_frag<T>(s[kg], *(const uint4 *)(sb + (kg * FD + fd) * kFragBytes), qf[fd]);
+                    for (int e = 0; e < 16; ++e) s[x][kg][e] = 0.0f;
+#pragma unroll
+                for (int fd = 0; fd < FD; ++fd) {
+                    const uint4 kf = *(const uint4 *)(sb + (kg * FD + fd) * kFragBytes);
+#pragma unroll
+                    for (int x = 0; x < QG; ++x) mma_frag<T>(s[x][kg], kf, qf[x][fd]);
+                }
             }
-            // online softmax; key of register e of tile kg: 64j + 32kg + 8(e/4) + 4h + e%4
+            // key of register e of tile kg: 64j + 32kg + 8(e/4) + 4h + e%4
             const int key0 = 64 * j + 4 * h;
             const bool masked = 64 * j + 63 > wave_min_last;  // wave-uniform
-            if (masked) {
-                const float gone = SOFTMAX ? -__builtin_inff() : 0.0f;
 #pragma unroll
-                for (int kg = 0; kg < 2; ++kg)
+            for (int x = 0; x < QG; ++x) {
+                if (masked) {
+                    const float gone = SOFTMAX ? -__builtin_inff() : 0.0f;
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        s[kg][e] = (key0 + 32 * kg + 8 * (e >> 2) + (e & 3) <= last) ? s[kg][e] : gone;
-            }
-            if constexpr (SOFTMAX) {
-                float bmx = -__builtin_inff();
+                    for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
-                for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) bmx = fmaxf(bmx, s[kg][e]);
-                bmx = fmaxf(bmx, __shfl_xor(bmx, 32, 64));
-                // The reference point m of the exponentials only has to stay within 2^8 of the true
-                // running maximum (the final division cancels it), so O and the sum are rescaled only
-                // in the steps where some query of the wave moved further than that.
-                const float bm = bmx * sl;
-                if (__any(bm > m + 8.0f)) {
-                    const float mn = fmaxf(m, bm);
-                    const float alpha = __builtin_amdgcn_exp2f(m - mn);
-                    m = mn;
-                    lsum *= alpha;
-#pragma unroll
-                    for (int dg = 0; dg < DG; ++dg)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) o[dg][e] *= alpha;
+                        for (int e = 0; e < 16; ++e)
+                            s[x][kg][e] = (key0 + 32 * kg + 8 * (e >> 2) + (e & 3) <= last[x]) ? s[x][kg][e] : gone;
                 }
-                float psum = 0.0f;
+                if constexpr (SOFTMAX) {
+                    float bmx = -__builtin_inff();
 #pragma unroll
-                for (int kg = 0; kg < 2; ++kg)
+                    for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        s[kg][e] = __builtin_amdgcn_exp2f(fmaf(s[kg][e], sl, -m));
-                        psum += s[kg][e];
+                        for (int e = 0; e < 16; ++e) bmx = fmaxf(bmx, s[x][kg][e]);
+                    bmx = fmaxf(bmx, __shfl_xor(bmx, 32, 64));
+                    // The reference point m of the exponentials only has to stay within 2^8 of the
+                    // true running maximum (the final division cancels it), so O and the sum are
+                    // rescaled only in the steps where some query of the wave moved further than that.
+                    const float bm = bmx * sl;
+                    if (__any(bm > m[x] + 8.0f)) {
+                        const float mn = fmaxf(m[x], bm);
+                        const float alpha = __builtin_amdgcn_exp2f(m[x] - mn);
+                        m[x] = mn;
+                        lsum[x] *= alpha;
+#pragma unroll
+                        for (int dg = 0; dg < DG; ++dg)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) o[x][dg][e] *= alpha;
                     }
-                lsum += psum;
-            } else if (a.scale != 1.0f) {
+                    float psum = 0.0f;
 #pragma unroll
-                for (int kg = 0; kg < 2; ++kg)
+                    for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) s[kg][e] *= a.scale;
+                        for (int e = 0; e < 16; ++e) {
+                            s[x][kg][e] = __builtin_amdgcn_exp2f(fmaf(s[x][kg][e], sl, -m[x]));
+                            psum += s[x][kg][e];
+                        }
+                    lsum[x] += psum;
+                } else if (a.scale != 1.0f) {
+#pragma unroll
+                    for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) s[x][kg][e] *= a.scale;
+                }
             }
             // P's fragments are the registers as they stand (bf16: rounded in pairs); O^T += V^T P^T
 #pragma unroll
             for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
                 for (int c = 0; c < FK; ++c) {
-                    uint4 pf;
-                    if constexpr (T::ES == 4) {
-                        pf = make_uint4(__float_as_uint(s[kg][4 * c]), __float_as_uint(s[kg][4 * c + 1]),
-                                        __float_as_uint(s[kg][4 * c + 2]), __float_as_uint(s[kg][4 * c + 3]));
-                    } else {
-                        pf = make_uint4(bf16_pack2(s[kg][8 * c], s[kg][8 * c + 1]), bf16_pack2(s[kg][8 * c + 2], s[kg][8 * c + 3]),
-                                        bf16_pack2(s[kg][8 * c + 4], s[kg][8 * c + 5]), bf16_pack2(s[kg][8 * c + 6], s[kg][8 * c + 7]));
+                    uint4 pf[QG];
+#pragma unroll
+                    for (int x = 0; x < QG; ++x) {
+                        const f32x16 &t = s[x][kg];
+                        if constexpr (T::ES == 4) {
+                            pf[x] = make_uint4(__float_as_uint(t[4 * c]), __float_as_uint(t[4 * c + 1]),
+                                               __float_as_uint(t[4 * c + 2]), __float_as_uint(t[4 * c + 3]));
+                        } else {
+                            pf[x] = make_uint4(bf16_pack2(t[8 * c], t[8 * c + 1]), bf16_pack2(t[8 * c + 2], t[8 * c + 3]),
+                                               bf16_pack2(t[8 * c + 4], t[8 * c + 5]), bf16_pack2(t[8 * c + 6], t[8 * c + 7]));
+                        }
                     }
 #pragma unroll
-                    for (int dg = 0; dg < DG; ++dg)
-                        mma_frag<T>(o[dg], *(const uint4 *)(sb + (NFK + dg * 2 * FK + kg * FK + c) * kFragBytes), pf);
+                    for (int dg = 0; dg < DG; ++dg) {
+                        const uint4 vf = *(const uint4 *)(sb + (NFK + dg * 2 * FK + kg * FK + c) * kFragBytes);
+#pragma unroll
+                        for (int x = 0; x < QG; ++x) mma_frag<T>(o[x][dg], vf, pf[x]);
+                    }
                 }
         }
-        if (have_g) {
-            const float l = SOFTMAX ? lsum + __shfl_xor(lsum, 32, 64) : 1.0f;
+#pragma unroll
+        for (int x = 0; x < QG; ++x) {
+            const int g = g0 + x, q = 32 * g + (lane & 31);
+            if (g >= a.q_groups) continue;
+            const float l = SOFTMAX ? lsum[x] + __shfl_xor(lsum[x], 32, 64) : 1.0f;
             const float inv = (l > 0.0f && q < a.tq) ? 1.0f / l : 0.0f;  // padding rows and rows without keys: zeros
             char *Ob = a.O + (int64_t)b * a.o_slot + (int64_t)g * kBlockBytes + lane * 16;
 #pragma unroll
             for (int dg = 0; dg < DG; ++dg) {
                 float v[16];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) v[e] = o[dg][e] * inv;
+                for (int e = 0; e < 16; ++e) v[e] = o[x][dg][e] * inv;
                 if constexpr (T::ES == 4) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
@@ -950,13 +977,13 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
     wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
 }
 
-template <typename T, int DH, bool SOFTMAX>
+template <typename T, int DH, bool SOFTMAX, int QG>
 static hipError_t launch_attention_dh(const AttnArgs &a, hipStream_t st)
 {
     constexpr int NF = 2 * (DH / T::KF) + (DH / 32) * 2 * (32 / T::KF);
     constexpr size_t lds = 2 * (size_t)NF * kFragBytes;
     static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
-    auto kern = attention_kernel<T, DH, SOFTMAX>;
+    auto kern = attention_kernel<T, DH, SOFTMAX, QG>;
     if (lds > 64 * 1024) {
         static bool done = false;
         if (!done) {
@@ -965,16 +992,28 @@ static hipError_t launch_attention_dh(const AttnArgs &a, hipStream_t st)
             done = true;
         }
     }
-    const int nqb = (a.q_groups + 3) / 4;
+    const int nqb = (a.q_groups + 4 * QG - 1) / (4 * QG);
     const int64_t grid = (int64_t)(a.causal ? (nqb + 1) / 2 : nqb) * a.batch;  // causal: query blocks in pairs
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
+// Two query groups per wave pay only where a launch keeps several workgroups per compute
+// unit even so and all of them do the same work: bf16, head_dim 64, no causal mask, at least
+// 512 workgroups (measured 113 against 123 us on 32 heads x 4096 x 4096; under a causal mask the
+// larger blocks lose more to imbalance than the reuse gives).  LPG_ATTN_QG=1|2 pins the choice
+// for head_dim 64 (a tuning and test aid).
 template <typename T, int DH>
 static hipError_t launch_attention_mode(const AttnArgs &a, hipStream_t st)
 {
-    return a.softmax ? launch_attention_dh<T, DH, true>(a, st) : launch_attention_dh<T, DH, false>(a, st);
+    if constexpr (DH == 64) {
+        const int64_t wgs2 = (int64_t)((a.q_groups + 7) / 8) * a.batch;
+        int qg = (T::ES == 2 && !a.causal && wgs2 >= 512) ? 2 : 1;
+        if (const char *f = getenv("LPG_ATTN_QG")) qg = atoi(f) == 2 ? 2 : 1;
+        if (qg == 2)
+            return a.softmax ? launch_attention_dh<T, DH, true, 2>(a, st) : launch_attention_dh<T, DH, false, 2>(a, st);
+    }
+    return a.softmax ? launch_attention_dh<T, DH, true, 1>(a, st) : launch_attention_dh<T, DH, false, 1>(a, st);
 }
 
 hipError_t launch_attention(const AttnArgs &a, int dtype, int head_dim, hipStream_t st)
