@@ -30,12 +30,16 @@ GEMM_ALGORITHMIC_BYTES = 60.0 * 2 ** 20
 HEADLINE = "mlp"
 
 
-def settle(ch, mode, seconds=0.05):
+SETTLE_SECONDS = 0.05
+
+
+def settle(ch, mode, seconds=None):
     """Set-up, before any warm-up or timed step: run the chain for ~50 ms once per chain and mode
     so that the device's clocks and the first-launch costs (code upload, LDS size attributes) are
     behind it.  Without it the first few milliseconds of a run measure the clock ramp: the same
     20 timed steps read 0.33 ms per step straight after start-up and 0.28 ms from then on."""
     import torch
+    seconds = SETTLE_SECONDS if seconds is None else seconds
     done = ch.__dict__.setdefault("_settled_modes", set())
     if mode in done:
         return
@@ -339,6 +343,9 @@ def main():
                          "llama_layer or llama_layer_fused_attention) and print its line")
     ap.add_argument("--mode", default="both", choices=["both", "propagated", "canonical"],
                     help="with --only: which chain mode(s) to run")
+    ap.add_argument("--settle-ms", type=float, default=50.0,
+                    help="set-up run of each chain before its warm-up steps, in milliseconds (0 for counter "
+                         "collection runs, where every extra launch is paid for)")
     ap.add_argument("--sweep", action="store_true",
                     help="run the synthetic single-GEMM / three-GEMM-chain size sweep instead (--steps = "
                          "repetitions per case) and print one JSON line per case")
@@ -349,6 +356,8 @@ def main():
                     help="profiling aid: run the elementwise SCALE kernel over a buffer of MIB MiB "
                          "(reads MIB, writes MIB per launch) --steps times, to scale HBM counters")
     args = ap.parse_args()
+    global SETTLE_SECONDS
+    SETTLE_SECONDS = args.settle_ms * 1e-3
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
