@@ -573,6 +573,11 @@ static hipError_t launch_row_dtype(const RowArgs &a, bool packed, hipStream_t st
                                         {8, 8, false}, {32, 4, true}};
     auto fits = [&](int v) { return !kVariants[v].cached || kVariants[v].r * a.nkb <= 128 * kVariants[v].nw; };
     int variant = fits(5) ? 5 : fits(0) ? 0 : fits(1) ? 1 : fits(2) ? 2 : fits(3) ? 3 : 4;  // short rows: 4 waves
+    // few row groups (a 4096-row activation matrix has 128): fewer rows per workgroup, so that
+    // the launch still has a couple of workgroups per compute unit
+    const int64_t groups = (int64_t)a.batch * a.ngroups;
+    while ((variant == 5 || variant == 0 || variant == 1) && groups * (32 / kVariants[variant].r) < 512)
+        variant = variant == 5 ? 0 : variant + 1;
     if (const char *f = getenv("LPG_ROW_VARIANT")) {
         const int v = atoi(f);
         if (v >= 0 && v < 6 && fits(v)) variant = v;
