@@ -102,6 +102,23 @@ __device__ __forceinline__ void mma_frag(f32x16 &acc, const uint4 &r, const uint
     }
 }
 
+// The same product in J = mma_depth<IN>() separately issued parts (part j of an fp32 fragment is
+// its j-th k-pair; a bf16 fragment is one part).
+template <typename IN>
+__device__ __forceinline__ constexpr int mma_depth() { return IN::ES == 4 ? 4 : 1; }
+template <typename IN>
+__device__ __forceinline__ void mma_part(f32x16 &acc, const uint4 &r, const uint4 &l, int j)
+{
+    if constexpr (IN::ES == 4) {
+        const uint32_t rj = j == 0 ? r.x : j == 1 ? r.y : j == 2 ? r.z : r.w;
+        const uint32_t lj = j == 0 ? l.x : j == 1 ? l.y : j == 2 ? l.z : l.w;
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(rj), __uint_as_float(lj), acc, 0, 0, 0);
+    } else {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, r), __builtin_bit_cast(bf16x8, l),
+                                                      acc, 0, 0, 0);
+    }
+}
+
 __device__ __forceinline__ float epi_apply(int epi, float v, float g)
 {
     if (epi == LPG_EPI_SILU) return silu_f(v);
@@ -429,7 +446,11 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
             // the last real step the transfers go on as harmless refills of the one ring
             // stage nobody reads again (their sources stay valid), which keeps this loop free
             // of branches.
-            constexpr int SLOTS = FS * WTL;
+            // A fragment is J MFMAs deep (fp32: four k-pairs, bf16: one); the k-pairs are the
+            // outer loop so that consecutive MFMAs go to different accumulators and a tile's
+            // accumulator comes round again only after all the wave's other tiles.
+            constexpr int J = mma_depth<IN>();
+            constexpr int SLOTS = FS * J * WTL;
 #pragma unroll
             for (int c = 0; c < FS; ++c) {
                 const int cb = c & 1, nb = (c + 1) & 1;
@@ -437,21 +458,26 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
                 const char *nL = more ? sL + (c + 1) * kFragBytes : sLw + stn * STAGE;
                 const char *nR = more ? sR + (c + 1) * kFragBytes : sRw + stn * STAGE;
 #pragma unroll
-                for (int a = 0; a < WTL; ++a) {
-                    if (more || XPF) {
-                        lf[nb][a] = *(const uint4 *)(nL + a * (FS * kFragBytes));
-                        if (a < WTR) rf[nb][a] = *(const uint4 *)(nR + a * (FS * kFragBytes));
-                        if (a == WTL - 1) {
+                for (int j = 0; j < J; ++j) {
 #pragma unroll
-                            for (int q = WTL; q < WTR; ++q) rf[nb][q] = *(const uint4 *)(nR + q * (FS * kFragBytes));
+                    for (int a = 0; a < WTL; ++a) {
+                        if (j == 0 && (more || XPF)) {
+                            lf[nb][a] = *(const uint4 *)(nL + a * (FS * kFragBytes));
+                            if (a < WTR) rf[nb][a] = *(const uint4 *)(nR + a * (FS * kFragBytes));
+                            if (a == WTL - 1) {
+#pragma unroll
+                                for (int q = WTL; q < WTR; ++q) rf[nb][q] = *(const uint4 *)(nR + q * (FS * kFragBytes));
+                            }
                         }
+#pragma unroll
+                        for (int q = 0; q < WTR; ++q) mma_part<IN>(acc[a][q], rf[cb][q], lf[cb][a], j);
+                        const int slot = (c * J + j) * WTL + a;
+#pragma unroll
+                        for (int i = (slot * FPW) / SLOTS; i < ((slot + 1) * FPW) / SLOTS; ++i) copy_issue(i);
+                        // fp32: one fence per k-pair round (a round already touches every accumulator
+                        // once); bf16: one per row of tiles
+                        if (J == 1 || a == WTL - 1) __builtin_amdgcn_sched_barrier(0);
                     }
-#pragma unroll
-                    for (int q = 0; q < WTR; ++q) mma_frag<IN>(acc[a][q], rf[cb][q], lf[cb][a]);
-                    const int slot = c * WTL + a;
-#pragma unroll
-                    for (int i = (slot * FPW) / SLOTS; i < ((slot + 1) * FPW) / SLOTS; ++i) copy_issue(i);
-                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             st = stn;
