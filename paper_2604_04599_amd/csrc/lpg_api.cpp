@@ -44,8 +44,14 @@ static inline int nbatch(const lpg_desc *d) { return d->batch > 0 ? d->batch : 1
 static inline int bdiv(const lpg_desc *d) { return d->batch_div > 0 ? d->batch_div : 1; }
 static inline int nslots(const lpg_desc *d) { return (nbatch(d) + bdiv(d) - 1) / bdiv(d); }
 
-// Reduce a packed descriptor to a PView and validate its geometry.
-static int make_pview(const lpg_desc *d, const char *what, PView *v)
+// Reduce a packed descriptor to a PView and validate its geometry.  A ragged extent (not a
+// multiple of 32 along the free index, of KB along the contraction index) normally has to end
+// at the parent's edge, where its padding is the parent's own.  `inner` names the dimensions
+// in which the caller can also take a ragged extent that ends inside the parent: the view's
+// last block is then shared with neighbouring elements of the parent, keep_f / keep_k are set,
+// and a writer must leave those neighbours alone.
+enum { kInnerF = 1, kInnerK = 2 };
+static int make_pview(const lpg_desc *d, const char *what, PView *v, unsigned inner = 0)
 {
     int rc = check_common(d, what);
     if (rc) return rc;
@@ -83,9 +89,11 @@ static int make_pview(const lpg_desc *d, const char *what, PView *v)
         return fail(LPG_EALIGN, "%s: stepped views need a free extent that is a multiple of 32", what);
     if (v->K % KB && (ns > 1 ? v->kstep != 0 : false))
         return fail(LPG_EALIGN, "%s: stepped views need a contraction extent that is a multiple of %d", what, (int)KB);
-    if (v->F % 32 && v->f0 + v->F != v->PF)
+    v->keep_f = v->F % 32 && v->f0 + v->F != v->PF;
+    v->keep_k = v->K % KB && v->k0 + v->K != v->PK;
+    if (v->keep_f && !(inner & kInnerF))
         return fail(LPG_EALIGN, "%s: a free extent that is not a multiple of 32 must end at the parent's edge", what);
-    if (v->K % KB && v->k0 + v->K != v->PK)
+    if (v->keep_k && !(inner & kInnerK))
         return fail(LPG_EALIGN, "%s: a contraction extent that is not a multiple of %d must end at the parent's edge", what, (int)KB);
     if (ns > 1 && v->bstride != 0 && v->bstride < v->PFp * v->PKp)
         return fail(LPG_EINVAL, "%s: batch_stride smaller than one packed parent", what);
@@ -162,7 +170,7 @@ static int do_pack_unpack(bool pack, const void *canon, const lpg_desc *cd, cons
     const char *name = pack ? "lpg_pack" : "lpg_unpack";
     PView pv;
     CView cv;
-    int rc = make_pview(pd, pack ? "lpg_pack dst" : "lpg_unpack src", &pv);
+    int rc = make_pview(pd, pack ? "lpg_pack dst" : "lpg_unpack src", &pv, kInnerF | kInnerK);
     if (rc) return rc;
     rc = make_cview(cd, pack ? "lpg_pack src" : "lpg_unpack dst", &cv);
     if (rc) return rc;
@@ -194,6 +202,8 @@ static int do_pack_unpack(bool pack, const void *canon, const lpg_desc *cd, cons
     a.nkb = (int32_t)((pv.K + kb_of(pv.dtype) - 1) / kb_of(pv.dtype));
     a.batch = pv.batch;
     a.kpw = 1;
+    a.keep_f = pv.keep_f;
+    a.keep_k = pv.keep_k;
     if (a.nkb > 65535 || a.batch > 65535) return fail(LPG_EUNSUPPORTED, "%s: more than 65535 K blocks or batches", name);
     hipError_t e = pack ? launch_pack(a, cv.dtype, pv.dtype, st) : launch_unpack(a, pv.dtype, cv.dtype, st);
     if (e != hipSuccess) return fail(LPG_EHIP, "%s: %s", name, hipGetErrorString(e));
@@ -227,7 +237,9 @@ static int make_operand(const lpg_desc *d, const void *ptr, bool is_a, Operand *
         if (d->kind != (is_a ? LPG_PACKED_A : LPG_PACKED_B))
             return fail(LPG_ELAYOUT, "%s: must be %s", what, is_a ? "LPG_PACKED_A" : "LPG_PACKED_B");
         PView v;
-        rc = make_pview(d, what, &v);
+        // rows past a ragged free extent only feed output elements that are never stored; a
+        // ragged contraction extent inside a parent would add the neighbours into every sum
+        rc = make_pview(d, what, &v, kInnerF);
         if (rc) return rc;
         *o = Operand{false, v.dtype, v.F, v.K, v.batch, v.bdiv, v.origin, v.slot_step, v.kb_stride, 0};
         return LPG_OK;
@@ -262,7 +274,7 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     const bool c_canon = is_canon(c_d->kind);
     PView cv{};
     CView ccv{};
-    rc = c_canon ? make_cview(c_d, "lpg_gemm_packed C", &ccv) : make_pview(c_d, "lpg_gemm_packed C", &cv);
+    rc = c_canon ? make_cview(c_d, "lpg_gemm_packed C", &ccv) : make_pview(c_d, "lpg_gemm_packed C", &cv, kInnerF | kInnerK);
     if (rc) return rc;
     const int c_dtype = c_d->dtype, c_batch = nbatch(c_d);
     if (ao.K != bo.K)
@@ -297,6 +309,7 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     const Operand &L = l_is_a ? ao : bo;
     const Operand &R = l_is_a ? bo : ao;
     GemmArgs g;
+    g.o_keep_l = g.o_keep_r = 0;
     g.L = (const char *)(l_is_a ? A : B) + L.origin;
     g.R = (const char *)(l_is_a ? B : A) + R.origin;
     g.l_canon = L.canon;
@@ -327,6 +340,8 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
         g.o_slot = cv.slot_step;
         g.o_sf = g.o_sk = 0;
         g.FRg_out = (int32_t)(round_up(R.F, kb_of(c_dtype)) / 32);
+        g.o_keep_l = cv.keep_f;
+        g.o_keep_r = cv.keep_k;
     }
     g.Cin = (beta != 0.0f) ? (const char *)C_in + c_origin : nullptr;
     g.Epi = epi_arg ? (const char *)epi_arg + c_origin : nullptr;
@@ -656,7 +671,7 @@ static int validate_stage(const lpg_stage &s, int i)
             PView pv;
             CView cv;
             const bool pk = s.type == LPG_STAGE_PACK;
-            int rc = make_pview(pk ? &s.out_d : &s.in0_d, "lpg_chain pack/unpack", &pv);
+            int rc = make_pview(pk ? &s.out_d : &s.in0_d, "lpg_chain pack/unpack", &pv, kInnerF | kInnerK);
             if (rc) return rc;
             rc = make_cview(pk ? &s.in0_d : &s.out_d, "lpg_chain pack/unpack", &cv);
             if (rc) return rc;
@@ -893,7 +908,7 @@ int lpg_layout_offset(const lpg_desc *d, int64_t b, int64_t row, int64_t col, in
         return LPG_OK;
     }
     PView v;
-    rc = make_pview(d, "lpg_layout_offset", &v);
+    rc = make_pview(d, "lpg_layout_offset", &v, kInnerF | kInnerK);
     if (rc) return rc;
     const int64_t f = v.transposed ? col : row, k = v.transposed ? row : col;
     const int64_t KB = kb_of(v.dtype), KV = 16 / v.es, KF = 2 * KV;

@@ -246,6 +246,20 @@ __device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc,
             const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
             if (fl >= p.FL || fr >= p.FR) v[e] = 0.0f;
         }
+        if (p.o_keep_l | p.o_keep_r) {
+            // the view's ragged extent ends inside its parent: what lies past it in this tile
+            // belongs to the parent's other elements and is left as it is
+            const bool l_mine = fl < p.FL || !p.o_keep_l;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+                if (!l_mine || (fr >= p.FR && p.o_keep_r)) continue;
+                char *dst = Ob + obase + (e / PER) * kFragBytes + (e % PER) * OUT::ES;
+                if constexpr (OUT::ES == 4) *(float *)dst = v[e];
+                else *(uint16_t *)dst = (uint16_t)bf16_rne(v[e]);
+            }
+            return;
+        }
     }
     if constexpr (OUT::ES == 4) {
 #pragma unroll

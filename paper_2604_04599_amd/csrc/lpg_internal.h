@@ -33,6 +33,7 @@ struct PView {
     int64_t origin;        // bytes from buffer start to slot 0's first block
     int64_t slot_step;     // bytes added per slot
     bool transposed;       // kind == PACKED_B (free = cols)
+    bool keep_f, keep_k;   // ragged extent ending inside the parent: its last block is shared
 };
 
 // A canonical descriptor reduced to strides over (free, contraction) indices.
@@ -58,6 +59,7 @@ struct PackArgs {
     int32_t nkb;         // ceil(K/KB)
     int32_t batch;
     int32_t kpw;         // K blocks per workgroup (set by the launcher)
+    int32_t keep_f, keep_k;  // pack: leave packed elements past F / past K untouched
 };
 
 struct GemmArgs {
@@ -83,6 +85,7 @@ struct GemmArgs {
     int32_t tiles_l, tiles_r, batch;
     int32_t epi;
     float alpha, beta;
+    int32_t o_keep_l, o_keep_r;      // packed out: leave elements past FL / past FR untouched
 };
 
 struct EwArgs {

@@ -85,7 +85,17 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs a)
                 }
 #pragma unroll
                 for (int j = 0; j < PER; ++j) pv[j] = convert_raw<C, P>(cv[j]);
-                if constexpr (P::ES == 4) {
+                // a view whose ragged extent ends inside its parent shares this block with the
+                // parent's other elements: write only what belongs to the view
+                const bool f_mine = row_in || !a.keep_f;
+                if (!f_mine || (a.keep_k && kbase + PER > a.K)) {
+#pragma unroll
+                    for (int j = 0; j < PER; ++j) {
+                        if (!f_mine || kbase + j >= a.K) continue;
+                        if constexpr (P::ES == 4) *(praw *)(dst0 + (piece & 1) * 512 + j * 4) = pv[j];
+                        else *(praw *)(dst0 + (j >> 2) * 512 + (piece & 1) * 8 + (j & 3) * 2) = pv[j];
+                    }
+                } else if constexpr (P::ES == 4) {
                     *(uint4 *)(dst0 + (piece & 1) * 512) = make_uint4(pv[0], pv[1], pv[2], pv[3]);
                 } else {
 #pragma unroll
@@ -141,7 +151,15 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs a)
                     canon[k * a.sk + f] = convert_raw<P, C>(v[j]);
             }
             if constexpr (PACK) {
-                if constexpr (P::ES == 4) {
+                const int64_t k_hi = (int64_t)kb * KB + KF * c + KF - 1;  // largest k this thread holds
+                const bool f_mine = f < a.F || !a.keep_f;
+                if (!f_mine || (a.keep_k && k_hi >= a.K)) {
+#pragma unroll
+                    for (int j = 0; j < KV; ++j) {
+                        const int64_t k = (int64_t)kb * KB + KF * c + 8 * (j >> 2) + 4 * h + (j & 3);
+                        if (f_mine && k < a.K) dst[j] = v[j];
+                    }
+                } else if constexpr (P::ES == 4) {
                     *(uint4 *)dst = make_uint4(v[0], v[1], v[2], v[3]);
                 } else {
                     uint32_t w[4];

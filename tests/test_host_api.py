@@ -117,8 +117,20 @@ def test_descriptor_errors_are_caught_on_the_host():
     # views: misaligned origin, ragged extent away from the edge
     bad = desc(LPG_PACKED_A, LPG_F32, 32, 32, parent=(64, 64), origin=(16, 0))
     assert _err(api.lpg_pack, fake, desc(LPG_ROW_MAJOR, LPG_F32, 32, 32), fake, bad) == api.LPG_EALIGN
-    bad = desc(LPG_PACKED_A, LPG_F32, 20, 32, parent=(64, 64), origin=(0, 0))
-    assert _err(api.lpg_pack, fake, desc(LPG_ROW_MAJOR, LPG_F32, 20, 32), fake, bad) == api.LPG_EALIGN
+    # a ragged extent that ends inside the parent: refused where neighbours would be read into
+    # a sum (contraction extent of a GEMM input) and by the row, elementwise, attention calls
+    inner_k = desc(LPG_PACKED_A, LPG_F32, 64, 20, parent=(64, 64), origin=(0, 0))
+    assert _err(api.lpg_gemm_packed, 1.0, fake, inner_k, fake, desc(LPG_PACKED_B, LPG_F32, 20, 64), 0.0, None,
+                2 * fake, pa) == api.LPG_EALIGN
+    inner_kb = desc(LPG_PACKED_B, LPG_F32, 20, 64, parent=(64, 64), origin=(0, 0))
+    assert _err(api.lpg_gemm_packed, 1.0, fake, desc(LPG_PACKED_A, LPG_F32, 64, 20), fake, inner_kb, 0.0, None,
+                2 * fake, pa) == api.LPG_EALIGN
+    inner_f = desc(LPG_PACKED_A, LPG_F32, 20, 32, parent=(64, 64), origin=(0, 0))
+    assert _err(api.lpg_softmax_packed, fake, fake, inner_f, 1.0, False) == api.LPG_EALIGN
+    assert _err(api.lpg_rmsnorm_packed, fake, fake, fake, inner_f, 1e-5) == api.LPG_EALIGN
+    stepped = desc(LPG_PACKED_A, LPG_F32, 20, 32, parent=(64, 64), batch=2, batch_step=(32, 0))
+    assert _err(api.lpg_pack, fake, desc(LPG_ROW_MAJOR, LPG_F32, 20, 32, batch=2, batch_stride=640), fake,
+                stepped) == api.LPG_EALIGN
     bad = desc(LPG_PACKED_A, LPG_F32, 64, 64, parent=(64, 64), origin=(32, 0))
     assert _err(api.lpg_pack, fake, rm, fake, bad) == api.LPG_EINVAL
     assert "exceeds" in api.lpg_last_error()
