@@ -352,6 +352,11 @@ def main():
     ap.add_argument("--gemm", default=None, metavar="M,N,K,DTYPE",
                     help="profiling aid: run one packed-in, packed-out GEMM C[MxN] = A[MxK] B[KxN] (DTYPE f32 or "
                          "bf16) --steps times and print its rate")
+    ap.add_argument("--gemm-data", default="zeros", choices=["zeros", "randn"],
+                    help="with --gemm: operand values (the bf16 rate depends on them through the clock)")
+    ap.add_argument("--gemm-seconds", type=float, default=0.0,
+                    help="with --gemm: instead of --steps launches, run back to back for this long and sample "
+                         "rocm-smi's shader clock every 0.3 s meanwhile")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="profiling aid: run the elementwise SCALE kernel over a buffer of MIB MiB "
                          "(reads MIB, writes MIB per launch) --steps times, to scale HBM counters")
@@ -382,9 +387,43 @@ def main():
         a_p, w_p, c_p = (api.desc(kind, dtype, r, c) for kind, r, c in
                          ((api.LPG_PACKED_A, m, k), (api.LPG_PACKED_B, k, n), (api.LPG_PACKED_A, m, n)))
         pa, pw, pc = (torch.zeros(api.lpg_packed_bytes(d), dtype=torch.uint8, device="cuda") for d in (a_p, w_p, c_p))
+        if args.gemm_data == "randn":   # a permutation of i.i.d. values is i.i.d.: fill the packed buffers directly
+            tdt = torch.float32 if dt == "f32" else torch.bfloat16
+            torch.manual_seed(7)
+            pa.view(tdt).copy_(torch.randn(pa.numel() // pa.view(tdt).element_size(), device="cuda").to(tdt))
+            pw.view(tdt).copy_((torch.randn(pw.numel() // pw.view(tdt).element_size(), device="cuda") / k ** 0.5).to(tdt))
         st = torch.cuda.current_stream().cuda_stream
-        t = _time_calls(lambda: api.lpg_gemm_packed(1.0, pa, a_p, pw, w_p, 0.0, None, pc, c_p, stream=st), args.steps)
-        print(json.dumps({"gemm": args.gemm, "us": round(t * 1e6, 2), "tflops": round(2.0 * m * n * k / t / 1e12, 2)}))
+        call = lambda: api.lpg_gemm_packed(1.0, pa, a_p, pw, w_p, 0.0, None, pc, c_p, stream=st)
+        if args.gemm_seconds > 0:
+            import re
+            import subprocess
+            import threading
+            clocks, stop = [], threading.Event()
+
+            def sample():
+                while not stop.wait(0.3):
+                    out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True).stdout
+                    clocks.extend(int(x) for x in re.findall(r"sclk clock level: \d+: \((\d+)Mhz\)", out)[:1])
+            for _ in range(20):
+                call()
+            torch.cuda.synchronize()
+            th = threading.Thread(target=sample)
+            th.start()
+            t0, n_it = time.perf_counter(), 0
+            while time.perf_counter() - t0 < args.gemm_seconds:
+                for _ in range(50):
+                    call()
+                torch.cuda.synchronize()
+                n_it += 50
+            t = (time.perf_counter() - t0) / n_it
+            stop.set()
+            th.join()
+            print(json.dumps({"gemm": args.gemm, "data": args.gemm_data, "us": round(t * 1e6, 2),
+                              "tflops": round(2.0 * m * n * k / t / 1e12, 2), "sclk_mhz": clocks}))
+            return
+        t = _time_calls(call, args.steps)
+        print(json.dumps({"gemm": args.gemm, "data": args.gemm_data, "us": round(t * 1e6, 2),
+                          "tflops": round(2.0 * m * n * k / t / 1e12, 2)}))
         return
 
     if args.copy_calibration:
