@@ -545,11 +545,12 @@ constexpr int ring_ns(bool bf16, int tlg, int trg, int nw)
 
 // fp32 with small tiles and no more tiles than compute units: a step's MFMAs (2048 cycles
 // for a 128 x 64 tile) are shorter than the memory latency under load, and no second
-// workgroup shares the compute unit to cover for it, so the ring is made deeper instead.
+// workgroup shares the compute unit to cover for it, so the ring is made deeper instead: as
+// deep as the whole LDS allows, the lone workgroup has it to itself.
 constexpr int ring_ns_lone(int tlg, int trg)
 {
     const int stage = (tlg + trg) * 4 * kFragBytes;
-    return 4 * stage <= 96 * 1024 ? 4 : (3 * stage <= 96 * 1024 ? 3 : 2);
+    return 4 * stage <= 160 * 1024 ? 4 : (3 * stage <= 160 * 1024 ? 3 : 2);
 }
 
 static int lds_bytes(const TileCfg &c, bool bf16)
