@@ -1094,6 +1094,12 @@ static hipError_t launch_gemm_dtype(const GemmArgs &a, int cfg, hipStream_t st)
 int choose_gemm_config(const GemmArgs &a, int in_dtype)
 {
     const bool bf16 = in_dtype == LPG_BF16;
+    // A contraction of at most 64 (attention scores with head_dim 64) makes the launch a stream
+    // of epilogues bound by the stores; the cost model has no term for that.  Measured on
+    // 32 heads of 2048^2 / 4096^2 scores: two workgroups per compute unit, so that one stores
+    // while the other multiplies, with 128 x 256 tiles in bf16 (255 us against 276-365 us for
+    // the others) and 128 x 128 in fp32 (187 against 195-219).
+    if (a.nkb * (bf16 ? 64 : 32) <= 64 && a.FLg >= 16 && a.FRg >= 16) return bf16 ? 5 : 3;
     int best = 3;
     double best_cost = 1e300;
     for (int i = 0; i < kNumCfgs; ++i) {
