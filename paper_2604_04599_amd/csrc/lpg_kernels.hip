@@ -1066,7 +1066,7 @@ static double estimate_cost(const GemmArgs &a, const TileCfg &c, bool bf16)
     const int nkb = a.nkb > 0 ? a.nkb : 1;
     const double cy_block = bf16 ? 128.0 : 1024.0;  // MFMA cycles of one 32x32 tile over one K block
     const int resident = (int)((per_cu < occ ? per_cu : occ) * waves_per_simd);  // waves per SIMD
-    double eff = resident >= 2 ? 1.0 : (bf16 ? 0.8 : 1.0);
+    double eff = resident >= 2 ? 1.0 : (bf16 ? 0.6 : 1.0);
     const double reads_per_mma = (double)(wtl + wtr) / (wtl * wtr);
     eff /= 1.0 + (bf16 ? 0.217 : 0.0525) * reads_per_mma;
     const double mfma = (double)per_cu * (c.tlg * c.trg / 4.0) * nkb * cy_block / eff;
@@ -1094,12 +1094,17 @@ static hipError_t launch_gemm_dtype(const GemmArgs &a, int cfg, hipStream_t st)
 int choose_gemm_config(const GemmArgs &a, int in_dtype)
 {
     const bool bf16 = in_dtype == LPG_BF16;
-    // A contraction of at most 64 (attention scores with head_dim 64) makes the launch a stream
-    // of epilogues bound by the stores; the cost model has no term for that.  Measured on
+    // A contraction of at most 256 (attention scores, whatever the head_dim) with at least two
+    // tiles per compute unit makes the launch a stream of epilogues bound by the stores; the
+    // cost model has no term for that.  Measured on
     // 32 heads of 2048^2 / 4096^2 scores: two workgroups per compute unit, so that one stores
     // while the other multiplies, with 128 x 256 tiles in bf16 (255 us against 276-365 us for
     // the others) and 128 x 128 in fp32 (187 against 195-219).
-    if (a.nkb * (bf16 ? 64 : 32) <= 64 && a.FLg >= 16 && a.FRg >= 16) return bf16 ? 5 : 3;
+    {
+        const TileCfg &c = kCfgs[bf16 ? 5 : 3];
+        const int64_t tiles = (int64_t)((a.FLg + c.tlg - 1) / c.tlg) * ((a.FRg_out + c.trg - 1) / c.trg) * a.batch;
+        if (a.nkb * (bf16 ? 64 : 32) <= 256 && tiles >= 512) return bf16 ? 5 : 3;
+    }
     int best = 3;
     double best_cost = 1e300;
     for (int i = 0; i < kNumCfgs; ++i) {
