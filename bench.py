@@ -225,6 +225,13 @@ def measure(name, steps, warmup, shape_over=None, modes="both", options=None):
             res["fused_attention_tflops"] = round(flops / t_a / 1e12, 2)
             res["fused_attention_stages"] = stage_breakdown(ach, max(3, steps // 2))
             del ach
+            if name != "attention":   # (the attention kernel itself takes packed operands only)
+                # both: fused attention kernel, boundary pack / unpack and SiLU(gate)*up inside GEMMs
+                bch = chains.build(name, inp, shape, fused=True, flash=True, **options)
+                t_b = time_chain(bch, api.LPG_CHAIN_PROPAGATED, steps, warmup)
+                res["fused_attention_and_boundaries_ms_per_step"] = round(t_b * 1e3, 4)
+                res["fused_attention_and_boundaries_tflops"] = round(flops / t_b / 1e12, 2)
+                del bch
         res["stages"] = stage_breakdown(ch, max(3, steps // 2))
         if name == "two_gemm":
             # launch-bound: the same chain replayed from a HIP graph
