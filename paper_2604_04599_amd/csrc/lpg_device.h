@@ -291,10 +291,10 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     constexpr int FPW = NFRAG / NW;          // fragments each wave copies per stage
     constexpr int FPW_L = TLG * FS / NW;     // ... of which the first FPW_L come from L
     constexpr int STAGE = NFRAG * kFragBytes;
-    constexpr int SPB = kFragsPerBlock / FS;  // steps per K block
+    constexpr int BPS = FS > kFragsPerBlock ? FS / kFragsPerBlock : 1;  // K blocks per step
     static_assert(NFRAG % NW == 0 && (TLG * FS) % NW == 0, "stage must divide over the waves");
     static_assert(TLG % WL == 0 && TRG % WR == 0, "tile must divide over the waves");
-    static_assert(FS == 2 || FS == 4, "a step is a whole or half K block");
+    static_assert(FS == 2 || FS == 4 || FS == 8, "a step is half a K block, one, or two");
     static_assert(NS >= 2 && NS <= 5 && (NS - 2) * FPW <= 63, "ring depth limited by the vmcnt field");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     const uint32_t ntile = (uint32_t)(p.tiles_l * p.tiles_r);
     const uint32_t total = ntile * (uint32_t)p.batch;
     const uint32_t G = gridDim.x;
-    const int spt = p.nkb * SPB;  // steps per tile
+    const int spt = FS > kFragsPerBlock ? p.nkb / BPS : p.nkb * (kFragsPerBlock / FS);  // steps per tile (launcher: BPS divides nkb)
     if (blockIdx.x >= total) return;
     const uint32_t my_tiles = (total - blockIdx.x + G - 1) / G;
 
@@ -360,7 +360,8 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
             } else {
                 const char *base = is_l ? t.Lp + min(grp, t.nlg - 1) * kBlockBytes
                                         : t.Rp + max(0, min(grp - TLG, t.nrg - 1)) * kBlockBytes;
-                src[i] = base + c * kFragBytes + lane * 16;
+                // fragment c of the step: fragment c % 4 of the step's K block c / 4
+                src[i] = base + (c / kFragsPerBlock) * (is_l ? p.l_kbs : p.r_kbs) + (c % kFragsPerBlock) * kFragBytes + lane * 16;
             }
         }
     };
@@ -385,7 +386,10 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
             else aim(decode(c_vb));
         } else {             // next step of the same tile
             int64_t dl, dr;
-            if (FS == 4 || (c_s & 1) == 0) {  // first fragments of the next K block
+            if (FS >= kFragsPerBlock) {       // whole K blocks per step
+                dl = BPS * p.l_kbs;
+                dr = BPS * p.r_kbs;
+            } else if ((c_s & 1) == 0) {      // first fragments of the next K block
                 dl = p.l_kbs - (kFragsPerBlock - FS) * kFragBytes;
                 dr = p.r_kbs - (kFragsPerBlock - FS) * kFragBytes;
             } else {                          // second half of the same K block
@@ -571,12 +575,12 @@ static int workgroups_per_cu(const TileCfg &c, bool bf16)
     return occ < 1 ? 1 : occ;
 }
 
-template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR, int NS>
+template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR, int NS, int FSX = 0>
 static hipError_t launch_gemm_ring(const GemmArgs &a, int64_t grid, hipStream_t st)
 {
     constexpr int NT = WL * WR * 64;
     constexpr bool BF = IN::ES == 2;
-    constexpr int FS = ring_fs(BF);
+    constexpr int FS = FSX ? FSX : ring_fs(BF);
     constexpr size_t lds = (size_t)NS * (TLG + TRG) * FS * kFragBytes;
     static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
     auto kern = gemm_kernel<IN, OUT, TLG, TRG, WL, WR, FS, NS, BF>;
@@ -606,7 +610,19 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
     int64_t grid = (int64_t)256 * workgroups_per_cu(c, BF);
     if (grid > total) grid = total;
     if constexpr (NS_LONE != NS) {
-        if (total <= 256) return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS_LONE>(a, grid, st);
+        if (total <= 256) {
+            // Small lone tiles: a step of one K block is 2048-4096 MFMA cycles and every step ends
+            // at a workgroup barrier that costs about 290 of them (no second wave on the SIMD to
+            // fill the gap), so an even number of K blocks is walked two per step.
+            constexpr int STAGE2 = (TLG + TRG) * 8 * kFragBytes;
+            constexpr int NS2 = 4 * STAGE2 <= 160 * 1024 ? 4 : (3 * STAGE2 <= 160 * 1024 ? 3 : 2);
+            if constexpr (!BF && TLG * TRG <= 16) {
+                static const int two = [] { const char *e = getenv("LPG_TWO_BLOCK_STEPS"); return e ? atoi(e) : 1; }();
+                if (two && a.nkb % 2 == 0 && a.nkb >= 4)
+                    return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS2, 8>(a, grid, st);
+            }
+            return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS_LONE>(a, grid, st);
+        }
     }
     return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS>(a, grid, st);
 }
