@@ -278,6 +278,50 @@ __device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc,
     }
 }
 
+// The common case of store_tile, kept small: packed output, no C_in, no fused operation, a
+// tile wholly inside the logical extents.  The epilogue is instantiated once per accumulator
+// tile of the wave; with only the general form, a launch of many short tiles (attention
+// scores) spends its time fetching that code.
+template <typename OUT, bool USE_C>
+__device__ __forceinline__ void store_tile_plain(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane, char *Ob,
+                                                 const char *Cb)
+{
+    float v[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) v[e] = acc[e] * p.alpha;
+    if constexpr (OUT::ES == 4) {
+        const int64_t off = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
+#pragma unroll
+        for (int fgi = 0; fgi < 4; ++fgi) {
+            if constexpr (USE_C) {
+                const uint4 c = *(const uint4 *)(Cb + off + fgi * kFragBytes);
+                v[4 * fgi] += p.beta * __uint_as_float(c.x);
+                v[4 * fgi + 1] += p.beta * __uint_as_float(c.y);
+                v[4 * fgi + 2] += p.beta * __uint_as_float(c.z);
+                v[4 * fgi + 3] += p.beta * __uint_as_float(c.w);
+            }
+            *(uint4 *)(Ob + off + fgi * kFragBytes) =
+                make_uint4(__float_as_uint(v[4 * fgi]), __float_as_uint(v[4 * fgi + 1]),
+                           __float_as_uint(v[4 * fgi + 2]), __float_as_uint(v[4 * fgi + 3]));
+        }
+    } else {
+        const int64_t off = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes + (grR & 1) * 2 * kFragBytes + lane * 16;
+#pragma unroll
+        for (int fgi = 0; fgi < 2; ++fgi) {
+            if constexpr (USE_C) {
+                const uint4 c = *(const uint4 *)(Cb + off + fgi * kFragBytes);
+                const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[8 * fgi + j] += p.beta * bf16_to_f32((cw[j >> 1] >> (16 * (j & 1))) & 0xffff);
+            }
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = bf16_pack2(v[8 * fgi + 2 * j], v[8 * fgi + 2 * j + 1]);
+            *(uint4 *)(Ob + off + fgi * kFragBytes) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
 // XPF (needs NS >= 3): the first fragment of the NEXT step is read into registers while the
 // last fragment of the current step is multiplied, so no LDS latency is exposed after the
 // barrier; the barrier of a step then also publishes the step after it.
@@ -506,14 +550,30 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
         // ---- epilogue
         const TileInfo cur = decode(vb);
         const int64_t oslot = (int64_t)cur.b * p.o_slot;
-        static_for<WTL * WTR>([&](auto I) {
-            constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
-            const int grL = cur.gl0 + wl * WTL + a;
-            const int grR = cur.gr0 + wr * WTR + q;
-            if (grL < p.FLg && grR < p.FRg_out)
-                store_tile<OUT>(p, acc[a][q], grL, grR, lane, p.Out + oslot, p.Cin + oslot, p.Epi + oslot, use_c,
-                                use_e);
-        });
+        const bool plain = !p.o_canon && !use_e && p.epi == LPG_EPI_NONE &&
+                           (cur.gl0 + TLG) * 32 <= p.FL && (cur.gr0 + TRG) * 32 <= p.FR;
+        if (plain && !use_c) {
+            static_for<WTL * WTR>([&](auto I) {
+                constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
+                store_tile_plain<OUT, false>(p, acc[a][q], cur.gl0 + wl * WTL + a, cur.gr0 + wr * WTR + q, lane,
+                                             p.Out + oslot, nullptr);
+            });
+        } else if (plain) {
+            static_for<WTL * WTR>([&](auto I) {
+                constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
+                store_tile_plain<OUT, true>(p, acc[a][q], cur.gl0 + wl * WTL + a, cur.gr0 + wr * WTR + q, lane,
+                                            p.Out + oslot, p.Cin + oslot);
+            });
+        } else {
+            static_for<WTL * WTR>([&](auto I) {
+                constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
+                const int grL = cur.gl0 + wl * WTL + a;
+                const int grR = cur.gr0 + wr * WTR + q;
+                if (grL < p.FLg && grR < p.FRg_out)
+                    store_tile<OUT>(p, acc[a][q], grL, grR, lane, p.Out + oslot, p.Cin + oslot, p.Epi + oslot, use_c,
+                                    use_e);
+            });
+        }
     }
     wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
 }
@@ -623,6 +683,17 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
             }
             return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS_LONE>(a, grid, st);
         }
+    }
+    if constexpr (BF && TLG * TRG <= 8) {
+        // bf16, small lone tiles: a half-block step is 64-256 MFMA cycles, far less than the
+        // barrier that ends it; two whole K blocks per step (four times fewer barriers), in as
+        // many stages as the LDS holds (the next-step prefetch needs three).
+        constexpr int STAGE2 = (TLG + TRG) * 8 * kFragBytes;
+        constexpr int NS2 = 5 * STAGE2 <= 160 * 1024 ? 5 : (4 * STAGE2 <= 160 * 1024 ? 4 : 3);
+        static_assert(NS2 * STAGE2 <= 160 * 1024, "two-block stages of the small tiles fit three times");
+        static const int two = [] { const char *e = getenv("LPG_TWO_BLOCK_STEPS"); return e ? atoi(e) : 1; }();
+        if (two && total <= 256 && a.nkb % 2 == 0 && a.nkb >= 4)
+            return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS2, 8>(a, grid, st);
     }
     return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS>(a, grid, st);
 }

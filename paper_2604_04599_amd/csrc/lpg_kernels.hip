@@ -1066,7 +1066,10 @@ static double estimate_cost(const GemmArgs &a, const TileCfg &c, bool bf16)
     const int nkb = a.nkb > 0 ? a.nkb : 1;
     const double cy_block = bf16 ? 128.0 : 1024.0;  // MFMA cycles of one 32x32 tile over one K block
     const int resident = (int)((per_cu < occ ? per_cu : occ) * waves_per_simd);  // waves per SIMD
-    double eff = resident >= 2 ? 1.0 : (bf16 ? 0.6 : 1.0);
+    // one bf16 wave per SIMD stalls at every barrier of its short steps, unless the launch
+    // qualifies for two K blocks per step (launch_gemm_cfg)
+    const bool two_block = tiles <= 256 && c.tlg * c.trg <= 8 && nkb % 2 == 0 && nkb >= 4;
+    double eff = resident >= 2 ? 1.0 : (bf16 ? (two_block ? 0.9 : 0.6) : 1.0);
     const double reads_per_mma = (double)(wtl + wtr) / (wtl * wtr);
     eff /= 1.0 + (bf16 ? 0.217 : 0.0525) * reads_per_mma;
     const double mfma = (double)per_cu * (c.tlg * c.trg / 4.0) * nkb * cy_block / eff;
