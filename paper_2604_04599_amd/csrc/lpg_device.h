@@ -282,43 +282,73 @@ __device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc,
 // tile wholly inside the logical extents.  The epilogue is instantiated once per accumulator
 // tile of the wave; with only the general form, a launch of many short tiles (attention
 // scores) spends its time fetching that code.
-template <typename OUT, bool USE_C>
-__device__ __forceinline__ void store_tile_plain(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane, char *Ob,
-                                                 const char *Cb)
+// 16 bytes of a packed fragment as floats (4 fp32 or 8 bf16 elements)
+template <typename OUT>
+__device__ __forceinline__ void frag_vals(const char *ptr, float (&x)[16 / OUT::ES])
 {
-    float v[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) v[e] = acc[e] * p.alpha;
+    const uint4 t = *(const uint4 *)ptr;
+    const uint32_t w[4] = {t.x, t.y, t.z, t.w};
     if constexpr (OUT::ES == 4) {
-        const int64_t off = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
 #pragma unroll
-        for (int fgi = 0; fgi < 4; ++fgi) {
-            if constexpr (USE_C) {
-                const uint4 c = *(const uint4 *)(Cb + off + fgi * kFragBytes);
-                v[4 * fgi] += p.beta * __uint_as_float(c.x);
-                v[4 * fgi + 1] += p.beta * __uint_as_float(c.y);
-                v[4 * fgi + 2] += p.beta * __uint_as_float(c.z);
-                v[4 * fgi + 3] += p.beta * __uint_as_float(c.w);
-            }
-            *(uint4 *)(Ob + off + fgi * kFragBytes) =
-                make_uint4(__float_as_uint(v[4 * fgi]), __float_as_uint(v[4 * fgi + 1]),
-                           __float_as_uint(v[4 * fgi + 2]), __float_as_uint(v[4 * fgi + 3]));
-        }
+        for (int j = 0; j < 4; ++j) x[j] = __uint_as_float(w[j]);
     } else {
-        const int64_t off = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes + (grR & 1) * 2 * kFragBytes + lane * 16;
 #pragma unroll
-        for (int fgi = 0; fgi < 2; ++fgi) {
-            if constexpr (USE_C) {
-                const uint4 c = *(const uint4 *)(Cb + off + fgi * kFragBytes);
-                const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+        for (int j = 0; j < 8; ++j) x[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
+    }
+}
+
+template <typename OUT, bool USE_C, int EPI>
+__device__ __forceinline__ void store_tile_plain(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane, char *Ob,
+                                                 const char *Cb, const char *Eb)
+{
+    constexpr int NF = (OUT::ES == 4) ? 4 : 2, PER = 16 / NF;
+    int64_t off;
+    if constexpr (OUT::ES == 4) off = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
+    else off = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes + (grR & 1) * 2 * kFragBytes + lane * 16;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[8 * fgi + j] += p.beta * bf16_to_f32((cw[j >> 1] >> (16 * (j & 1))) & 0xffff);
-            }
-            uint32_t w[4];
+    for (int fgi = 0; fgi < NF; ++fgi) {
+        float v[PER];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) w[j] = bf16_pack2(v[8 * fgi + 2 * j], v[8 * fgi + 2 * j + 1]);
-            *(uint4 *)(Ob + off + fgi * kFragBytes) = make_uint4(w[0], w[1], w[2], w[3]);
+        for (int j = 0; j < PER; ++j) v[j] = acc[fgi * PER + j] * p.alpha;
+        if constexpr (USE_C) {
+            float c[PER];
+            frag_vals<OUT>(Cb + off + fgi * kFragBytes, c);
+#pragma unroll
+            for (int j = 0; j < PER; ++j) v[j] += p.beta * c[j];
         }
+        if constexpr (EPI == LPG_EPI_SILU) {
+#pragma unroll
+            for (int j = 0; j < PER; ++j) v[j] = silu_f(v[j]);
+        } else if constexpr (EPI == LPG_EPI_GATE_SILU) {
+            float g[PER];
+            frag_vals<OUT>(Eb + off + fgi * kFragBytes, g);
+#pragma unroll
+            for (int j = 0; j < PER; ++j) v[j] = silu_f(g[j]) * v[j];
+        }
+        if constexpr (OUT::ES == 4) {
+            *(uint4 *)(Ob + off + fgi * kFragBytes) =
+                make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+        } else {
+            *(uint4 *)(Ob + off + fgi * kFragBytes) = make_uint4(bf16_pack2(v[0], v[1]), bf16_pack2(v[2], v[3]),
+                                                                  bf16_pack2(v[4], v[5]), bf16_pack2(v[6], v[7]));
+        }
+    }
+}
+
+// The same for a row- or column-major output (Ending kernel), interior tiles, no C_in, no
+// fused operation: lanes run along out's free index, so for each register the 32 lanes of a
+// half wave write one contiguous run.
+template <typename OUT>
+__device__ __forceinline__ void store_tile_canon_plain(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane, char *Ob)
+{
+    const int h = lane >> 5;
+    char *o = Ob + (int64_t)(grL * 32 + (lane & 31)) * p.o_sf + (int64_t)(grR * 32 + 4 * h) * p.o_sk;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        char *dst = o + (int64_t)(8 * (e >> 2) + (e & 3)) * p.o_sk;
+        const float x = acc[e] * p.alpha;
+        if constexpr (OUT::ES == 4) *(float *)dst = x;
+        else *(uint16_t *)dst = (uint16_t)bf16_rne(x);
     }
 }
 
@@ -550,20 +580,33 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
         // ---- epilogue
         const TileInfo cur = decode(vb);
         const int64_t oslot = (int64_t)cur.b * p.o_slot;
-        const bool plain = !p.o_canon && !use_e && p.epi == LPG_EPI_NONE &&
-                           (cur.gl0 + TLG) * 32 <= p.FL && (cur.gr0 + TRG) * 32 <= p.FR;
-        if (plain && !use_c) {
-            static_for<WTL * WTR>([&](auto I) {
-                constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
-                store_tile_plain<OUT, false>(p, acc[a][q], cur.gl0 + wl * WTL + a, cur.gr0 + wr * WTR + q, lane,
-                                             p.Out + oslot, nullptr);
-            });
-        } else if (plain) {
-            static_for<WTL * WTR>([&](auto I) {
-                constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
-                store_tile_plain<OUT, true>(p, acc[a][q], cur.gl0 + wl * WTL + a, cur.gr0 + wr * WTR + q, lane,
-                                            p.Out + oslot, p.Cin + oslot);
-            });
+        // compact forms for tiles wholly inside the logical extents; 0: general form
+        const bool interior = (cur.gl0 + TLG) * 32 <= p.FL && (cur.gr0 + TRG) * 32 <= p.FR;
+        int form = 0;
+        if (interior && !p.o_canon) {
+            if (p.epi == LPG_EPI_NONE) form = use_c ? 2 : 1;
+            else if (!use_c) form = (p.epi == LPG_EPI_SILU) ? 3 : (use_e ? 4 : 0);
+        } else if (interior && !use_c && p.epi == LPG_EPI_NONE) {
+            form = 5;
+        }
+#define LPG_EPILOGUE_FORM(CALL)                                                                    \
+    static_for<WTL * WTR>([&](auto I) {                                                            \
+        constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;                  \
+        const int grL = cur.gl0 + wl * WTL + a, grR = cur.gr0 + wr * WTR + q;                      \
+        CALL;                                                                                      \
+    })
+        char *Oo = p.Out + oslot;
+        if (form == 1) {
+            LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_NONE>(p, acc[a][q], grL, grR, lane, Oo, nullptr, nullptr)));
+        } else if (form == 2) {
+            LPG_EPILOGUE_FORM((store_tile_plain<OUT, true, LPG_EPI_NONE>(p, acc[a][q], grL, grR, lane, Oo, p.Cin + oslot, nullptr)));
+        } else if (form == 3) {
+            LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_SILU>(p, acc[a][q], grL, grR, lane, Oo, nullptr, nullptr)));
+        } else if (form == 4) {
+            LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_GATE_SILU>(p, acc[a][q], grL, grR, lane, Oo, nullptr, p.Epi + oslot)));
+        } else if (form == 5) {
+            LPG_EPILOGUE_FORM((store_tile_canon_plain<OUT>(p, acc[a][q], grL, grR, lane, Oo)));
+#undef LPG_EPILOGUE_FORM
         } else {
             static_for<WTL * WTR>([&](auto I) {
                 constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
