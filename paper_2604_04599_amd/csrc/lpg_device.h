@@ -686,7 +686,7 @@ static hipError_t launch_gemm_ring(const GemmArgs &a, int64_t grid, hipStream_t 
     constexpr int FS = FSX ? FSX : ring_fs(BF);
     constexpr size_t lds = (size_t)NS * (TLG + TRG) * FS * kFragBytes;
     static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
-    auto kern = gemm_kernel<IN, OUT, TLG, TRG, WL, WR, FS, NS, BF>;
+    auto kern = gemm_kernel<IN, OUT, TLG, TRG, WL, WR, FS, NS, (BF && NS >= 3)>;
     if (lds > 64 * 1024) {
         static bool done = false;  // per instantiation
         if (!done) {
@@ -737,6 +737,15 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
         static const int two = [] { const char *e = getenv("LPG_TWO_BLOCK_STEPS"); return e ? atoi(e) : 1; }();
         if (two && total <= 256 && a.nkb % 2 == 0 && a.nkb >= 4)
             return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS2, 8>(a, grid, st);
+    }
+    if constexpr (BF && TLG * TRG >= 8 && TLG * TRG <= 16 && WL * WR == 4) {
+        // bf16 tiles of 128 x 64 to 128 x 128 (several workgroups per compute unit): whole K
+        // blocks per step in two stages, without the next-step prefetch, instead of half blocks
+        // in four stages with it: half the barriers in the same LDS; measured 2-8 % faster on
+        // 2048^3, 4096 x 2048 x 2048, 16384 x 1024 x 1024 and ragged shapes.  LPG_BF16_FS4=0
+        // restores the half-block ring (tuning aid).
+        static const int fs4 = [] { const char *e = getenv("LPG_BF16_FS4"); return e ? atoi(e) : 1; }();
+        if (fs4) return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, 2, 4>(a, grid, st);
     }
     return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS>(a, grid, st);
 }
