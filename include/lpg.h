@@ -16,6 +16,12 @@
  *   - Return value: LPG_OK (0) or a negative lpg_status.  Errors are detected on
  *     the host before anything is launched; lpg_last_error() gives a message.
  *   - Packed buffers must be 16-byte aligned (LPG_EALIGN otherwise).
+ *   - Sizes: rows and cols up to 2^31-1 each (LPG_EINVAL past that); every byte
+ *     offset is formed in 64 bits, so buffers, slots and leading dimensions may
+ *     pass 4 GiB.  A request whose launch would exceed the device's grid limits
+ *     (lpg_pack / lpg_unpack: more than 65535 batches or K blocks; any call: more
+ *     than 2^31-1 workgroups or output tiles) returns LPG_EUNSUPPORTED or LPG_EHIP
+ *     and launches nothing.
  *
  * The packed layout P(X; F, K) (this library's re-design, for 64-lane MFMA
  * operand registers, of the tile order of Eq. 3).  X has a free dimension F and

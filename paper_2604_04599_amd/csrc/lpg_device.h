@@ -708,7 +708,7 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
     a.tiles_r = (a.FRg_out + TRG - 1) / TRG;
     const int64_t total = (int64_t)a.tiles_l * a.tiles_r * a.batch;
     if (total <= 0) return hipSuccess;
-    if (total > 0x7fffffff) return hipErrorInvalidValue;
+    if (total > 0x7fffffff) return hipErrorInvalidValue;  // the kernel counts tiles in 32 bits
     const TileCfg c = {TLG, TRG, WL, WR};
     int64_t grid = (int64_t)256 * workgroups_per_cu(c, BF);
     if (grid > total) grid = total;

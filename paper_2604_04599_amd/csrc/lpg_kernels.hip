@@ -10,6 +10,9 @@
 
 namespace lpg {
 
+// Launch limits of HIP: a request past them is reported, never narrowed.
+constexpr int64_t kMaxGridX = 0x7fffffff, kMaxGridYZ = 65535;
+
 // ---------------------------------------------------------------------------------
 // pack / unpack.  A workgroup of 256 threads moves whole blocks (32 f x KB k), KPW
 // consecutive K blocks of one 32-group per workgroup.
@@ -177,6 +180,7 @@ static hipError_t launch_pack_impl(PackArgs a, int cdt, int pdt, hipStream_t st)
 {
     if (a.ngroups <= 0 || a.nkb <= 0 || a.batch <= 0) return hipSuccess;
     a.kpw = a.nkb >= 16 ? 4 : 1;
+    if ((a.nkb + a.kpw - 1) / a.kpw > kMaxGridYZ || a.batch > kMaxGridYZ) return hipErrorInvalidConfiguration;
     dim3 grid(a.ngroups, (a.nkb + a.kpw - 1) / a.kpw, a.batch), block(256);
     const bool kc = (a.sk == 1);
     // vector path: every PER-element run of the canonical side starts on a 16-byte boundary
@@ -575,6 +579,7 @@ static hipError_t launch_row_dtype(const RowArgs &a, bool packed, hipStream_t st
 {
     if (!packed) {
         const int64_t grid = (int64_t)a.batch * a.rows;
+        if (grid > kMaxGridX) return hipErrorInvalidConfiguration;
         const bool vec = ((uintptr_t)a.x | (uintptr_t)a.out | (uint64_t)a.row_stride | (uint64_t)a.slot |
                           (uint64_t)((int64_t)a.cols * T::ES)) % 16 == 0;
         if (vec)
@@ -600,6 +605,7 @@ static hipError_t launch_row_dtype(const RowArgs &a, bool packed, hipStream_t st
         const int v = atoi(f);
         if (v >= 0 && v < 6 && fits(v)) variant = v;
     }
+    if ((int64_t)a.batch * a.ngroups * (32 / kVariants[variant].r) > kMaxGridX) return hipErrorInvalidConfiguration;
     const unsigned grid = (unsigned)((int64_t)a.batch * a.ngroups * (32 / kVariants[variant].r));
     const dim3 block(kVariants[variant].nw * 64);
     switch (variant) {
@@ -641,6 +647,7 @@ hipError_t launch_rope_tables(float *cos_t, float *sin_t, int64_t rows, int head
 {
     const int64_t n = rows * (head_dim / 2);
     if (n <= 0) return hipSuccess;
+    if ((n + 255) / 256 > kMaxGridX) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(rope_tables_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, cos_t, sin_t, n,
                        head_dim / 2, base, pos0);
     return hipGetLastError();
@@ -1017,6 +1024,7 @@ static hipError_t launch_attention_dh(const AttnArgs &a, hipStream_t st)
     }
     const int nqb = (a.q_groups + 4 * QG - 1) / (4 * QG);
     const int64_t grid = (int64_t)(a.causal ? (nqb + 1) / 2 : nqb) * a.batch;  // causal: query blocks in pairs
+    if (grid > kMaxGridX) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a);
     return hipGetLastError();
 }

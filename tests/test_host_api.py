@@ -162,6 +162,10 @@ def test_descriptor_errors_are_caught_on_the_host():
     assert _err(api.lpg_rope_tables, fake, fake, 8, 7, 10000.0, 0) == api.LPG_EINVAL
     assert _err(api.lpg_rope_tables, fake, fake, 8, 8, -1.0, 0) == api.LPG_EINVAL
     assert _err(api.lpg_rope_tables, None, fake, 8, 8, 10000.0, 0) == api.LPG_EINVAL
+    # a batch the pack kernel's grid cannot hold is reported, not narrowed
+    many = 70000
+    assert _err(api.lpg_pack, fake, desc(LPG_ROW_MAJOR, LPG_F32, 32, 32, batch=many, batch_stride=1024), fake,
+                desc(LPG_PACKED_A, LPG_F32, 32, 32, batch=many, batch_stride=1024)) == api.LPG_EUNSUPPORTED
     # fused attention: roles, head_dim, shapes, dtype, aliasing
     qd, kd, vd = desc(LPG_PACKED_A, LPG_F32, 96, 64), desc(LPG_PACKED_A, LPG_F32, 80, 64), desc(LPG_PACKED_B, LPG_F32, 80, 64)
     od = desc(LPG_PACKED_A, LPG_F32, 96, 64)
