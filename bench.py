@@ -268,12 +268,20 @@ SWEEP_CHAINS = [(256, (512, 512, 512, 512)), (1024, (1024, 4096, 1024, 256)), (1
                 (8192, (1024, 1024, 1024, 1024)), (1000, (1000, 3000, 1000, 300))]
 
 
-def _time_calls(fn, reps):
+def _time_calls(fn, reps, min_seconds=0.03):
+    """Seconds per call.  Small cases get more than `reps` calls: a measurement shorter than some
+    tens of milliseconds sees the clocks of an idle device, not those of a loaded one."""
     import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
     for _ in range(2):
         fn()
+    e1.record()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    per_call = max(e0.elapsed_time(e1) * 1e-3 / 2, 1e-6)
+    reps = max(reps, min(2000, int(min_seconds / per_call)))
+    for _ in range(reps // 2):
+        fn()
     e0.record()
     for _ in range(reps):
         fn()
@@ -326,8 +334,10 @@ def sweep(reps):
         ws = [rng.standard_normal((a, b), dtype=np.float32) / np.float32(np.sqrt(a)) for a, b in zip(widths, widths[1:])]
         ch = chains.build_linear_chain(x, ws)
         fch = chains.build_linear_chain(x, ws, fused=True)
-        tp, tc = compare_modes(ch, 6 * reps)
-        tf = time_chain(fch, api.LPG_CHAIN_PROPAGATED, reps, 2)
+        est = max(time_chain(ch, api.LPG_CHAIN_PROPAGATED, 3, 2), 1e-6)
+        steps = max(6 * reps, min(6000, int(0.15 / est)))          # long enough for loaded clocks
+        tp, tc = compare_modes(ch, steps)
+        tf = time_chain(fch, api.LPG_CHAIN_PROPAGATED, max(reps, steps // 6), 2)
         print(json.dumps({"sweep": "chain3_f32", "m": m, "widths": list(widths),
                           "propagated_ms": round(tp * 1e3, 4), "canonical_ms": round(tc * 1e3, 4),
                           "fused_boundaries_ms": round(tf * 1e3, 4), "speedup_vs_canonical": round(tc / tp, 3),
