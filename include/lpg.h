@@ -77,25 +77,33 @@ typedef enum {
  * parent_rows/cols    extent of the parent this view lives in (0,0 = the view is
  *                     the whole parent).  For packed kinds the parent fixes the
  *                     padded geometry (block strides).
- * row0, col0          origin of the view inside the parent.  Packed kinds: the
- *                     free-dimension origin must be a multiple of 32 and the
- *                     contraction-dimension origin a multiple of KB.  A view
- *                     extent that is not such a multiple either ends at the
- *                     parent's edge (its padding is then the parent's own zero
- *                     padding; every entry point takes this) or ends inside the
- *                     parent, sharing its last block with the parent's other
- *                     elements.  The second form is taken by lpg_pack (destination),
- *                     lpg_unpack (source) and by C / C_in / epi_arg of lpg_gemm_packed
- *                     in both dimensions: writes then touch the view's own elements
- *                     only, as if the rectangle had been replaced in the canonical
- *                     parent; and by A and B of lpg_gemm_packed in their free
- *                     dimension only (a ragged contraction extent inside a parent
- *                     would add the neighbours to every sum: LPG_EALIGN).  Batched
- *                     views with a per-slot origin step and the row, elementwise
- *                     and attention entry points need the first form.  This is the
- *                     restricted form of the paper's "store stride / block order"
- *                     parameters (section III-C) that per-head slices of Q, K, V, O
- *                     (section IV-A) and appends to a growing operand need.
+ * row0, col0          origin of the view inside the parent.  Packed kinds: read
+ *                     views (A and B of lpg_gemm_packed, the row, elementwise and
+ *                     attention entry points) and batched views with a per-slot
+ *                     origin step need the free-dimension origin to be a multiple
+ *                     of 32 and the contraction-dimension origin a multiple of KB
+ *                     (LPG_EALIGN otherwise).  A view extent that is not such a
+ *                     multiple either ends at the parent's edge (its padding is then
+ *                     the parent's own zero padding; every entry point takes this)
+ *                     or ends inside the parent, sharing its last block with the
+ *                     parent's other elements; that second form is taken by A and
+ *                     B of lpg_gemm_packed in their free dimension only (a ragged
+ *                     contraction extent inside a parent would add the neighbours
+ *                     to every sum: LPG_EALIGN).
+ *                     WRITTEN views - the destination of lpg_pack, the source of
+ *                     lpg_unpack, and C / C_in / epi_arg of lpg_gemm_packed - may
+ *                     have any origin and any extent inside the parent: the call
+ *                     touches the view's own elements only, as if the rectangle had
+ *                     been replaced in the canonical parent and the parent packed
+ *                     again.  With an origin on the 32 / KB grid whole 16-byte lane
+ *                     vectors are moved (edge blocks element by element); with an
+ *                     origin off the grid every element is addressed by itself and
+ *                     the parent's padding is never written, so the parent must
+ *                     have been zero-filled or packed once before.  This is the
+ *                     general form of the paper's "store stride / block order"
+ *                     parameters (section III-C): per-head slices of Q, K, V, O
+ *                     (section IV-A), and appends of any number of rows or columns
+ *                     at any position of a growing operand (a key / value cache).
  * batch               number of matrices (0 is read as 1).
  * batch_div           matrix b uses slot b / batch_div (0 is read as 1); lets
  *                     several query heads share one key/value head instead of

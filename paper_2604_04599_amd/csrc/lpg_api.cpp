@@ -49,8 +49,10 @@ static inline int nslots(const lpg_desc *d) { return (nbatch(d) + bdiv(d) - 1) /
 // at the parent's edge, where its padding is the parent's own.  `inner` names the dimensions
 // in which the caller can also take a ragged extent that ends inside the parent: the view's
 // last block is then shared with neighbouring elements of the parent, keep_f / keep_k are set,
-// and a writer must leave those neighbours alone.
-enum { kInnerF = 1, kInnerK = 2 };
+// and a writer must leave those neighbours alone.  kOffGrid: the caller also takes an origin
+// that is not a multiple of 32 / KB (f_off / k_off are then non-zero, the origin points at the
+// block that holds the first element, and nothing outside the view may be written).
+enum { kInnerF = 1, kInnerK = 2, kOffGrid = 4 };
 static int make_pview(const lpg_desc *d, const char *what, PView *v, unsigned inner = 0)
 {
     int rc = check_common(d, what);
@@ -77,9 +79,12 @@ static int make_pview(const lpg_desc *d, const char *what, PView *v, unsigned in
     v->PFp = round_up(v->PF, 32);
     v->PKp = round_up(v->PK, KB);
     const int ns = nslots(d);
-    if (v->f0 % 32 || v->fstep % 32)
+    v->f_off = (int)(v->f0 % 32);
+    v->k_off = (int)(v->k0 % KB);
+    const bool off_grid = v->f_off || v->k_off;
+    if ((v->f_off && !(inner & kOffGrid)) || v->fstep % 32)
         return fail(LPG_EALIGN, "%s: free-dimension origin/step must be a multiple of 32", what);
-    if (v->k0 % KB || v->kstep % KB)
+    if ((v->k_off && !(inner & kOffGrid)) || v->kstep % KB)
         return fail(LPG_EALIGN, "%s: contraction-dimension origin/step must be a multiple of %d", what, (int)KB);
     const int64_t f_last = v->f0 + (ns - 1) * v->fstep, k_last = v->k0 + (ns - 1) * v->kstep;
     if (f_last + v->F > v->PF || k_last + v->K > v->PK)
@@ -89,8 +94,8 @@ static int make_pview(const lpg_desc *d, const char *what, PView *v, unsigned in
         return fail(LPG_EALIGN, "%s: stepped views need a free extent that is a multiple of 32", what);
     if (v->K % KB && (ns > 1 ? v->kstep != 0 : false))
         return fail(LPG_EALIGN, "%s: stepped views need a contraction extent that is a multiple of %d", what, (int)KB);
-    v->keep_f = v->F % 32 && v->f0 + v->F != v->PF;
-    v->keep_k = v->K % KB && v->k0 + v->K != v->PK;
+    v->keep_f = !off_grid && v->F % 32 && v->f0 + v->F != v->PF;
+    v->keep_k = !off_grid && v->K % KB && v->k0 + v->K != v->PK;
     if (v->keep_f && !(inner & kInnerF))
         return fail(LPG_EALIGN, "%s: a free extent that is not a multiple of 32 must end at the parent's edge", what);
     if (v->keep_k && !(inner & kInnerK))
@@ -170,7 +175,7 @@ static int do_pack_unpack(bool pack, const void *canon, const lpg_desc *cd, cons
     const char *name = pack ? "lpg_pack" : "lpg_unpack";
     PView pv;
     CView cv;
-    int rc = make_pview(pd, pack ? "lpg_pack dst" : "lpg_unpack src", &pv, kInnerF | kInnerK);
+    int rc = make_pview(pd, pack ? "lpg_pack dst" : "lpg_unpack src", &pv, kInnerF | kInnerK | kOffGrid);
     if (rc) return rc;
     rc = make_cview(cd, pack ? "lpg_pack src" : "lpg_unpack dst", &cv);
     if (rc) return rc;
@@ -198,12 +203,15 @@ static int do_pack_unpack(bool pack, const void *canon, const lpg_desc *cd, cons
     a.p_div = pv.bdiv;
     a.F = (int32_t)pv.F;
     a.K = (int32_t)pv.K;
-    a.ngroups = (int32_t)((pv.F + 31) / 32);
-    a.nkb = (int32_t)((pv.K + kb_of(pv.dtype) - 1) / kb_of(pv.dtype));
+    // blocks the view touches, counted from the block that holds its origin
+    a.ngroups = (int32_t)((pv.f_off + pv.F + 31) / 32);
+    a.nkb = (int32_t)((pv.k_off + pv.K + kb_of(pv.dtype) - 1) / kb_of(pv.dtype));
     a.batch = pv.batch;
     a.kpw = 1;
     a.keep_f = pv.keep_f;
     a.keep_k = pv.keep_k;
+    a.f_off = pv.f_off;
+    a.k_off = pv.k_off;
     if (a.nkb > 65535 || a.batch > 65535) return fail(LPG_EUNSUPPORTED, "%s: more than 65535 K blocks or batches", name);
     hipError_t e = pack ? launch_pack(a, cv.dtype, pv.dtype, st) : launch_unpack(a, pv.dtype, cv.dtype, st);
     if (e != hipSuccess) return fail(LPG_EHIP, "%s: %s", name, hipGetErrorString(e));
@@ -274,7 +282,7 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     const bool c_canon = is_canon(c_d->kind);
     PView cv{};
     CView ccv{};
-    rc = c_canon ? make_cview(c_d, "lpg_gemm_packed C", &ccv) : make_pview(c_d, "lpg_gemm_packed C", &cv, kInnerF | kInnerK);
+    rc = c_canon ? make_cview(c_d, "lpg_gemm_packed C", &ccv) : make_pview(c_d, "lpg_gemm_packed C", &cv, kInnerF | kInnerK | kOffGrid);
     if (rc) return rc;
     const int c_dtype = c_d->dtype, c_batch = nbatch(c_d);
     if (ao.K != bo.K)
@@ -310,6 +318,7 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     const Operand &R = l_is_a ? bo : ao;
     GemmArgs g;
     g.o_keep_l = g.o_keep_r = 0;
+    g.o_foff = g.o_koff = 0;
     g.L = (const char *)(l_is_a ? A : B) + L.origin;
     g.R = (const char *)(l_is_a ? B : A) + R.origin;
     g.l_canon = L.canon;
@@ -342,6 +351,14 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
         g.FRg_out = (int32_t)(round_up(R.F, kb_of(c_dtype)) / 32);
         g.o_keep_l = cv.keep_f;
         g.o_keep_r = cv.keep_k;
+        if (cv.f_off || cv.k_off) {
+            // origin off the grid: element-wise stores at shifted packed positions, nothing
+            // outside the view (padding included) is written
+            g.o_canon = 2;
+            g.o_foff = cv.f_off;
+            g.o_koff = cv.k_off;
+            g.FRg_out = (int32_t)((R.F + 31) / 32);
+        }
     }
     g.Cin = (beta != 0.0f) ? (const char *)C_in + c_origin : nullptr;
     g.Epi = epi_arg ? (const char *)epi_arg + c_origin : nullptr;
@@ -671,7 +688,7 @@ static int validate_stage(const lpg_stage &s, int i)
             PView pv;
             CView cv;
             const bool pk = s.type == LPG_STAGE_PACK;
-            int rc = make_pview(pk ? &s.out_d : &s.in0_d, "lpg_chain pack/unpack", &pv, kInnerF | kInnerK);
+            int rc = make_pview(pk ? &s.out_d : &s.in0_d, "lpg_chain pack/unpack", &pv, kInnerF | kInnerK | kOffGrid);
             if (rc) return rc;
             rc = make_cview(pk ? &s.in0_d : &s.out_d, "lpg_chain pack/unpack", &cv);
             if (rc) return rc;
@@ -908,9 +925,10 @@ int lpg_layout_offset(const lpg_desc *d, int64_t b, int64_t row, int64_t col, in
         return LPG_OK;
     }
     PView v;
-    rc = make_pview(d, "lpg_layout_offset", &v, kInnerF | kInnerK);
+    rc = make_pview(d, "lpg_layout_offset", &v, kInnerF | kInnerK | kOffGrid);
     if (rc) return rc;
-    const int64_t f = v.transposed ? col : row, k = v.transposed ? row : col;
+    // v.origin is the block that holds the view's first element
+    const int64_t f = (v.transposed ? col : row) + v.f_off, k = (v.transposed ? row : col) + v.k_off;
     const int64_t KB = kb_of(v.dtype), KV = 16 / v.es, KF = 2 * KV;
     const int64_t kin = k % KB, c = kin / KF, r = kin % KF;
     const int64_t h = (r >> 2) & 1, vv = 4 * (r >> 3) + (r & 3);

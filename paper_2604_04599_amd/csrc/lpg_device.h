@@ -177,12 +177,23 @@ __device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc,
     }
     if (p.o_canon) {
         // Ending kernel: straight to row/column-major.  Lanes run along out's free index, so
-        // for each register the 32 lanes of a half wave write one contiguous run.
+        // for each register the 32 lanes of a half wave write one contiguous run.  The same
+        // element-by-element walk serves a packed out whose origin is off the grid.
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
             if (fl >= p.FL || fr >= p.FR) continue;
-            const int64_t off = (int64_t)fl * p.o_sf + (int64_t)fr * p.o_sk;
+            int64_t off;
+            if (p.o_canon == 2) {
+                // packed out with its origin off the grid: the element's own position in the
+                // parent's blocks, o_foff / o_koff further along than in an aligned view
+                const int fp = fl + p.o_foff, kp = fr + p.o_koff;
+                const int kin = kp % OUT::KB, r = kin % OUT::KF;
+                off = (int64_t)(kp / OUT::KB) * p.o_kbs + (int64_t)(fp >> 5) * kBlockBytes + (kin / OUT::KF) * kFragBytes +
+                      (((r >> 2) & 1) * 32 + (fp & 31)) * 16 + (4 * (r >> 3) + (r & 3)) * OUT::ES;
+            } else {
+                off = (int64_t)fl * p.o_sf + (int64_t)fr * p.o_sk;
+            }
             float x = v[e];
             if (use_c) {
                 if constexpr (OUT::ES == 4) x += p.beta * *(const float *)(Cb + off);
@@ -586,7 +597,7 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
         if (interior && !p.o_canon) {
             if (p.epi == LPG_EPI_NONE) form = use_c ? 2 : 1;
             else if (!use_c) form = (p.epi == LPG_EPI_SILU) ? 3 : (use_e ? 4 : 0);
-        } else if (interior && !use_c && p.epi == LPG_EPI_NONE) {
+        } else if (p.o_canon == 1 && interior && !use_c && p.epi == LPG_EPI_NONE) {
             form = 5;
         }
 #define LPG_EPILOGUE_FORM(CALL)                                                                    \

@@ -34,6 +34,7 @@ struct PView {
     int64_t slot_step;     // bytes added per slot
     bool transposed;       // kind == PACKED_B (free = cols)
     bool keep_f, keep_k;   // ragged extent ending inside the parent: its last block is shared
+    int f_off, k_off;      // origin's distance from the 32 / KB grid (origin points at the block that holds it)
 };
 
 // A canonical descriptor reduced to strides over (free, contraction) indices.
@@ -60,6 +61,7 @@ struct PackArgs {
     int32_t batch;
     int32_t kpw;         // K blocks per workgroup (set by the launcher)
     int32_t keep_f, keep_k;  // pack: leave packed elements past F / past K untouched
+    int32_t f_off, k_off;    // view origin inside its first block (off the 32 / KB grid when non-zero)
 };
 
 struct GemmArgs {
@@ -86,6 +88,9 @@ struct GemmArgs {
     int32_t epi;
     float alpha, beta;
     int32_t o_keep_l, o_keep_r;      // packed out: leave elements past FL / past FR untouched
+    // o_canon == 2: packed out whose origin is off the 32 / KB grid; Out points at the block holding
+    // the origin, the view starts o_foff free indices and o_koff contraction indices into it
+    int32_t o_foff, o_koff;
 };
 
 struct EwArgs {

@@ -175,10 +175,48 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs a)
     }
 }
 
+// The same move for a view whose origin is off the 32 / KB grid (a.f_off / a.k_off into the
+// block a.packed points at).  The canonical run that feeds one 16-byte lane vector is then
+// neither aligned nor whole, so every element goes by itself: thread t owns the 16 packed
+// bytes at t*16 of a block, maps each of its KV elements back to the view's (f, k) and moves
+// it if it lies inside.  Nothing outside the view is written, padding included.
+template <bool PACK, typename C, typename P>
+__global__ __launch_bounds__(256) void pack_offgrid_kernel(PackArgs a)
+{
+    typedef typename C::raw craw;
+    typedef typename P::raw praw;
+    constexpr int KV = P::KV, KF = P::KF, KB = P::KB;
+    const int g = blockIdx.x, kb = blockIdx.y, b = blockIdx.z;
+    const int t = threadIdx.x;
+    craw *canon = (craw *)(a.canon + (int64_t)(b / a.c_div) * a.c_slot);
+    praw *pvec = (praw *)(a.packed + (int64_t)(b / a.p_div) * a.p_slot + (int64_t)g * kBlockBytes +
+                          (int64_t)kb * a.p_kbs + t * 16);
+    const int c = t >> 6, lane = t & 63, h = lane >> 5, fl = lane & 31;
+    const int64_t f = (int64_t)g * 32 + fl - a.f_off;
+    if (f < 0 || f >= a.F) return;
+#pragma unroll
+    for (int v = 0; v < KV; ++v) {
+        const int64_t k = (int64_t)kb * KB + KF * c + 8 * (v >> 2) + 4 * h + (v & 3) - a.k_off;
+        if (k < 0 || k >= a.K) continue;
+        craw *ce = canon + f * a.sf + k * a.sk;
+        if constexpr (PACK) pvec[v] = convert_raw<C, P>(*ce);
+        else *ce = convert_raw<P, C>(pvec[v]);
+    }
+}
+
 template <bool PACK>
 static hipError_t launch_pack_impl(PackArgs a, int cdt, int pdt, hipStream_t st)
 {
     if (a.ngroups <= 0 || a.nkb <= 0 || a.batch <= 0) return hipSuccess;
+    if (a.f_off || a.k_off) {
+        if (a.nkb > kMaxGridYZ || a.batch > kMaxGridYZ) return hipErrorInvalidConfiguration;
+        const dim3 grid(a.ngroups, a.nkb, a.batch), block(256);
+        if (cdt == LPG_F32 && pdt == LPG_F32) hipLaunchKernelGGL((pack_offgrid_kernel<PACK, F32, F32>), grid, block, 0, st, a);
+        else if (cdt == LPG_BF16 && pdt == LPG_BF16) hipLaunchKernelGGL((pack_offgrid_kernel<PACK, BF16, BF16>), grid, block, 0, st, a);
+        else if (cdt == LPG_F32 && pdt == LPG_BF16) hipLaunchKernelGGL((pack_offgrid_kernel<PACK, F32, BF16>), grid, block, 0, st, a);
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
     a.kpw = a.nkb >= 16 ? 4 : 1;
     if ((a.nkb + a.kpw - 1) / a.kpw > kMaxGridYZ || a.batch > kMaxGridYZ) return hipErrorInvalidConfiguration;
     dim3 grid(a.ngroups, (a.nkb + a.kpw - 1) / a.kpw, a.batch), block(256);

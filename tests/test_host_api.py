@@ -114,9 +114,16 @@ def test_descriptor_errors_are_caught_on_the_host():
                 desc(LPG_PACKED_A, LPG_BF16, 64, 64)) == api.LPG_EUNSUPPORTED
     assert _err(api.lpg_gemm_packed, 1.0, fake, pa, fake, pb, 1.0, None, 2 * fake, pa) == api.LPG_EINVAL
     assert _err(api.lpg_gemm_packed, 1.0, fake, pa, 2 * fake, pb, 0.0, None, fake, pa) == api.LPG_EINVAL
-    # views: misaligned origin, ragged extent away from the edge
-    bad = desc(LPG_PACKED_A, LPG_F32, 32, 32, parent=(64, 64), origin=(16, 0))
-    assert _err(api.lpg_pack, fake, desc(LPG_ROW_MAJOR, LPG_F32, 32, 32), fake, bad) == api.LPG_EALIGN
+    # views: an origin off the 32 / KB grid is for written views only (pack destination, unpack
+    # source, GEMM C); inputs of a product, row operations and stepped batches refuse it
+    bad = desc(LPG_PACKED_A, LPG_F32, 32, 64, parent=(64, 64), origin=(16, 0))
+    assert _err(api.lpg_gemm_packed, 1.0, fake, bad, fake, pb, 0.0, None, 2 * fake,
+                desc(LPG_PACKED_A, LPG_F32, 32, 64)) == api.LPG_EALIGN
+    bad_k = desc(LPG_PACKED_B, LPG_F32, 64, 64, parent=(64, 96), origin=(0, 8))
+    assert _err(api.lpg_gemm_packed, 1.0, fake, pa, fake, bad_k, 0.0, None, 2 * fake, pa) == api.LPG_EALIGN
+    assert _err(api.lpg_softmax_packed, fake, fake, bad, 1.0, False) == api.LPG_EALIGN
+    assert _err(api.lpg_pack, fake, desc(LPG_ROW_MAJOR, LPG_F32, 32, 32, batch=2, batch_stride=1024), fake,
+                desc(LPG_PACKED_A, LPG_F32, 32, 32, parent=(128, 64), origin=(8, 0), batch=2, batch_step=(40, 0))) == api.LPG_EALIGN
     # a ragged extent that ends inside the parent: refused where neighbours would be read into
     # a sum (contraction extent of a GEMM input) and by the row, elementwise, attention calls
     inner_k = desc(LPG_PACKED_A, LPG_F32, 64, 20, parent=(64, 64), origin=(0, 0))
