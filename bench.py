@@ -23,9 +23,9 @@ import numpy as np
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6}     # dense MFMA, MI355X (256 CU x 2.4 GHz)
 # HBM bytes per fp32 GEMM launch of the headline chain, from profiles/hbm_traffic_mlp_chain.txt:
-# FETCH_SIZE (x2.0 calibration) 80.3 and 168.3 MiB, WRITE_SIZE (x1.0) 32 and 8 MiB for the two
-# launches of a step -> mean 144.3 MiB; the algorithmic bytes are 56 and 64 MiB.
-GEMM_TRAFFIC_BYTES = 144.3 * 2 ** 20
+# FETCH_SIZE (x2.0 calibration) 64.3 and 136.3 MiB, WRITE_SIZE (x1.0) 32 and 8 MiB for the two
+# launches of a step -> mean 120.3 MiB; the algorithmic bytes are 56 and 64 MiB.
+GEMM_TRAFFIC_BYTES = 120.3 * 2 ** 20
 GEMM_ALGORITHMIC_BYTES = 60.0 * 2 ** 20
 HEADLINE = "mlp"
 

@@ -404,7 +404,7 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
         TileInfo t;
         t.b = (int)(pid / ntile);
         const int tp = (int)(pid % ntile);
-        constexpr int GM = 8;
+        const int GM = p.gm;
         const int width = GM * p.tiles_r;
         const int first_l = (tp / width) * GM;
         const int gsz = min(p.tiles_l - first_l, GM);
@@ -723,6 +723,22 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
     const TileCfg c = {TLG, TRG, WL, WR};
     int64_t grid = (int64_t)256 * workgroups_per_cu(c, BF);
     if (grid > total) grid = total;
+    // Band height of the tile walk.  An XCD works on a contiguous range of tile ids, gm tile rows x
+    // (range / gm) tile columns at a time, and fetches gm row panels and range / gm column panels
+    // into its L2: take the height that makes the sum of their bytes smallest.
+    {
+        const int64_t range = (grid < total ? grid : total) / 8 > 0 ? (grid < total ? grid : total) / 8 : 1;
+        int best = 8;
+        int64_t best_cost = -1;
+        for (int gm : {8, 4, 2, 16}) {
+            const int64_t rows = gm < a.tiles_l ? gm : a.tiles_l;
+            const int64_t cols = (range + rows - 1) / rows < a.tiles_r ? (range + rows - 1) / rows : a.tiles_r;
+            const int64_t cost = rows * TLG + cols * TRG;
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = gm; }
+        }
+        static const int force = [] { const char *e = getenv("LPG_GM"); return e ? atoi(e) : 0; }();
+        a.gm = force > 0 ? force : best;
+    }
     if constexpr (NS_LONE != NS) {
         if (total <= 256) {
             // Small lone tiles: a step of one K block is 2048-4096 MFMA cycles and every step ends

@@ -91,6 +91,7 @@ struct GemmArgs {
     // o_canon == 2: packed out whose origin is off the 32 / KB grid; Out points at the block holding
     // the origin, the view starts o_foff free indices and o_koff contraction indices into it
     int32_t o_foff, o_koff;
+    int32_t gm;                      // tile rows per band of the tile walk (set by the launcher)
 };
 
 struct EwArgs {
