@@ -154,7 +154,9 @@ int lpg_layout_offset(const lpg_desc *d, int64_t b, int64_t row, int64_t col, in
  * lpg_pack - canonical -> packed, once at the chain's entry (the packing step of
  * the GotoBLAS loop nest, Fig. 2c, done for the whole matrix; paper II-A).
  * src_d: ROW_MAJOR or COL_MAJOR; dst_d: PACKED_A or PACKED_B, same rows/cols/batch.
- * Writes every block the view touches, zero-filling padding.  dtype pairs:
+ * Writes every block the matrix touches, zero-filling padding; a destination that is
+ * a view inside a larger parent is written as lpg_desc describes (its own elements
+ * only where a block is shared with the parent's other elements).  dtype pairs:
  * f32->f32, bf16->bf16 (bit-exact copies), f32->bf16 (round to nearest even).
  */
 int lpg_pack(const void *src, const lpg_desc *src_d, void *dst, const lpg_desc *dst_d,
@@ -179,7 +181,7 @@ int lpg_unpack(const void *src, const lpg_desc *src_d, void *dst, const lpg_desc
  *   when beta == 0 (the packed-C requirement of III-B, which this library
  *   supports).  C_in == C_out (in place) is allowed; C_out must not alias A or B.
  *   Batches: c_d.batch matrices; A, B use slot b / batch_div of their descriptors.
- *   Padding of C_out is written as zeros.
+ *   Padding of C_out is written as zeros (C as a view inside a parent: see lpg_desc).
  * The same call is also the paper's Initial and Ending kernels (III-A.1, III-A.3):
  *   Initial: a_d may be LPG_ROW_MAJOR and/or b_d LPG_COL_MAJOR (the canonical order
  *   that is contiguous along the contraction index).  The kernel then gathers MFMA
