@@ -193,3 +193,45 @@ def test_llama_layer_full_size_sampled_rows():
     y = ch.output("Y").copy()
     rows = np.arange(11, shape["t"], 409)
     _check_llama(inp, shape, ch, y, rows)
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_row_operations_random_shapes(seed):
+    """Seeded sweep of the three row operations on the packed layout: row counts around the 32-row
+    groups, row lengths around the K blocks and around the register-resident / streamed limits."""
+    rng = np.random.default_rng(110000 + seed)
+    dtype = LPG_BF16 if rng.random() < 0.5 else LPG_F32
+    rows = int(rng.choice([1, 31, 32, 33, 64, 65, 100])) if rng.random() < 0.7 else int(rng.integers(1, 200))
+    op = str(rng.choice(["softmax", "softmax_causal", "rmsnorm", "rope"]))
+    if op == "rope":
+        dh = int(rng.choice([32, 64, 128])) if dtype == LPG_BF16 else int(rng.choice([16, 32, 64, 128]))
+        heads = int(rng.integers(1, 6))
+        cols = heads * dh
+    else:
+        cols = int(rng.choice([1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 1023, 1024, 1025, 2049, 4097])) \
+            if rng.random() < 0.7 else int(rng.integers(1, 9000))
+    x = (rng.standard_normal((rows, cols)) * 2).astype(np.float32)
+    px, d = pack_dev(x, LPG_PACKED_A, dtype)
+    xin = unpack_dev(px, d)
+    out = dev_empty(api.lpg_packed_bytes(d), fill=0xA5)
+    if op.startswith("softmax"):
+        causal = op.endswith("causal")
+        api.lpg_softmax_packed(px, out, d, 0.6, causal, stream())
+        want = ref.softmax_rows(xin, scale=0.6, causal=causal)
+        tol = (1e-5 if dtype == LPG_F32 else BF16_REL) * want + 1e-12
+    elif op == "rmsnorm":
+        w = rng.uniform(0.5, 1.5, cols).astype(np.float32)
+        api.lpg_rmsnorm_packed(px, dev_f32(w), out, d, 1e-5, stream())
+        want = ref.rmsnorm(xin, w.astype(np.float64), 1e-5)
+        tol = (1e-5 if dtype == LPG_F32 else BF16_REL) * np.abs(want) + 1e-12
+    else:
+        c, s = tables(rows, dh, pos0=int(rng.integers(0, 5000)))
+        api.lpg_rope_packed(px, out, d, dev_f32(c), dev_f32(s), dh, stream())
+        want = ref.rope(xin, c.astype(np.float64), s.astype(np.float64), dh)
+        half = dh // 2
+        mag = np.abs(xin).reshape(rows, heads, 2, half).sum(axis=2, keepdims=True).repeat(2, axis=2).reshape(rows, -1)
+        tol = 4e-7 * mag + (BF16_REL * np.abs(want) if dtype == LPG_BF16 else 0.0)
+    got = unpack_dev(out, d)
+    assert np.all(np.abs(got - want) <= tol), (op, rows, cols, dtype)
+    raw = host(out, NP_RAW[dtype])
+    assert np.count_nonzero(raw) == np.count_nonzero(got)              # padding stays zero
