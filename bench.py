@@ -245,7 +245,7 @@ def cpu_baseline(inp, shape, budget_s=15.0):
     from oracle import ref, workloads
     m = shape["m"]
     per_row = 2 * 2 * shape["d"] * shape["h"]
-    probe = min(m, 32)
+    probe = min(m, 256)
     t0 = time.perf_counter()
     workloads.mlp(inp, rows=np.arange(probe))
     dt = time.perf_counter() - t0
@@ -254,10 +254,20 @@ def cpu_baseline(inp, shape, budget_s=15.0):
     t0 = time.perf_counter()
     workloads.mlp(inp, rows=np.arange(rows))
     dt = time.perf_counter() - t0
-    return {"value": round(rows * per_row / dt / 1e12, 5), "unit": "TFLOP/s", "cores": ref.threads(),
+    # when the whole sample takes well under the budget it is repeated, so that the figure rests on
+    # about ten seconds of CPU work rather than on one short run
+    reps = 1
+    if dt < 5.0:
+        extra = int(min(63, max(0, 10.0 / max(dt, 1e-3) - 1)))
+        t0 = time.perf_counter()
+        for _ in range(extra):
+            workloads.mlp(inp, rows=np.arange(rows))
+        dt += time.perf_counter() - t0
+        reps += extra
+    return {"value": round(reps * rows * per_row / dt / 1e12, 5), "unit": "TFLOP/s", "cores": ref.threads(),
             "kind": "oracle", "seconds": round(dt, 2),
             "sample": f"first {rows} of {m} rows of X through both GEMMs of the MLP-like chain "
-                      f"(fp64 triple loop, OpenMP over rows)"}
+                      f"(fp64 triple loop, OpenMP over rows), {reps} time(s)"}
 
 
 SWEEP_GEMMS = [(n, n, n) for n in (256, 512, 1024, 2048, 4096, 8192)] + [
