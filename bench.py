@@ -15,6 +15,7 @@ bounded row sample of the same workload.
 """
 import argparse
 import json
+import os
 import statistics
 import sys
 import time
@@ -387,6 +388,9 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="profiling aid: run the elementwise SCALE kernel over a buffer of MIB MiB "
                          "(reads MIB, writes MIB per launch) --steps times, to scale HBM counters")
+    ap.add_argument("--probe", action="store_true",
+                    help="run the stand-alone main-loop probe (MFMA-only rates and the bf16 step rebuilt piece by "
+                         "piece; csrc/probe_mainloop.hip) and print its lines")
     args = ap.parse_args()
     global SETTLE_SECONDS
     SETTLE_SECONDS = args.settle_ms * 1e-3
@@ -394,6 +398,15 @@ def main():
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.probe:
+        # a child process of its own: nothing here has touched the GPU yet
+        import subprocess
+        exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_04599_amd", "probe_mainloop")
+        if not os.path.exists(exe):
+            print("bench.py: probe not built (python -c 'import __graft_entry__ as g; g.build()')", file=sys.stderr)
+            sys.exit(1)
+        sys.exit(subprocess.run([exe]).returncode)
 
     import torch
     if not torch.cuda.is_available():

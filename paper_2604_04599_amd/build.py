@@ -5,6 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblpg.so")
+PROBE = os.path.join(HERE, "probe_mainloop")   # stand-alone measuring tool, run by bench.py --probe
 OBJ = os.path.join(HERE, "_build")
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -45,6 +46,7 @@ def build(verbose: bool = False) -> str:
         if verbose and out.strip():
             print(out)
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)
+    _run([hipcc] + COMMON + ["-mllvm", "-amdgpu-mfma-vgpr-form=1", os.path.join(CSRC, "probe_mainloop.hip"), "-o", PROBE], verbose)
     return LIB
 
 
