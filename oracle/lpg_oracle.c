@@ -8,8 +8,6 @@
  *
  * What it holds
  *   orc_gemm        C = alpha*A*B + beta*C      (paper Eq. 1), fp64, row-major
- *   orc_gemm_alg1   the paper's Algorithm 1 written out literally (i-j-l loops,
- *                   alpha applied to every term); used as a brute-force pin
  *   orc_round_f32 / orc_round_bf16   storage rounding of an fp64 array
  *   orc_bf16_bits   fp32 bit pattern -> bf16 bit pattern, round-nearest-even
  *   orc_silu_mul    g*sigmoid(g)*u in fp64 (the activation F_i of Eq. 2 used by
@@ -79,20 +77,6 @@ void orc_gemm(int64_t m, int64_t n, int64_t k, double alpha,
         }
         free(acc);
     }
-}
-
-/* Algorithm 1 as printed: scale C by beta, then add alpha*A[i][l]*B[l][j] term
- * by term.  In place on C.  Single-threaded, small shapes only.  (Unlike
- * orc_gemm it reads C even when beta == 0, exactly as the listing does.) */
-void orc_gemm_alg1(int64_t m, int64_t n, int64_t k, double alpha,
-                   const double *A, const double *B, double beta, double *C)
-{
-    for (int64_t i = 0; i < m; ++i)
-        for (int64_t j = 0; j < n; ++j) {
-            C[i * n + j] = beta * C[i * n + j];
-            for (int64_t l = 0; l < k; ++l)
-                C[i * n + j] = C[i * n + j] + alpha * A[i * k + l] * B[l * n + j];
-        }
 }
 
 /* ------------------------------------------------------- storage rounding */

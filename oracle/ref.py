@@ -28,8 +28,6 @@ def lib():
         i64, dbl, vp, i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_int
         L.orc_gemm.argtypes = [i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, vp, i64]
         L.orc_gemm.restype = None
-        L.orc_gemm_alg1.argtypes = [i64, i64, i64, dbl, vp, vp, dbl, vp]
-        L.orc_gemm_alg1.restype = None
         L.orc_round_f32.argtypes = [vp, i64]
         L.orc_round_bf16.argtypes = [vp, i64]
         L.orc_bf16_bits.argtypes = [ctypes.c_uint32]
@@ -75,18 +73,6 @@ def gemm(A, B, alpha=1.0, beta=0.0, C=None):
         cptr, ldc_in = None, 0
     lib().orc_gemm(m, n, k, float(alpha), A.ctypes.data, k, B.ctypes.data, n,
                    float(beta), cptr, ldc_in, out.ctypes.data, n)
-    return out
-
-
-def gemm_alg1(A, B, alpha=1.0, beta=0.0, C=None):
-    """Algorithm 1 literally (brute-force pin); C defaults to zeros."""
-    A = _f64(A)
-    B = _f64(B)
-    m, k = A.shape
-    _, n = B.shape
-    out = np.zeros((m, n), dtype=np.float64) if C is None else _f64(C).copy()
-    lib().orc_gemm_alg1(m, n, k, float(alpha), A.ctypes.data, B.ctypes.data, float(beta),
-                        out.ctypes.data)
     return out
 
 

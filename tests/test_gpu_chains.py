@@ -12,6 +12,7 @@ import torch
 from oracle import ref, workloads
 from paper_2604_04599_amd import api, chains, inputs
 from paper_2604_04599_amd.api import LPG_CHAIN_CANONICAL, LPG_CHAIN_PROPAGATED
+from tests.gpu_util import assert_elements_bf16, assert_elements_f32, fetch_slot, spread_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -67,8 +68,11 @@ def test_mlp(over):
     h = ch.fetch("H")
     assert ref.rel_frobenius(h[sel], want["H"]) <= F32_TOL
     x = inp["X"][sel]
-    assert ref.rel_frobenius(prop[sel], ref.gemm(h[sel], inp["W2"], 1.0, 1.0, x)) <= F32_TOL
+    local = ref.gemm(h[sel], inp["W2"], 1.0, 1.0, x)
+    assert ref.rel_frobenius(prop[sel], local) <= F32_TOL
     assert ref.rel_frobenius(prop[sel], want["Y"]) <= 2 * F32_TOL
+    assert_elements_f32(h[sel], want["H"], "H")
+    assert_elements_f32(prop[sel], local, "Y")
 
 
 @pytest.mark.parametrize("over", [dict(heads=3, t=160, dh=64), dict()])
@@ -84,11 +88,24 @@ def test_attention(over):
             assert ref.rel_frobenius(prop[h], ref.gemm(s[h], inp["V"][h])) <= F32_TOL
             assert ref.rel_frobenius(prop[h], want["O"][h]) <= 2 * F32_TOL
     else:
-        rows = np.arange(5, shape["t"], 131)
+        # full size: per GEMM, on rows that fall into every 32-row group of the tiles.  S against the
+        # oracle on the inputs; O against the oracle fed with the device's own S (stage-local) and
+        # against the fp64 chain (end to end).
+        rows = spread_rows(shape["t"], 5)
         heads = [0, 13, 31]
-        want = workloads.attention(inp, rows=rows, heads=heads)
+        want = workloads.attention(inp, rows=rows, heads=heads, keep_s=True)
         for h in heads:
-            assert ref.rel_frobenius(prop[h][rows], want["O"][h]) <= 2 * F32_TOL
+            s = fetch_slot(ch, "S", h)
+            assert ref.rel_frobenius(s[rows], want["S"][h]) <= F32_TOL, h
+            assert_elements_f32(s[rows], want["S"][h], ("S", h))
+            local = ref.gemm(s[rows], inp["V"][h])
+            assert ref.rel_frobenius(prop[h][rows], local) <= F32_TOL, h
+            assert_elements_f32(prop[h][rows], local, ("O", h))
+            assert ref.rel_frobenius(prop[h][rows], want["O"][h]) <= 2 * F32_TOL, h
+            # columns of S as well (every tile column): all queries against a sample of keys
+            cols = spread_rows(shape["t"], 77, 16)
+            s_cols = ref.gemm(inp["Q"][h], np.ascontiguousarray(inp["K"][h][cols].T), alpha=shape["dh"] ** -0.5)
+            assert_elements_f32(s[:, cols], s_cols, ("S columns", h))
 
 
 @pytest.mark.parametrize("over", [dict(n=192, depth=5), dict(n=160, depth=8), dict()])
@@ -97,34 +114,62 @@ def test_deep_chain(over):
     prop, canon = run_both_modes(ch, "C")
     assert np.array_equal(prop.view(np.uint32), canon.view(np.uint32))
     depth = shape["depth"]
-    rows = None if over else np.arange(3, shape["n"], 257)
+    rows = None if over else spread_rows(shape["n"], 3)
+    cols = None if over else spread_rows(shape["n"], 70, 16)
     sel = slice(None) if rows is None else rows
     want = workloads.deep_chain(inp, rows=rows)
     prev = np.asarray(inp["C0"], dtype=np.float64)
     for i in range(1, depth + 1):
         ci = ch.fetch(f"C{i}")
-        assert ref.rel_frobenius(ci[sel], ref.gemm(prev[sel], inp["B"][i - 1])) <= F32_TOL, i
+        local = ref.gemm(prev[sel], inp["B"][i - 1])
+        assert ref.rel_frobenius(ci[sel], local) <= F32_TOL, i
+        assert_elements_f32(ci[sel], local, f"C{i}")
         assert ref.rel_frobenius(ci[sel], want["C"][i]) <= i * F32_TOL, i
+        if cols is not None:
+            # sampled columns over all rows: with the row sample, every tile of the output is met
+            assert_elements_f32(ci[:, cols], ref.gemm(prev, np.ascontiguousarray(inp["B"][i - 1][:, cols])), f"C{i} columns")
         prev = ci
     assert np.array_equal(prop, ch.fetch(f"C{depth}"))
 
 
-def _check_decoder(inp, shape, ch, prop, rows):
+def _check_decoder(inp, shape, ch, prop, rows, s_heads=None):
     nq, nkv = shape["n_q"], shape["n_kv"]
+    dh = shape["hidden"] // nq
+    rep = nq // nkv
     sel = slice(None) if rows is None else rows
     want = workloads.decoder_layer(inp, nq, nkv, rows=rows)
     got = {n: ch.fetch(n) for n in ("Q", "K", "V", "O", "attn", "gate", "up", "act")}
-    # end-to-end against the fp64 chain: stage count along the longest path
-    depth = {"Q": 1, "K": 1, "V": 1, "O": 3, "attn": 4, "gate": 5, "up": 5, "act": 5}
-    for n, s in depth.items():
+    # end-to-end against the fp64 chain
+    for n in ("Q", "K", "V", "O", "attn", "gate", "up", "act"):
         g = got[n] if n in ("K", "V") else got[n][sel]
         assert ref.rel_frobenius(g, want[n]) <= BF16_TOL, n
     assert ref.rel_frobenius(prop[sel], want["Y"]) <= BF16_TOL
-    # stage-local: oracle GEMM on the device's own (bf16-exact) intermediates
-    assert ref.rel_frobenius(got["attn"][sel], ref.gemm(got["O"][sel], inp["Wo"])) <= BF16_TOL
-    assert ref.rel_frobenius(got["gate"][sel], ref.gemm(got["attn"][sel], inp["Wg"])) <= BF16_TOL
-    assert ref.rel_frobenius(got["act"][sel], ref.silu_mul(got["gate"][sel], got["up"][sel])) <= BF16_TOL
-    assert ref.rel_frobenius(prop[sel], ref.gemm(got["act"][sel], inp["Wd"])) <= 1e-5   # fp32 out
+    # stage-local, per GEMM: the oracle on the device's own (bf16-exact) intermediates, by norm and
+    # element by element
+    x = np.asarray(inp["X"], dtype=np.float64)
+    local = {"Q": ref.gemm(x[sel], inp["Wq"]), "K": ref.gemm(x, inp["Wk"]), "V": ref.gemm(x, inp["Wv"]),
+             "attn": ref.gemm(got["O"][sel], inp["Wo"]), "gate": ref.gemm(got["attn"][sel], inp["Wg"]),
+             "up": ref.gemm(got["attn"][sel], inp["Wu"]), "act": ref.silu_mul(got["gate"][sel], got["up"][sel])}
+    for n, w in local.items():
+        g = got[n] if n in ("K", "V") else got[n][sel]
+        assert ref.rel_frobenius(g, w) <= BF16_TOL, n
+        assert_elements_bf16(g, w, n)
+    y_local = ref.gemm(got["act"][sel], inp["Wd"])
+    assert ref.rel_frobenius(prop[sel], y_local) <= 1e-5   # fp32 out
+    assert_elements_f32(prop[sel], y_local, "Y")
+    # the two attention GEMMs per head: S against the oracle on the device's own Q and K, O against
+    # the oracle on the device's own S and V
+    ridx = np.arange(shape["t"]) if rows is None else rows
+    for h in (range(nq) if s_heads is None else s_heads):
+        g = h // rep
+        s = fetch_slot(ch, "S", h)
+        s_ref = ref.gemm(np.ascontiguousarray(got["Q"][ridx, h * dh:(h + 1) * dh]),
+                         np.ascontiguousarray(got["K"][:, g * dh:(g + 1) * dh].T), alpha=dh ** -0.5)
+        assert ref.rel_frobenius(s[ridx], s_ref) <= BF16_TOL, h
+        assert_elements_bf16(s[ridx], s_ref, ("S", h))
+        o_ref = ref.gemm(s[ridx], np.ascontiguousarray(got["V"][:, g * dh:(g + 1) * dh]))
+        assert ref.rel_frobenius(got["O"][ridx, h * dh:(h + 1) * dh], o_ref) <= BF16_TOL, h
+        assert_elements_bf16(got["O"][ridx, h * dh:(h + 1) * dh], o_ref, ("O", h))
 
 
 def test_decoder_layer_small():
@@ -132,22 +177,14 @@ def test_decoder_layer_small():
     prop, canon = run_both_modes(ch, "Y")
     assert np.array_equal(prop.view(np.uint32), canon.view(np.uint32))
     _check_decoder(inp, shape, ch, prop, None)
-    # the S matrix itself, per head, against the oracle on the device's own Q and K
-    s = ch.fetch("S")
-    q, k = ch.fetch("Q"), ch.fetch("K")
-    dh = shape["hidden"] // shape["n_q"]
-    for h in range(shape["n_q"]):
-        g = h // (shape["n_q"] // shape["n_kv"])
-        s_ref = ref.gemm(q[:, h * dh:(h + 1) * dh].copy(), k[:, g * dh:(g + 1) * dh].T.copy(), alpha=dh ** -0.5)
-        assert ref.rel_frobenius(s[h], s_ref) <= BF16_TOL
 
 
 def test_decoder_layer_full_size_sampled_rows():
     inp, shape, ch = build("decoder_layer")
     prop, canon = run_both_modes(ch, "Y")
     assert np.array_equal(prop.view(np.uint32), canon.view(np.uint32))
-    rows = np.arange(11, shape["t"], 409)        # 10 rows; K and V are checked whole
-    _check_decoder(inp, shape, ch, prop, rows)
+    rows = spread_rows(shape["t"], 11)           # 32 rows; K and V are checked whole
+    _check_decoder(inp, shape, ch, prop, rows, s_heads=[0, 13, 31])
 
 
 def test_chain_rejects_mismatched_geometry_on_device_buffers():

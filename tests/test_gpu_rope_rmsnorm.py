@@ -16,7 +16,8 @@ from oracle import ref, workloads
 from paper_2604_04599_amd import api, chains, inputs
 from paper_2604_04599_amd.api import (LPG_BF16, LPG_CHAIN_CANONICAL, LPG_CHAIN_PROPAGATED, LPG_F32, LPG_PACKED_A,
                                       LPG_ROW_MAJOR, desc)
-from gpu_util import NP_RAW, bf16_raw_to_f64, dev_bytes, dev_empty, host, pack_dev, stream, unpack_dev
+from gpu_util import (NP_RAW, assert_elements_bf16, bf16_raw_to_f64, dev_bytes, dev_empty, host, pack_dev, spread_rows, stream,
+                      unpack_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -155,7 +156,14 @@ def _check_llama(inp, shape, ch, y, rows):
     th = ref.rope_angles(np.arange(shape["t"]), shape["hidden"] // nq, base)
     k_local = ref.rope(ref.round_bf16(ref.gemm(got["h1"], inp["Wk"])), np.cos(th), np.sin(th), shape["hidden"] // nq)
     assert ref.rel_frobenius(got["K"], k_local) <= 5e-3
-    assert ref.rel_frobenius(got["A"][sel], ref.gemm(got["O"][sel], inp["Wo"], beta=1.0, C=inp["X"][sel])) <= 3e-3
+    a_local = ref.gemm(got["O"][sel], inp["Wo"], beta=1.0, C=inp["X"][sel])
+    assert ref.rel_frobenius(got["A"][sel], a_local) <= 3e-3
+    assert_elements_bf16(got["A"][sel], a_local, "A")
+    act_local = ref.silu_mul(ref.round_bf16(ref.gemm(got["h2"][sel], inp["Wg"])), ref.round_bf16(ref.gemm(got["h2"][sel], inp["Wu"])))
+    assert ref.rel_frobenius(got["act"][sel], act_local) <= 1e-2
+    y_local = ref.gemm(got["act"][sel], inp["Wd"], beta=1.0, C=got["A"][sel])
+    assert ref.rel_frobenius(y[sel], y_local) <= 3e-3
+    assert_elements_bf16(y[sel], y_local, "Y")
     return want
 
 
@@ -191,7 +199,7 @@ def test_llama_layer_full_size_sampled_rows():
     ch = chains.build("llama_layer", inp, shape)
     ch.run(LPG_CHAIN_PROPAGATED)
     y = ch.output("Y").copy()
-    rows = np.arange(11, shape["t"], 409)
+    rows = spread_rows(shape["t"], 11)
     _check_llama(inp, shape, ch, y, rows)
 
 
