@@ -340,6 +340,27 @@ size_t lpg_chain_workspace_bytes(const lpg_stage *stages, int n, int mode);
 int lpg_chain(const lpg_stage *stages, int n, int mode, void *workspace,
               size_t workspace_bytes, void *stream);
 
+/*
+ * Tuning and test hooks.  Every choice the library makes per launch (tile configuration, band
+ * height of the tile walk, staging-ring variants, row-kernel variant) can be pinned for
+ * measurements and for tests that must reach every variant; -1 (LPG_TUNE_AUTO) gives the choice
+ * back to the library.  Process-wide, read at every launch, not meant for production use.
+ * Table I of the paper lists such parameters per architecture; these are this library's.
+ */
+typedef enum {
+    LPG_TUNE_TILE = 0,                    /* GEMM tile configuration index 0..LPG_TILE_CONFIGS-1   */
+    LPG_TUNE_BAND = 1,                    /* tile rows per band of the XCD-local tile walk          */
+    LPG_TUNE_TWO_BLOCK_STEPS = 2,         /* 0: lone small tiles take one K block per step          */
+    LPG_TUNE_BF16_WHOLE_BLOCK_STEPS = 3,  /* 0: bf16 4-wave tiles use the half-block ring           */
+    LPG_TUNE_ROW_VARIANT = 4,             /* softmax / RMSNorm kernel variant 0..5                  */
+    LPG_TUNE_ATTN_QUERY_GROUPS = 5,       /* fused attention: 1 or 2 query groups per wave          */
+    LPG_TUNE_TRACE = 6,                   /* 1: print the tile configuration of every GEMM launch   */
+    LPG_TUNE_KEYS = 7
+} lpg_tune_key;
+#define LPG_TUNE_AUTO (-1)
+int lpg_tune_set(int key, int value);
+int lpg_tune_get(int key, int *value);
+
 /* Message for the last error on this thread ("" if none). */
 const char *lpg_last_error(void);
 

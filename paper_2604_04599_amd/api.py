@@ -21,6 +21,9 @@ LPG_STAGE_PACK, LPG_STAGE_GEMM, LPG_STAGE_ELEMENTWISE, LPG_STAGE_UNPACK, LPG_STA
 LPG_STAGE_RMSNORM, LPG_STAGE_ROPE, LPG_STAGE_ATTENTION = 5, 6, 7
 LPG_CHAIN_PROPAGATED, LPG_CHAIN_CANONICAL = 0, 1
 LPG_ATTN_CAUSAL, LPG_ATTN_NO_SOFTMAX = 1, 2
+(LPG_TUNE_TILE, LPG_TUNE_BAND, LPG_TUNE_TWO_BLOCK_STEPS, LPG_TUNE_BF16_WHOLE_BLOCK_STEPS, LPG_TUNE_ROW_VARIANT,
+ LPG_TUNE_ATTN_QUERY_GROUPS, LPG_TUNE_TRACE) = range(7)
+LPG_TUNE_AUTO = -1
 
 ELEM_SIZE = {LPG_F32: 4, LPG_BF16: 2}
 
@@ -98,6 +101,10 @@ def lib():
         L.lpg_chain_workspace_bytes.restype = ctypes.c_size_t
         L.lpg_chain.argtypes = [sp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp]
         L.lpg_chain.restype = ctypes.c_int
+        L.lpg_tune_set.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.lpg_tune_set.restype = ctypes.c_int
+        L.lpg_tune_get.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+        L.lpg_tune_get.restype = ctypes.c_int
         L.lpg_last_error.restype = ctypes.c_char_p
         L.lpg_version.restype = ctypes.c_char_p
         _lib = L
@@ -106,7 +113,7 @@ def lib():
 
 EXPORTS = ("lpg_packed_bytes", "lpg_layout_offset", "lpg_pack", "lpg_unpack", "lpg_gemm_packed",
            "lpg_elementwise_packed", "lpg_softmax_packed", "lpg_attention_packed", "lpg_rmsnorm_packed", "lpg_rope_tables", "lpg_rope_packed",
-           "lpg_chain_workspace_bytes", "lpg_chain", "lpg_last_error",
+           "lpg_chain_workspace_bytes", "lpg_chain", "lpg_tune_set", "lpg_tune_get", "lpg_last_error",
            "lpg_version")
 
 
@@ -217,6 +224,16 @@ def lpg_chain_workspace_bytes(stages, mode):
 def lpg_chain(stages, mode=LPG_CHAIN_PROPAGATED, workspace=None, workspace_bytes=0, stream=None):
     arr = stages if isinstance(stages, ctypes.Array) else stage_array(stages)
     return _check(lib().lpg_chain(arr, len(arr), mode, _ptr(workspace), workspace_bytes, stream))
+
+
+def lpg_tune_set(key, value):
+    return _check(lib().lpg_tune_set(key, value))
+
+
+def lpg_tune_get(key):
+    v = ctypes.c_int(0)
+    _check(lib().lpg_tune_get(key, ctypes.byref(v)))
+    return v.value
 
 
 # stage constructors (pure marshalling)

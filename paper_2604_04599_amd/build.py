@@ -5,14 +5,15 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblpg.so")
-PROBE = os.path.join(HERE, "probe_mainloop")   # stand-alone measuring tool, run by bench.py --probe
 OBJ = os.path.join(HERE, "_build")
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 # source -> extra flags.  MFMA accumulators are pinned to VGPRs: with the default the compiler
 # parks VGPR spills in AGPRs for the 4-wave 256 x 128 tiles and halves their occupancy.
-SOURCES = {"lpg_api.cpp": [], "lpg_kernels.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]
+SOURCES = {"lpg_api.cpp": [], "lpg_kernels.hip": VGPR_FORM, "lpg_gemm_f32.hip": VGPR_FORM,
+           "lpg_gemm_bf16.hip": VGPR_FORM, "lpg_gemm_bf16_f32.hip": VGPR_FORM}
 
 
 def _run(cmd, verbose):
@@ -46,7 +47,6 @@ def build(verbose: bool = False) -> str:
         if verbose and out.strip():
             print(out)
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)
-    _run([hipcc] + COMMON + ["-mllvm", "-amdgpu-mfma-vgpr-form=1", os.path.join(CSRC, "probe_mainloop.hip"), "-o", PROBE], verbose)
     return LIB
 
 

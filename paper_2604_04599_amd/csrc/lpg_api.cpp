@@ -375,10 +375,8 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     g.alpha = alpha;
     g.beta = beta;
     if (g.FL == 0 || g.FR == 0) return LPG_OK;
-    // LPG_FORCE_TILE=<index> pins the tile configuration (a tuning aid; unset = automatic)
-    int cfg = -1;
-    if (const char *f = getenv("LPG_FORCE_TILE")) cfg = atoi(f);
-    hipError_t e = launch_gemm(g, ao.dtype, c_dtype, cfg, st);
+    // the tuning hook LPG_TUNE_TILE pins the tile configuration (-1 = automatic)
+    hipError_t e = launch_gemm(g, ao.dtype, c_dtype, tune_get(LPG_TUNE_TILE), st);
     if (e != hipSuccess) return fail(LPG_EHIP, "lpg_gemm_packed: %s", hipGetErrorString(e));
     return LPG_OK;
 }
@@ -401,7 +399,6 @@ static int do_elementwise(int op, const void *x0, const void *x1, float s, void 
     if (!x0 || !out) return fail(LPG_EINVAL, "lpg_elementwise_packed: NULL pointer");
     if (op != LPG_EW_SCALE && !x1) return fail(LPG_EINVAL, "lpg_elementwise_packed: op needs x1");
     const size_t bytes = desc_bytes(d);
-    if (bytes % 16) return fail(LPG_EALIGN, "lpg_elementwise_packed: buffer size must be a multiple of 16 bytes");
     if ((uintptr_t)x0 % 16 || (uintptr_t)out % 16 || (x1 && (uintptr_t)x1 % 16))
         return fail(LPG_EALIGN, "lpg_elementwise_packed: buffers must be 16-byte aligned");
     if (!launch) return LPG_OK;
@@ -410,6 +407,7 @@ static int do_elementwise(int op, const void *x0, const void *x1, float s, void 
     a.x1 = (op == LPG_EW_SCALE) ? nullptr : (const char *)x1;
     a.out = (char *)out;
     a.n16 = (int64_t)(bytes / 16);
+    a.tail = (int32_t)((bytes % 16) / elem_size(d->dtype));
     a.op = op;
     a.s = s;
     hipError_t e = launch_elementwise(a, d->dtype, st);
@@ -788,6 +786,9 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
 {
     std::vector<Slot> slots;
     size_t used = 0;
+    // the dry pass validates the control's own stages too: it hands them addresses that have the
+    // workspace's alignment and are never dereferenced
+    if (!ws) ws = (char *)(uintptr_t)4096;
     auto find = [&](const void *p) -> Slot * {
         for (auto &s : slots)
             if (s.packed == p) return &s;
@@ -805,7 +806,7 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
         Slot *s = find(p);
         const size_t bytes = twin_bytes(pd);
         if (s && s->bytes >= bytes) return s;
-        Slot ns{p, ws ? ws + used : nullptr, bytes, false};
+        Slot ns{p, ws + used, bytes, false};
         used += bytes;
         if (s) { *s = ns; return s; }
         slots.push_back(ns);
@@ -845,13 +846,13 @@ static int chain_canonical(const lpg_stage *st, int n, char *ws, size_t ws_bytes
                 // get_slot may have moved the vector: look the inputs up again
                 s0 = find(s.in0);
                 s1 = (!sm && s.in1) ? find(s.in1) : nullptr;
-                if (!dry) {
+                {
                     int rc;
                     if (sm) {
-                        rc = run_row_stage(s, s0->canon, so->canon, &c, hs, true);
+                        rc = run_row_stage(s, s0->canon, so->canon, &c, hs, !dry);
                     } else {
                         c.ld = 0;
-                        rc = do_elementwise(s.op, s0->canon, s1 ? s1->canon : nullptr, s.scalar, so->canon, &c, hs, true);
+                        rc = do_elementwise(s.op, s0->canon, s1 ? s1->canon : nullptr, s.scalar, so->canon, &c, hs, !dry);
                     }
                     if (rc) return rc;
                 }
@@ -1034,6 +1035,19 @@ int lpg_chain(const lpg_stage *stages, int n, int mode, void *workspace, size_t 
         return fail(LPG_EWORKSPACE, "lpg_chain: workspace too small (%zu needed, %zu given)", need, workspace_bytes);
     if (need && (uintptr_t)workspace % 256) return fail(LPG_EALIGN, "lpg_chain: workspace must be 256-byte aligned");
     return chain_canonical(stages, n, (char *)workspace, workspace_bytes, hs, false, nullptr);
+}
+
+int lpg_tune_set(int key, int value)
+{
+    if (tune_set(key, value)) return fail(LPG_EINVAL, "lpg_tune_set: unknown key %d", key);
+    return LPG_OK;
+}
+
+int lpg_tune_get(int key, int *value)
+{
+    if (key < 0 || key >= LPG_TUNE_KEYS || !value) return fail(LPG_EINVAL, "lpg_tune_get: unknown key %d or NULL value", key);
+    *value = tune_get(key);
+    return LPG_OK;
 }
 
 const char *lpg_last_error(void) { return g_err; }

@@ -1,5 +1,5 @@
 // Device code shared by the translation units of the GPU path: element types, bf16
-// conversions, the MFMA GEMM kernel with its tile configurations and launchers.
+// conversions, the direct global->LDS transfer, MFMA and wait helpers.
 #pragma once
 
 #include <cstdio>
@@ -56,29 +56,6 @@ __device__ __forceinline__ typename D::raw convert_raw(typename S::raw x)
 }
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
-
-// ---------------------------------------------------------------------------------
-// GEMM.  out[fl][fr] = epilogue(alpha * sum_k L[fl][k] * R[fr][k] + beta * Cin[fl][fr]),
-// L = P(L; FL, K), R = P(R; FR, K), out = P(out; free = FL, contraction = FR).
-//
-// The MFMA computes a 32x32 tile D[i][j] = sum_k Aop[i][k] * Bop[k][j]; lane l of the
-// A operand carries row i = l%32, lane l of the B operand carries column j = l%32, and
-// lane l, register r of D holds D[8*(r/4) + 4*(l/32) + r%4][l%32].  With R's fragment
-// in the A slot and L's fragment in the B slot, lanes run along out's free index and
-// each group of four registers is four consecutive contraction indices of out: the
-// accumulators already are fragments of P(out; FL, FR) and are stored as they stand.
-//
-// Workgroup tile: TLG x TRG 32-groups; WL x WR waves, each owning (TLG/WL) x (TRG/WR)
-// 32x32 tiles.  A step stages FS fragments per group (FS = 4: a whole K block, FS = 2:
-// half of one) into one of NS LDS stages used as a ring; NS-1 steps are in flight ahead of
-// the one being multiplied.  The packed block already is the register image, so the copy
-// is verbatim: each wave moves whole 1 KiB fragments with the direct global->LDS load (no
-// VGPR round trip), and every ds_read_b128 at lane*16 is conflict free.
-//
-// Workgroups are persistent: workgroup j walks the virtual tile ids j, j + G, j + 2G, ...
-// (G = grid size) and the staging ring runs across tile boundaries, so the next tile's
-// first steps are in flight while the current tile's epilogue stores drain.  Every
-// workgroup runs a fixed, finite number of steps; there is no queue and no atomics.
 
 // 16 bytes per lane, global -> LDS at lds_addr + lane*16 (lds_addr wave-uniform).  Written
 // as inline asm so that the compiler does not serialise later LDS reads of the OTHER stage
@@ -158,623 +135,6 @@ template <int MASK, int N>
 __device__ __forceinline__ void sched_group()
 {
     if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
-}
-
-// registers -> fragments of P(out; FL, FR) for one 32x32 accumulator tile
-template <typename OUT>
-__device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane,
-                                           char *Ob, const char *Cb, const char *Eb, bool use_c, bool use_e)
-{
-    const int h = lane >> 5;
-    const int fl = grL * 32 + (lane & 31);
-    const bool have = grR < p.FRg;
-    float v[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) v[e] = have ? acc[e] : 0.0f;
-    if (p.alpha != 1.0f) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] *= p.alpha;
-    }
-    if (p.o_canon) {
-        // Ending kernel: straight to row/column-major.  Lanes run along out's free index, so
-        // for each register the 32 lanes of a half wave write one contiguous run.  The same
-        // element-by-element walk serves a packed out whose origin is off the grid.
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-            if (fl >= p.FL || fr >= p.FR) continue;
-            int64_t off;
-            if (p.o_canon == 2) {
-                // packed out with its origin off the grid: the element's own position in the
-                // parent's blocks, o_foff / o_koff further along than in an aligned view
-                const int fp = fl + p.o_foff, kp = fr + p.o_koff;
-                const int kin = kp % OUT::KB, r = kin % OUT::KF;
-                off = (int64_t)(kp / OUT::KB) * p.o_kbs + (int64_t)(fp >> 5) * kBlockBytes + (kin / OUT::KF) * kFragBytes +
-                      (((r >> 2) & 1) * 32 + (fp & 31)) * 16 + (4 * (r >> 3) + (r & 3)) * OUT::ES;
-            } else {
-                off = (int64_t)fl * p.o_sf + (int64_t)fr * p.o_sk;
-            }
-            float x = v[e];
-            if (use_c) {
-                if constexpr (OUT::ES == 4) x += p.beta * *(const float *)(Cb + off);
-                else x += p.beta * bf16_to_f32(*(const uint16_t *)(Cb + off));
-            }
-            float gte = 0.0f;
-            if (use_e) {
-                if constexpr (OUT::ES == 4) gte = *(const float *)(Eb + off);
-                else gte = bf16_to_f32(*(const uint16_t *)(Eb + off));
-            }
-            x = epi_apply(p.epi, x, gte);
-            if constexpr (OUT::ES == 4) *(float *)(Ob + off) = x;
-            else *(uint16_t *)(Ob + off) = (uint16_t)bf16_rne(x);
-        }
-        return;
-    }
-    int64_t obase;  // byte offset of this tile's first fragment inside out
-    if constexpr (OUT::ES == 4)
-        obase = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
-    else
-        obase = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes + (grR & 1) * 2 * kFragBytes + lane * 16;
-    constexpr int NF = (OUT::ES == 4) ? 4 : 2;  // fragments this tile spans
-    constexpr int PER = 16 / NF;
-    if (use_c || use_e) {
-#pragma unroll
-        for (int fgi = 0; fgi < NF; ++fgi) {
-            float cv[PER], ev[PER];
-            if (use_c) {
-                const uint4 t4 = *(const uint4 *)(Cb + obase + fgi * kFragBytes);
-                const uint32_t w[4] = {t4.x, t4.y, t4.z, t4.w};
-#pragma unroll
-                for (int j = 0; j < PER; ++j) {
-                    if constexpr (OUT::ES == 4) cv[j] = __uint_as_float(w[j]);
-                    else cv[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
-                }
-            }
-            if (use_e) {
-                const uint4 t4 = *(const uint4 *)(Eb + obase + fgi * kFragBytes);
-                const uint32_t w[4] = {t4.x, t4.y, t4.z, t4.w};
-#pragma unroll
-                for (int j = 0; j < PER; ++j) {
-                    if constexpr (OUT::ES == 4) ev[j] = __uint_as_float(w[j]);
-                    else ev[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < PER; ++j) {
-                float x = v[fgi * PER + j];
-                if (use_c) x += p.beta * cv[j];
-                v[fgi * PER + j] = epi_apply(p.epi, x, use_e ? ev[j] : 0.0f);
-            }
-        }
-    } else if (p.epi == LPG_EPI_SILU) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] = silu_f(v[e]);
-    }
-    // zero the padding of ragged edge tiles
-    if (grL * 32 + 32 > p.FL || grR * 32 + 32 > p.FR) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-            if (fl >= p.FL || fr >= p.FR) v[e] = 0.0f;
-        }
-        if (p.o_keep_l | p.o_keep_r) {
-            // the view's ragged extent ends inside its parent: what lies past it in this tile
-            // belongs to the parent's other elements and is left as it is
-            const bool l_mine = fl < p.FL || !p.o_keep_l;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int fr = grR * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-                if (!l_mine || (fr >= p.FR && p.o_keep_r)) continue;
-                char *dst = Ob + obase + (e / PER) * kFragBytes + (e % PER) * OUT::ES;
-                if constexpr (OUT::ES == 4) *(float *)dst = v[e];
-                else *(uint16_t *)dst = (uint16_t)bf16_rne(v[e]);
-            }
-            return;
-        }
-    }
-    if constexpr (OUT::ES == 4) {
-#pragma unroll
-        for (int fgi = 0; fgi < 4; ++fgi)
-            *(uint4 *)(Ob + obase + fgi * kFragBytes) =
-                make_uint4(__float_as_uint(v[4 * fgi]), __float_as_uint(v[4 * fgi + 1]),
-                           __float_as_uint(v[4 * fgi + 2]), __float_as_uint(v[4 * fgi + 3]));
-    } else {
-#pragma unroll
-        for (int fgi = 0; fgi < 2; ++fgi) {
-            uint32_t w[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) w[j] = bf16_pack2(v[8 * fgi + 2 * j], v[8 * fgi + 2 * j + 1]);
-            *(uint4 *)(Ob + obase + fgi * kFragBytes) = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-    }
-}
-
-// The common case of store_tile, kept small: packed output, no C_in, no fused operation, a
-// tile wholly inside the logical extents.  The epilogue is instantiated once per accumulator
-// tile of the wave; with only the general form, a launch of many short tiles (attention
-// scores) spends its time fetching that code.
-// 16 bytes of a packed fragment as floats (4 fp32 or 8 bf16 elements)
-template <typename OUT>
-__device__ __forceinline__ void frag_vals(const char *ptr, float (&x)[16 / OUT::ES])
-{
-    const uint4 t = *(const uint4 *)ptr;
-    const uint32_t w[4] = {t.x, t.y, t.z, t.w};
-    if constexpr (OUT::ES == 4) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) x[j] = __uint_as_float(w[j]);
-    } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) x[j] = bf16_to_f32((w[j >> 1] >> (16 * (j & 1))) & 0xffff);
-    }
-}
-
-template <typename OUT, bool USE_C, int EPI>
-__device__ __forceinline__ void store_tile_plain(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane, char *Ob,
-                                                 const char *Cb, const char *Eb)
-{
-    constexpr int NF = (OUT::ES == 4) ? 4 : 2, PER = 16 / NF;
-    int64_t off;
-    if constexpr (OUT::ES == 4) off = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
-    else off = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes + (grR & 1) * 2 * kFragBytes + lane * 16;
-#pragma unroll
-    for (int fgi = 0; fgi < NF; ++fgi) {
-        float v[PER];
-#pragma unroll
-        for (int j = 0; j < PER; ++j) v[j] = acc[fgi * PER + j] * p.alpha;
-        if constexpr (USE_C) {
-            float c[PER];
-            frag_vals<OUT>(Cb + off + fgi * kFragBytes, c);
-#pragma unroll
-            for (int j = 0; j < PER; ++j) v[j] += p.beta * c[j];
-        }
-        if constexpr (EPI == LPG_EPI_SILU) {
-#pragma unroll
-            for (int j = 0; j < PER; ++j) v[j] = silu_f(v[j]);
-        } else if constexpr (EPI == LPG_EPI_GATE_SILU) {
-            float g[PER];
-            frag_vals<OUT>(Eb + off + fgi * kFragBytes, g);
-#pragma unroll
-            for (int j = 0; j < PER; ++j) v[j] = silu_f(g[j]) * v[j];
-        }
-        if constexpr (OUT::ES == 4) {
-            *(uint4 *)(Ob + off + fgi * kFragBytes) =
-                make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
-        } else {
-            *(uint4 *)(Ob + off + fgi * kFragBytes) = make_uint4(bf16_pack2(v[0], v[1]), bf16_pack2(v[2], v[3]),
-                                                                  bf16_pack2(v[4], v[5]), bf16_pack2(v[6], v[7]));
-        }
-    }
-}
-
-// The same for a row- or column-major output (Ending kernel), interior tiles, no C_in, no
-// fused operation: lanes run along out's free index, so for each register the 32 lanes of a
-// half wave write one contiguous run.
-template <typename OUT>
-__device__ __forceinline__ void store_tile_canon_plain(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane, char *Ob)
-{
-    const int h = lane >> 5;
-    char *o = Ob + (int64_t)(grL * 32 + (lane & 31)) * p.o_sf + (int64_t)(grR * 32 + 4 * h) * p.o_sk;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        char *dst = o + (int64_t)(8 * (e >> 2) + (e & 3)) * p.o_sk;
-        const float x = acc[e] * p.alpha;
-        if constexpr (OUT::ES == 4) *(float *)dst = x;
-        else *(uint16_t *)dst = (uint16_t)bf16_rne(x);
-    }
-}
-
-// XPF (needs NS >= 3): the first fragment of the NEXT step is read into registers while the
-// last fragment of the current step is multiplied, so no LDS latency is exposed after the
-// barrier; the barrier of a step then also publishes the step after it.
-template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR, int FS, int NS, bool XPF>
-__global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
-{
-    static_assert(!XPF || NS >= 3, "cross-step prefetch needs a landed stage beyond the current one");
-    constexpr int NW = WL * WR;
-    constexpr int WTL = TLG / WL, WTR = TRG / WR;
-    constexpr int NFRAG = (TLG + TRG) * FS;  // fragments per stage
-    constexpr int FPW = NFRAG / NW;          // fragments each wave copies per stage
-    constexpr int FPW_L = TLG * FS / NW;     // ... of which the first FPW_L come from L
-    constexpr int STAGE = NFRAG * kFragBytes;
-    constexpr int BPS = FS > kFragsPerBlock ? FS / kFragsPerBlock : 1;  // K blocks per step
-    static_assert(NFRAG % NW == 0 && (TLG * FS) % NW == 0, "stage must divide over the waves");
-    static_assert(TLG % WL == 0 && TRG % WR == 0, "tile must divide over the waves");
-    static_assert(FS == 2 || FS == 4 || FS == 8, "a step is half a K block, one, or two");
-    static_assert(NS >= 2 && NS <= 5 && (NS - 2) * FPW <= 63, "ring depth limited by the vmcnt field");
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wl = wave % WL, wr = wave / WL;
-
-    const uint32_t ntile = (uint32_t)(p.tiles_l * p.tiles_r);
-    const uint32_t total = ntile * (uint32_t)p.batch;
-    const uint32_t G = gridDim.x;
-    const int spt = FS > kFragsPerBlock ? p.nkb / BPS : p.nkb * (kFragsPerBlock / FS);  // steps per tile (launcher: BPS divides nkb)
-    if (blockIdx.x >= total) return;
-    const uint32_t my_tiles = (total - blockIdx.x + G - 1) / G;
-
-    // virtual block id -> (batch, tile).  Hardware deals consecutive workgroups round-robin
-    // to the 8 XCDs; ids congruent mod 8 get one contiguous range of tile ids, walked in
-    // bands of GM tile-rows, so the tiles an XCD works on share L and R panels in its L2.
-    auto decode = [&](uint32_t vb) -> TileInfo {
-        const uint32_t per = total / 8, rem = total % 8, x = vb % 8, idx = vb / 8;
-        const uint32_t pid = (x < rem) ? x * (per + 1) + idx : rem * (per + 1) + (x - rem) * per + idx;
-        TileInfo t;
-        t.b = (int)(pid / ntile);
-        const int tp = (int)(pid % ntile);
-        const int GM = p.gm;
-        const int width = GM * p.tiles_r;
-        const int first_l = (tp / width) * GM;
-        const int gsz = min(p.tiles_l - first_l, GM);
-        const int tl = first_l + (tp % width) % gsz;
-        const int tr = (tp % width) / gsz;
-        t.gl0 = tl * TLG;
-        t.gr0 = tr * TRG;
-        t.nlg = min(TLG, p.FLg - t.gl0);
-        t.nrg = max(0, min(TRG, p.FRg - t.gr0));
-        // packed: first block of the tile; canonical: the operand's (slot's) first element
-        t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (p.l_canon ? 0 : (int64_t)t.gl0 * kBlockBytes);
-        t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (p.r_canon ? 0 : (int64_t)t.gr0 * kBlockBytes);
-        return t;
-    };
-
-    // ---- copy side.  Wave w copies fragments w, w + NW, ... of a stage; src[i] is this
-    // lane's address of its i-th fragment at the step the copy cursor stands on.  Every wave
-    // always issues exactly FPW transfers per step, so outstanding-transfer counts agree
-    // across waves: a group the tile does not have is replaced by the tile's last existing
-    // group (its data is never used), which keeps every address inside the operand.
-    const char *src[FPW];
-    auto aim = [&](const TileInfo &t) {
-#pragma unroll
-        for (int i = 0; i < FPW; ++i) {
-            const int fid = i * NW + wave;
-            const int grp = fid / FS, c = fid % FS;
-            const bool is_l = i < FPW_L;
-            if (is_l ? p.l_canon : p.r_canon) {
-                // Initial kernel: gather the fragment straight from the canonical matrix.  Lane
-                // (fl, h) of fragment c needs k = KF*c + 4*h .. +3 of free index fl: 16
-                // contiguous bytes of a k-contiguous fp32 row, which the transfer drops at
-                // lane*16 of the stage, i.e. in fragment order.  Rows past the end are
-                // replaced by the last row (never used).
-                const int g0 = is_l ? t.gl0 + grp : t.gr0 + grp - TLG;
-                const int row = min(g0 * 32 + (lane & 31), (is_l ? p.FL : p.FR) - 1);
-                const char *base = is_l ? t.Lp + (int64_t)row * p.l_ld : t.Rp + (int64_t)row * p.r_ld;
-                src[i] = base + c * (IN::KF * IN::ES) + (lane >> 5) * 16;
-            } else {
-                const char *base = is_l ? t.Lp + min(grp, t.nlg - 1) * kBlockBytes
-                                        : t.Rp + max(0, min(grp - TLG, t.nrg - 1)) * kBlockBytes;
-                // fragment c of the step: fragment c % 4 of the step's K block c / 4
-                src[i] = base + (c / kFragsPerBlock) * (is_l ? p.l_kbs : p.r_kbs) + (c % kFragsPerBlock) * kFragBytes + lane * 16;
-            }
-        }
-    };
-    uint32_t c_tiles_left = my_tiles;  // tiles the copy cursor still has to start or finish
-    uint32_t c_vb = blockIdx.x;
-    int c_s = 0;                       // step of its tile the copy cursor stands on
-    int c_st = 0;                      // ring stage it fills next
-    int pending = 0;                   // steps copied (or in flight) and not yet multiplied
-    bool c_live = spt > 0;
-    // fragment i of the step the copy cursor stands on -> ring stage c_st
-    auto copy_issue = [&](int i) {
-        lds_dma16(src[i], sbase + c_st * STAGE + (i * NW + wave) * kFragBytes);
-    };
-    // move the copy cursor one step on
-    auto copy_advance = [&]() {
-        c_st = (c_st + 1 == NS) ? 0 : c_st + 1;
-        ++pending;
-        if (++c_s == spt) {  // next tile
-            c_s = 0;
-            c_vb += G;
-            if (--c_tiles_left == 0) c_live = false;
-            else aim(decode(c_vb));
-        } else {             // next step of the same tile
-            int64_t dl, dr;
-            if (FS >= kFragsPerBlock) {       // whole K blocks per step
-                dl = BPS * p.l_kbs;
-                dr = BPS * p.r_kbs;
-            } else if ((c_s & 1) == 0) {      // first fragments of the next K block
-                dl = p.l_kbs - (kFragsPerBlock - FS) * kFragBytes;
-                dr = p.r_kbs - (kFragsPerBlock - FS) * kFragBytes;
-            } else {                          // second half of the same K block
-                dl = dr = FS * kFragBytes;
-            }
-            if (p.l_canon) dl = FS * IN::KF * IN::ES;  // canonical rows are contiguous along k
-            if (p.r_canon) dr = FS * IN::KF * IN::ES;
-#pragma unroll
-            for (int i = 0; i < FPW; ++i) src[i] += (i < FPW_L) ? dl : dr;
-        }
-    };
-    auto copy_step = [&]() {
-#pragma unroll
-        for (int i = 0; i < FPW; ++i) copy_issue(i);
-        copy_advance();
-    };
-    aim(decode(c_vb));
-#pragma unroll
-    for (int j = 0; j < NS - 1; ++j)
-        if (c_live) copy_step();
-
-    const bool use_c = (p.beta != 0.0f) && p.Cin;
-    const bool use_e = (p.epi == LPG_EPI_GATE_SILU) && p.Epi;
-
-    // ---- multiply side
-    int st = 0;
-    const char *sLw = smem + (wl * WTL) * (FS * kFragBytes) + lane * 16;
-    const char *sRw = smem + (TLG + wr * WTR) * (FS * kFragBytes) + lane * 16;
-    uint4 lf[2][WTL], rf[2][WTR];
-    if constexpr (XPF) {
-        // prime: fragment 0 of the very first step
-        if (pending == NS - 1) wait_vmcnt<(NS - 2) * FPW>();
-        else wait_vmcnt<0>();
-        __syncthreads();
-#pragma unroll
-        for (int a = 0; a < WTL; ++a) lf[0][a] = *(const uint4 *)(sLw + a * (FS * kFragBytes));
-#pragma unroll
-        for (int q = 0; q < WTR; ++q) rf[0][q] = *(const uint4 *)(sRw + q * (FS * kFragBytes));
-    }
-    uint32_t vb = blockIdx.x;
-    for (uint32_t ti = 0; ti < my_tiles; ++ti, vb += G) {
-        f32x16 acc[WTL][WTR];
-#pragma unroll
-        for (int a = 0; a < WTL; ++a)
-#pragma unroll
-            for (int q = 0; q < WTR; ++q)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[a][q][e] = 0.0f;
-
-        for (int s = 0; s < spt; ++s) {
-            // Wait until this wave's transfers of the step that must be readable have landed
-            // (XPF: the step after the current one; otherwise the current one); later steps
-            // stay in flight (transfers complete in issue order).
-            constexpr int KEEP = XPF ? NS - 3 : NS - 2;
-            if (pending == NS - 1) wait_vmcnt<KEEP * FPW>();
-            else wait_vmcnt<0>();
-            __syncthreads();  // everyone's transfers landed; the stage multiplied last step is free
-
-            const char *sL = sLw + st * STAGE;
-            const char *sR = sRw + st * STAGE;
-            const int stn = (st + 1 == NS) ? 0 : st + 1;
-            if constexpr (!XPF) {
-#pragma unroll
-                for (int a = 0; a < WTL; ++a) lf[0][a] = *(const uint4 *)(sL + a * (FS * kFragBytes));
-#pragma unroll
-                for (int q = 0; q < WTR; ++q) rf[0][q] = *(const uint4 *)(sR + q * (FS * kFragBytes));
-            }
-            // The step is cut into FS*WTL phases (one row of the wave's tiles each).  A phase
-            // reads its share of the NEXT fragment from LDS, multiplies one row of the current
-            // fragment, and issues its share of this step's global->LDS transfers, so that
-            // neither LDS reads nor transfer issue ever pile up in front of the MFMAs.  After
-            // the last real step the transfers go on as harmless refills of the one ring
-            // stage nobody reads again (their sources stay valid), which keeps this loop free
-            // of branches.
-            // A fragment is J MFMAs deep (fp32: four k-pairs, bf16: one); the k-pairs are the
-            // outer loop so that consecutive MFMAs go to different accumulators and a tile's
-            // accumulator comes round again only after all the wave's other tiles.
-            constexpr int J = mma_depth<IN>();
-            constexpr int SLOTS = FS * J * WTL;
-#pragma unroll
-            for (int c = 0; c < FS; ++c) {
-                const int cb = c & 1, nb = (c + 1) & 1;
-                const bool more = c + 1 < FS;
-                const char *nL = more ? sL + (c + 1) * kFragBytes : sLw + stn * STAGE;
-                const char *nR = more ? sR + (c + 1) * kFragBytes : sRw + stn * STAGE;
-#pragma unroll
-                for (int j = 0; j < J; ++j) {
-#pragma unroll
-                    for (int a = 0; a < WTL; ++a) {
-                        if (j == 0 && (more || XPF)) {
-                            lf[nb][a] = *(const uint4 *)(nL + a * (FS * kFragBytes));
-                            if (a < WTR) rf[nb][a] = *(const uint4 *)(nR + a * (FS * kFragBytes));
-                            if (a == WTL - 1) {
-#pragma unroll
-                                for (int q = WTL; q < WTR; ++q) rf[nb][q] = *(const uint4 *)(nR + q * (FS * kFragBytes));
-                            }
-                        }
-#pragma unroll
-                        for (int q = 0; q < WTR; ++q) mma_part<IN>(acc[a][q], rf[cb][q], lf[cb][a], j);
-                        const int slot = (c * J + j) * WTL + a;
-#pragma unroll
-                        for (int i = (slot * FPW) / SLOTS; i < ((slot + 1) * FPW) / SLOTS; ++i) copy_issue(i);
-                        // fp32: one fence per k-pair round (a round already touches every accumulator
-                        // once); bf16: one per row of tiles
-                        if (J == 1 || a == WTL - 1) __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-            }
-            st = stn;
-            --pending;
-            if (c_live) copy_advance();
-        }
-
-        // ---- epilogue
-        const TileInfo cur = decode(vb);
-        const int64_t oslot = (int64_t)cur.b * p.o_slot;
-        // compact forms for tiles wholly inside the logical extents; 0: general form
-        const bool interior = (cur.gl0 + TLG) * 32 <= p.FL && (cur.gr0 + TRG) * 32 <= p.FR;
-        int form = 0;
-        if (interior && !p.o_canon) {
-            if (p.epi == LPG_EPI_NONE) form = use_c ? 2 : 1;
-            else if (!use_c) form = (p.epi == LPG_EPI_SILU) ? 3 : (use_e ? 4 : 0);
-        } else if (p.o_canon == 1 && interior && !use_c && p.epi == LPG_EPI_NONE) {
-            form = 5;
-        }
-#define LPG_EPILOGUE_FORM(CALL)                                                                    \
-    static_for<WTL * WTR>([&](auto I) {                                                            \
-        constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;                  \
-        const int grL = cur.gl0 + wl * WTL + a, grR = cur.gr0 + wr * WTR + q;                      \
-        CALL;                                                                                      \
-    })
-        char *Oo = p.Out + oslot;
-        if (form == 1) {
-            LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_NONE>(p, acc[a][q], grL, grR, lane, Oo, nullptr, nullptr)));
-        } else if (form == 2) {
-            LPG_EPILOGUE_FORM((store_tile_plain<OUT, true, LPG_EPI_NONE>(p, acc[a][q], grL, grR, lane, Oo, p.Cin + oslot, nullptr)));
-        } else if (form == 3) {
-            LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_SILU>(p, acc[a][q], grL, grR, lane, Oo, nullptr, nullptr)));
-        } else if (form == 4) {
-            LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_GATE_SILU>(p, acc[a][q], grL, grR, lane, Oo, nullptr, p.Epi + oslot)));
-        } else if (form == 5) {
-            LPG_EPILOGUE_FORM((store_tile_canon_plain<OUT>(p, acc[a][q], grL, grR, lane, Oo)));
-#undef LPG_EPILOGUE_FORM
-        } else {
-            static_for<WTL * WTR>([&](auto I) {
-                constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
-                const int grL = cur.gl0 + wl * WTL + a;
-                const int grR = cur.gr0 + wr * WTR + q;
-                if (grL < p.FLg && grR < p.FRg_out)
-                    store_tile<OUT>(p, acc[a][q], grL, grR, lane, p.Out + oslot, p.Cin + oslot, p.Epi + oslot, use_c,
-                                    use_e);
-            });
-        }
-    }
-    wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
-}
-
-// Tile configurations (TLG, TRG, WL, WR) in 32-groups; index = position in this list.
-struct TileCfg {
-    int tlg, trg, wl, wr;
-};
-static const TileCfg kCfgs[] = {
-    {2, 2, 2, 2},  // 0:  64 x  64, 4 waves of 1x1
-    {4, 2, 2, 2},  // 1: 128 x  64, 4 waves of 2x1
-    {2, 4, 2, 2},  // 2:  64 x 128, 4 waves of 1x2
-    {4, 4, 2, 2},  // 3: 128 x 128, 4 waves of 2x2
-    {8, 4, 2, 2},  // 4: 256 x 128, 4 waves of 4x2
-    {4, 8, 2, 2},  // 5: 128 x 256, 4 waves of 2x4
-    {8, 8, 2, 4},  // 6: 256 x 256, 8 waves of 4x2
-    {8, 2, 4, 1},  // 7: 256 x  64, 4 waves of 2x2
-};
-constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
-
-// Staging ring per input type and tile: fp32 moves whole K blocks through two stages (its
-// MFMAs are slow enough to cover memory latency); bf16 moves half blocks through a ring of
-// four stages (three where four would keep a second workgroup off the compute unit) and
-// reads the next step's first fragment ahead.
-constexpr int ring_fs(bool bf16) { return bf16 ? 2 : 4; }
-constexpr int ring_ns(bool bf16, int tlg, int trg, int nw)
-{
-    if (!bf16) return 2;
-    const int stage = (tlg + trg) * 2 * kFragBytes;
-    if (nw == 8) return 5 * stage <= 160 * 1024 ? 5 : 4;  // one workgroup per compute unit: use all the LDS
-    return 4 * stage <= 80 * 1024 ? 4 : 3;
-}
-
-// fp32 with small tiles and no more tiles than compute units: a step's MFMAs (2048 cycles
-// for a 128 x 64 tile) are shorter than the memory latency under load, and no second
-// workgroup shares the compute unit to cover for it, so the ring is made deeper instead: as
-// deep as the whole LDS allows, the lone workgroup has it to itself.
-constexpr int ring_ns_lone(int tlg, int trg)
-{
-    const int stage = (tlg + trg) * 4 * kFragBytes;
-    return 4 * stage <= 160 * 1024 ? 4 : (3 * stage <= 160 * 1024 ? 3 : 2);
-}
-
-static int lds_bytes(const TileCfg &c, bool bf16)
-{
-    return ring_ns(bf16, c.tlg, c.trg, c.wl * c.wr) * (c.tlg + c.trg) * ring_fs(bf16) * kFragBytes;
-}
-
-static int workgroups_per_cu(const TileCfg &c, bool bf16)
-{
-    int occ = (160 * 1024) / lds_bytes(c, bf16);
-    const int waves = c.wl * c.wr;
-    // accumulators + operand registers per lane decide how many waves fit a SIMD
-    const int regs = (c.tlg / c.wl) * (c.trg / c.wr) * 16 + 64;
-    const int waves_per_simd = regs > 256 ? 1 : (regs > 128 ? 2 : 4);
-    const int by_regs = waves_per_simd * 4 / waves;
-    if (occ > by_regs) occ = by_regs;
-    if (occ > 4) occ = 4;
-    return occ < 1 ? 1 : occ;
-}
-
-template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR, int NS, int FSX = 0>
-static hipError_t launch_gemm_ring(const GemmArgs &a, int64_t grid, hipStream_t st)
-{
-    constexpr int NT = WL * WR * 64;
-    constexpr bool BF = IN::ES == 2;
-    constexpr int FS = FSX ? FSX : ring_fs(BF);
-    constexpr size_t lds = (size_t)NS * (TLG + TRG) * FS * kFragBytes;
-    static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
-    auto kern = gemm_kernel<IN, OUT, TLG, TRG, WL, WR, FS, NS, (BF && NS >= 3)>;
-    if (lds > 64 * 1024) {
-        static bool done = false;  // per instantiation
-        if (!done) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            done = true;
-        }
-    }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, st, a);
-    return hipGetLastError();
-}
-
-template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR>
-static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
-{
-    constexpr bool BF = IN::ES == 2;
-    constexpr int NS = ring_ns(BF, TLG, TRG, WL * WR), NS_LONE = BF ? NS : ring_ns_lone(TLG, TRG);
-    a.tiles_l = (a.FLg + TLG - 1) / TLG;
-    a.tiles_r = (a.FRg_out + TRG - 1) / TRG;
-    const int64_t total = (int64_t)a.tiles_l * a.tiles_r * a.batch;
-    if (total <= 0) return hipSuccess;
-    if (total > 0x7fffffff) return hipErrorInvalidValue;  // the kernel counts tiles in 32 bits
-    const TileCfg c = {TLG, TRG, WL, WR};
-    int64_t grid = (int64_t)256 * workgroups_per_cu(c, BF);
-    if (grid > total) grid = total;
-    // Band height of the tile walk.  An XCD works on a contiguous range of tile ids, gm tile rows x
-    // (range / gm) tile columns at a time, and fetches gm row panels and range / gm column panels
-    // into its L2: take the height that makes the sum of their bytes smallest.
-    {
-        const int64_t range = (grid < total ? grid : total) / 8 > 0 ? (grid < total ? grid : total) / 8 : 1;
-        int best = 8;
-        int64_t best_cost = -1;
-        for (int gm : {8, 4, 2, 16}) {
-            const int64_t rows = gm < a.tiles_l ? gm : a.tiles_l;
-            const int64_t cols = (range + rows - 1) / rows < a.tiles_r ? (range + rows - 1) / rows : a.tiles_r;
-            const int64_t cost = rows * TLG + cols * TRG;
-            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = gm; }
-        }
-        static const int force = [] { const char *e = getenv("LPG_GM"); return e ? atoi(e) : 0; }();
-        a.gm = force > 0 ? force : best;
-    }
-    if constexpr (NS_LONE != NS) {
-        if (total <= 256) {
-            // Small lone tiles: a step of one K block is 2048-4096 MFMA cycles and every step ends
-            // at a workgroup barrier that costs about 290 of them (no second wave on the SIMD to
-            // fill the gap), so an even number of K blocks is walked two per step.
-            constexpr int STAGE2 = (TLG + TRG) * 8 * kFragBytes;
-            constexpr int NS2 = 4 * STAGE2 <= 160 * 1024 ? 4 : (3 * STAGE2 <= 160 * 1024 ? 3 : 2);
-            if constexpr (!BF && TLG * TRG <= 16) {
-                static const int two = [] { const char *e = getenv("LPG_TWO_BLOCK_STEPS"); return e ? atoi(e) : 1; }();
-                if (two && a.nkb % 2 == 0 && a.nkb >= 4)
-                    return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS2, 8>(a, grid, st);
-            }
-            return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS_LONE>(a, grid, st);
-        }
-    }
-    if constexpr (BF && TLG * TRG <= 8) {
-        // bf16, small lone tiles: a half-block step is 64-256 MFMA cycles, far less than the
-        // barrier that ends it; two whole K blocks per step (four times fewer barriers), in as
-        // many stages as the LDS holds (the next-step prefetch needs three).
-        constexpr int STAGE2 = (TLG + TRG) * 8 * kFragBytes;
-        constexpr int NS2 = 5 * STAGE2 <= 160 * 1024 ? 5 : (4 * STAGE2 <= 160 * 1024 ? 4 : 3);
-        static_assert(NS2 * STAGE2 <= 160 * 1024, "two-block stages of the small tiles fit three times");
-        static const int two = [] { const char *e = getenv("LPG_TWO_BLOCK_STEPS"); return e ? atoi(e) : 1; }();
-        if (two && total <= 256 && a.nkb % 2 == 0 && a.nkb >= 4)
-            return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS2, 8>(a, grid, st);
-    }
-    if constexpr (BF && TLG * TRG >= 8 && TLG * TRG <= 16 && WL * WR == 4) {
-        // bf16 tiles of 128 x 64 to 128 x 128 (several workgroups per compute unit): whole K
-        // blocks per step in two stages, without the next-step prefetch, instead of half blocks
-        // in four stages with it: half the barriers in the same LDS; measured 2-8 % faster on
-        // 2048^3, 4096 x 2048 x 2048, 16384 x 1024 x 1024 and ragged shapes.  LPG_BF16_FS4=0
-        // restores the half-block ring (tuning aid).
-        static const int fs4 = [] { const char *e = getenv("LPG_BF16_FS4"); return e ? atoi(e) : 1; }();
-        if (fs4) return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, 2, 4>(a, grid, st);
-    }
-    return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS>(a, grid, st);
 }
 
 }  // namespace lpg

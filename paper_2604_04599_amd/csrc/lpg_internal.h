@@ -16,6 +16,26 @@ constexpr int kFragBytes = 1024;
 constexpr int kBlockBytes = 4096;
 constexpr int kFragsPerBlock = 4;
 
+// Tuning and test hooks (lpg_tune_set): process-wide, -1 = the library's own choice.
+int tune_get(int key);
+int tune_set(int key, int value);  // 0, or -1 for an unknown key
+
+// What the library needs to know of the device a launch goes to, queried once per device.
+struct DeviceInfo {
+    int ncu;        // compute units
+    int lds_bytes;  // LDS a workgroup may use
+};
+const DeviceInfo &device_info();
+
+// True the first time it is called for (flag, current device): guards per-device, per-kernel
+// set-up such as hipFuncSetAttribute.  Safe to call from several threads (the set-up it guards is
+// idempotent, so two threads doing it once each is harmless).
+struct PerDeviceFlag {
+    unsigned long long done[2] = {0, 0};  // one bit per device ordinal (up to 128)
+};
+bool first_use_on_device(PerDeviceFlag &f);
+void mark_used_on_device(PerDeviceFlag &f);
+
 inline int elem_size(int dtype) { return dtype == LPG_F32 ? 4 : 2; }
 inline int kb_of(int dtype) { return dtype == LPG_F32 ? 32 : 64; }  // K extent of a block
 
@@ -97,7 +117,8 @@ struct GemmArgs {
 struct EwArgs {
     const char *x0, *x1;
     char *out;
-    int64_t n16;  // number of 16-byte chunks
+    int64_t n16;  // number of whole 16-byte chunks
+    int32_t tail; // elements after the last whole chunk (tight canonical buffers of odd sizes)
     int32_t op;
     float s;
 };
@@ -150,6 +171,10 @@ hipError_t launch_pack(const PackArgs &a, int src_dtype, int dst_dtype, hipStrea
 hipError_t launch_unpack(const PackArgs &a, int src_dtype, int dst_dtype, hipStream_t st);
 // cfg < 0 lets the library choose the tile configuration.
 hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, int cfg, hipStream_t st);
+// One translation unit per dtype pair (lpg_gemm_*.hip); cfg is a valid tile configuration index.
+hipError_t launch_gemm_f32(const GemmArgs &a, int cfg, hipStream_t st);
+hipError_t launch_gemm_bf16(const GemmArgs &a, int cfg, hipStream_t st);
+hipError_t launch_gemm_bf16_f32(const GemmArgs &a, int cfg, hipStream_t st);
 int choose_gemm_config(const GemmArgs &a, int in_dtype);
 hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st);
 hipError_t launch_row_op(const RowArgs &a, int op, int dtype, bool packed, hipStream_t st);

@@ -1,4 +1,5 @@
-// Device code of the GPU path: pack / unpack / elementwise / MFMA GEMM for gfx950.
+// Device code of the GPU path for gfx950: pack / unpack / elementwise / row operations / RoPE /
+// fused attention, and the choice of the GEMM tile configuration.
 //
 // Packed layout (see include/lpg.h): blocks of 4 KiB = 32 free indices x KB
 // contraction indices, each made of four 1 KiB fragments; a fragment is the
@@ -7,8 +8,63 @@
 
 
 #include "lpg_device.h"
+#include "lpg_tiles.h"
 
 namespace lpg {
+
+// ---------------------------------------------------------------------------------
+// Process-wide state: tuning hooks, per-device facts.
+
+static int g_tune[LPG_TUNE_KEYS] = {-1, -1, -1, -1, -1, -1, -1};
+
+int tune_get(int key) { return __atomic_load_n(&g_tune[key], __ATOMIC_RELAXED); }
+
+int tune_set(int key, int value)
+{
+    if (key < 0 || key >= LPG_TUNE_KEYS) return -1;
+    __atomic_store_n(&g_tune[key], value < 0 ? -1 : value, __ATOMIC_RELAXED);
+    return 0;
+}
+
+constexpr int kMaxDevices = 128;
+
+static int current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+    return dev;
+}
+
+const DeviceInfo &device_info()
+{
+    // filled once per device; a race between two first callers writes the same values twice
+    static DeviceInfo info[kMaxDevices];
+    static unsigned char known[kMaxDevices];
+    const int dev = current_device();
+    if (!__atomic_load_n(&known[dev], __ATOMIC_ACQUIRE)) {
+        int ncu = 0, lds = 0;
+        if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu <= 0) ncu = 256;
+        // the LDS of one compute unit: what a single resident workgroup can be given
+        if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess || lds < 64 * 1024)
+            lds = 64 * 1024;
+        info[dev].ncu = ncu;
+        info[dev].lds_bytes = lds;
+        __atomic_store_n(&known[dev], 1, __ATOMIC_RELEASE);
+    }
+    return info[dev];
+}
+
+bool first_use_on_device(PerDeviceFlag &f)
+{
+    const int dev = current_device();
+    return !((__atomic_load_n(&f.done[dev / 64], __ATOMIC_ACQUIRE) >> (dev % 64)) & 1ull);
+}
+
+void mark_used_on_device(PerDeviceFlag &f)
+{
+    const int dev = current_device();
+    __atomic_fetch_or(&f.done[dev / 64], 1ull << (dev % 64), __ATOMIC_RELEASE);
+}
 
 // Launch limits of HIP: a request past them is reported, never narrowed.
 constexpr int64_t kMaxGridX = 0x7fffffff, kMaxGridYZ = 65535;
@@ -286,13 +342,27 @@ __global__ __launch_bounds__(256) void ew_kernel(EwArgs a)
         }
         ((uint4 *)a.out)[i] = make_uint4(r[0], r[1], r[2], r[3]);
     }
+    // elements past the last whole 16-byte chunk (tight canonical buffers of odd sizes only:
+    // packed buffers are whole blocks)
+    if (blockIdx.x == 0 && (int)threadIdx.x < a.tail) {
+        const int64_t e = a.n16 * (16 / T::ES) + threadIdx.x;
+        typedef typename T::raw raw;
+        const raw x0 = ((const raw *)a.x0)[e];
+        const raw x1 = a.x1 ? ((const raw *)a.x1)[e] : (raw)0;
+        if constexpr (T::ES == 4) {
+            ((raw *)a.out)[e] = __float_as_uint(ew_apply(a.op, __uint_as_float(x0), __uint_as_float(x1), a.s));
+        } else {
+            ((raw *)a.out)[e] = (raw)bf16_rne(ew_apply(a.op, bf16_to_f32(x0), bf16_to_f32(x1), a.s));
+        }
+    }
 }
 
 hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st)
 {
-    if (a.n16 <= 0) return hipSuccess;
+    if (a.n16 <= 0 && a.tail <= 0) return hipSuccess;
     int64_t blocks = (a.n16 + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks > (int64_t)device_info().ncu * 16) blocks = (int64_t)device_info().ncu * 16;
+    if (blocks < 1) blocks = 1;
     if (dtype == LPG_F32)
         hipLaunchKernelGGL((ew_kernel<F32>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     else
@@ -627,8 +697,8 @@ static hipError_t launch_row_dtype(const RowArgs &a, bool packed, hipStream_t st
         return hipGetLastError();
     }
     // Variants: rows per workgroup, waves, cached.  A cached variant holds rows of up to
-    // 128 * waves / R K blocks (16 chunks a lane).  LPG_ROW_VARIANT=<n> pins the choice if
-    // that variant can hold the rows (a tuning aid).
+    // 128 * waves / R K blocks (16 chunks a lane).  The tuning hook LPG_TUNE_ROW_VARIANT pins the
+    // choice if that variant can hold the rows.
     struct Variant { int r, nw; bool cached; };
     static const Variant kVariants[] = {{32, 8, true}, {16, 8, true}, {8, 8, true}, {8, 16, true},
                                         {8, 8, false}, {32, 4, true}};
@@ -639,8 +709,8 @@ static hipError_t launch_row_dtype(const RowArgs &a, bool packed, hipStream_t st
     const int64_t groups = (int64_t)a.batch * a.ngroups;
     while ((variant == 5 || variant == 0 || variant == 1) && groups * (32 / kVariants[variant].r) < 512)
         variant = variant == 5 ? 0 : variant + 1;
-    if (const char *f = getenv("LPG_ROW_VARIANT")) {
-        const int v = atoi(f);
+    {
+        const int v = tune_get(LPG_TUNE_ROW_VARIANT);
         if (v >= 0 && v < 6 && fits(v)) variant = v;
     }
     if ((int64_t)a.batch * a.ngroups * (32 / kVariants[variant].r) > kMaxGridX) return hipErrorInvalidConfiguration;
@@ -1052,12 +1122,13 @@ static hipError_t launch_attention_dh(const AttnArgs &a, hipStream_t st)
     constexpr size_t lds = 2 * (size_t)NF * kFragBytes;
     static_assert(lds <= 160 * 1024, "ring does not fit the LDS");
     auto kern = attention_kernel<T, DH, SOFTMAX, QG>;
+    if (lds > (size_t)device_info().lds_bytes) return hipErrorInvalidConfiguration;
     if (lds > 64 * 1024) {
-        static bool done = false;
-        if (!done) {
+        static PerDeviceFlag raised;
+        if (first_use_on_device(raised)) {
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
-            done = true;
+            mark_used_on_device(raised);
         }
     }
     const int nqb = (a.q_groups + 4 * QG - 1) / (4 * QG);
@@ -1070,15 +1141,16 @@ static hipError_t launch_attention_dh(const AttnArgs &a, hipStream_t st)
 // Two query groups per wave pay only where a launch keeps several workgroups per compute
 // unit even so and all of them do the same work: bf16, head_dim 64, no causal mask, at least
 // 512 workgroups (measured 113 against 123 us on 32 heads x 4096 x 4096; under a causal mask the
-// larger blocks lose more to imbalance than the reuse gives).  LPG_ATTN_QG=1|2 pins the choice
-// for head_dim 64 (a tuning and test aid).
+// larger blocks lose more to imbalance than the reuse gives).  The tuning hook LPG_TUNE_ATTN_QUERY_GROUPS (1 or 2)
+// pins the choice for head_dim 64.
 template <typename T, int DH>
 static hipError_t launch_attention_mode(const AttnArgs &a, hipStream_t st)
 {
     if constexpr (DH == 64) {
         const int64_t wgs2 = (int64_t)((a.q_groups + 7) / 8) * a.batch;
         int qg = (T::ES == 2 && !a.causal && wgs2 >= 512) ? 2 : 1;
-        if (const char *f = getenv("LPG_ATTN_QG")) qg = atoi(f) == 2 ? 2 : 1;
+        const int force = tune_get(LPG_TUNE_ATTN_QUERY_GROUPS);
+        if (force == 1 || force == 2) qg = force;
         if (qg == 2)
             return a.softmax ? launch_attention_dh<T, DH, true, 2>(a, st) : launch_attention_dh<T, DH, false, 2>(a, st);
     }
@@ -1104,7 +1176,7 @@ static double estimate_cost(const GemmArgs &a, const TileCfg &c, bool bf16)
 {
     const int64_t tl = (a.FLg + c.tlg - 1) / c.tlg, tr = (a.FRg_out + c.trg - 1) / c.trg;
     const int64_t tiles = tl * tr * a.batch;
-    const int ncu = 256;
+    const int ncu = device_info().ncu;
     const int occ = workgroups_per_cu(c, bf16);
     const int64_t per_cu = (tiles + ncu - 1) / ncu;  // tiles the busiest CU runs
     const int wtl = c.tlg / c.wl, wtr = c.trg / c.wr;
@@ -1114,7 +1186,7 @@ static double estimate_cost(const GemmArgs &a, const TileCfg &c, bool bf16)
     const int resident = (int)((per_cu < occ ? per_cu : occ) * waves_per_simd);  // waves per SIMD
     // one bf16 wave per SIMD stalls at every barrier of its short steps, unless the launch
     // qualifies for two K blocks per step (launch_gemm_cfg)
-    const bool two_block = tiles <= 256 && c.tlg * c.trg <= 8 && nkb % 2 == 0 && nkb >= 4;
+    const bool two_block = tiles <= ncu && c.tlg * c.trg <= 8 && nkb % 2 == 0 && nkb >= 4;
     double eff = resident >= 2 ? 1.0 : (bf16 ? (two_block ? 0.9 : 0.6) : 1.0);
     const double reads_per_mma = (double)(wtl + wtr) / (wtl * wtr);
     eff /= 1.0 + (bf16 ? 0.217 : 0.0525) * reads_per_mma;
@@ -1122,22 +1194,6 @@ static double estimate_cost(const GemmArgs &a, const TileCfg &c, bool bf16)
     const double traffic = (double)per_cu * nkb * (c.tlg + c.trg) * 205.0 * (bf16 ? 0.141 : 0.0805);
     const double fixed = (double)per_cu * (c.tlg * c.trg * (bf16 ? 60.0 : 32.0) + 2228.0);
     return mfma + traffic + fixed;
-}
-
-template <typename IN, typename OUT>
-static hipError_t launch_gemm_dtype(const GemmArgs &a, int cfg, hipStream_t st)
-{
-    switch (cfg) {
-        case 0: return launch_gemm_cfg<IN, OUT, 2, 2, 2, 2>(a, st);
-        case 1: return launch_gemm_cfg<IN, OUT, 4, 2, 2, 2>(a, st);
-        case 2: return launch_gemm_cfg<IN, OUT, 2, 4, 2, 2>(a, st);
-        case 3: return launch_gemm_cfg<IN, OUT, 4, 4, 2, 2>(a, st);
-        case 4: return launch_gemm_cfg<IN, OUT, 8, 4, 2, 2>(a, st);
-        case 5: return launch_gemm_cfg<IN, OUT, 4, 8, 2, 2>(a, st);
-        case 6: return launch_gemm_cfg<IN, OUT, 8, 8, 2, 4>(a, st);
-        case 7: return launch_gemm_cfg<IN, OUT, 8, 2, 4, 1>(a, st);
-        default: return hipErrorInvalidValue;
-    }
 }
 
 int choose_gemm_config(const GemmArgs &a, int in_dtype)
@@ -1169,11 +1225,11 @@ int choose_gemm_config(const GemmArgs &a, int in_dtype)
 hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, int cfg, hipStream_t st)
 {
     if (cfg < 0 || cfg >= kNumCfgs) cfg = choose_gemm_config(a, in_dtype);
-    if (getenv("LPG_TRACE_TILE"))
+    if (tune_get(LPG_TUNE_TRACE) > 0)
         fprintf(stderr, "lpg gemm: FL %d FR %d nkb %d batch %d -> tile configuration %d\n", a.FL, a.FR, a.nkb, a.batch, cfg);
-    if (in_dtype == LPG_F32 && out_dtype == LPG_F32) return launch_gemm_dtype<F32, F32>(a, cfg, st);
-    if (in_dtype == LPG_BF16 && out_dtype == LPG_BF16) return launch_gemm_dtype<BF16, BF16>(a, cfg, st);
-    if (in_dtype == LPG_BF16 && out_dtype == LPG_F32) return launch_gemm_dtype<BF16, F32>(a, cfg, st);
+    if (in_dtype == LPG_F32 && out_dtype == LPG_F32) return launch_gemm_f32(a, cfg, st);
+    if (in_dtype == LPG_BF16 && out_dtype == LPG_BF16) return launch_gemm_bf16(a, cfg, st);
+    if (in_dtype == LPG_BF16 && out_dtype == LPG_F32) return launch_gemm_bf16_f32(a, cfg, st);
     return hipErrorInvalidValue;
 }
 

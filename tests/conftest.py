@@ -19,3 +19,17 @@ def oracle_lib():
     from oracle import ref
     ref.lib()
     return ref
+
+
+@pytest.fixture
+def tune():
+    """Pin one of the library's per-launch choices (lpg_tune_set) for the duration of a test."""
+    from paper_2604_04599_amd import api
+    touched = []
+
+    def set_(key, value):
+        api.lpg_tune_set(key, value)
+        touched.append(key)
+    yield set_
+    for key in touched:
+        api.lpg_tune_set(key, api.LPG_TUNE_AUTO)

@@ -45,12 +45,12 @@ def oracle_attention(q, k, v, scale, causal):
 SHAPES = [(32, 64, 64), (1, 1, 64), (70, 70, 64), (200, 333, 64), (300, 100, 64), (130, 4200, 64), (257, 257, 128)]
 
 
-@pytest.mark.parametrize("qg", ["1", "2"])
+@pytest.mark.parametrize("qg", [1, 2])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("dtype", [LPG_F32, LPG_BF16])
 @pytest.mark.parametrize("tq,tk,dh", SHAPES)
-def test_attention_matches_oracle(tq, tk, dh, dtype, causal, qg, monkeypatch):
-    monkeypatch.setenv("LPG_ATTN_QG", qg)              # one or two 32-query groups per wave (head_dim 64)
+def test_attention_matches_oracle(tq, tk, dh, dtype, causal, qg, tune):
+    tune(api.LPG_TUNE_ATTN_QUERY_GROUPS, qg)            # one or two 32-query groups per wave (head_dim 64)
     rng = np.random.default_rng(tq * 7 + tk + dh)
     q, k, v = (rng.standard_normal((n, dh)).astype(np.float32) for n in (tq, tk, tk))
     got, qs, ks, vs = run_attention(q, k, v, dtype, dh ** -0.5, causal)

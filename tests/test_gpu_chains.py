@@ -251,6 +251,34 @@ def test_three_gemm_chains_of_unequal_widths(m, widths, dtype):
     assert np.array_equal(fch.output("Y").view(np.uint32), prop.view(np.uint32))
 
 
+@pytest.mark.parametrize("dtype", [api.LPG_F32, api.LPG_BF16])
+@pytest.mark.parametrize("m,k,n", [(33, 35, 35), (1, 1, 1), (70, 100, 100)])
+def test_elementwise_stage_of_odd_sizes_in_both_modes(m, k, n, dtype):
+    """GEMM -> SCALE -> ADD -> GEMM with extents that make the control's tight row-major copies end
+    off a 16-byte boundary: both modes run and agree bit for bit, and match the oracle."""
+    rng = np.random.default_rng(m + k)
+    A = inputs._bf16_representable(rng.standard_normal((m, k), dtype=np.float32))
+    B = inputs._bf16_representable(rng.standard_normal((k, n), dtype=np.float32) / np.float32(np.sqrt(k)))
+    ch = chains.Chain("odd", {}, 0)
+    a_d, c_d = api.desc(api.LPG_PACKED_A, dtype, m, k), api.desc(api.LPG_PACKED_A, dtype, m, n)
+    y_d = api.desc(api.LPG_PACKED_A, api.LPG_F32, m, n)
+    xa = ch.inputs["A"] = chains.device_array(A)
+    _, b_d = ch.pack_weight("B", B, api.LPG_PACKED_B, dtype)
+    pa, c1, c2, c3, py = (ch.new_packed(nm, d) for nm, d in (("A", a_d), ("C1", c_d), ("C2", c_d), ("C3", c_d), ("Y", y_d)))
+    out = ch.outputs["Y"] = torch.empty((m, n), dtype=torch.float32, device="cuda")
+    rm_a, rm_y = api.desc(api.LPG_ROW_MAJOR, api.LPG_F32, m, k), api.desc(api.LPG_ROW_MAJOR, api.LPG_F32, m, n)
+    ch.add(api.stage_pack(xa, rm_a, pa, a_d))
+    ch.add(api.stage_gemm(1.0, pa, a_d, ch.bufs["B"][0], b_d, 0.0, None, c1, c_d))
+    ch.add(api.stage_elementwise(api.LPG_EW_SCALE, c1, None, 0.5, c2, c_d))
+    ch.add(api.stage_elementwise(api.LPG_EW_ADD, c1, c2, 2.0, c3, c_d))
+    ch.add(api.stage_gemm(1.0, c3, c_d, ch.bufs["B"][0], b_d, 0.0, None, py, y_d))
+    ch.add(api.stage_unpack(py, y_d, out, rm_y))
+    prop, canon = run_both_modes(ch, "Y")
+    assert np.array_equal(prop.view(np.uint32), canon.view(np.uint32))
+    want = ref.gemm(2.0 * ref.gemm(A, B), B)
+    assert ref.rel_frobenius(prop, want) <= (3 * F32_TOL if dtype == api.LPG_F32 else BF16_TOL)
+
+
 @pytest.mark.parametrize("name,over,out", [("two_gemm", dict(), "C2"), ("mlp", dict(m=160, d=96, h=224), "Y"),
                                            ("attention", dict(heads=3, t=160, dh=64), "O")])
 def test_graph_replay_matches_eager(name, over, out):

@@ -203,13 +203,13 @@ def test_elementwise_ops(dtype):
 
 
 @pytest.mark.parametrize("cfg", range(8))
-def test_every_tile_configuration(cfg, monkeypatch):
-    """Each tile configuration of the GEMM kernel, forced through LPG_FORCE_TILE, on shapes
+def test_every_tile_configuration(cfg, tune):
+    """Each tile configuration of the GEMM kernel, forced through the LPG_TUNE_TILE hook, on shapes
     that span several tiles, a ragged tail and several tiles per persistent workgroup.  The
     first two shapes have at most 256 tiles (fp32 then runs its deeper staging ring), the
     third more than 256 tiles in every configuration up to 128 x 128, the fourth at most 256
     tiles and an even number of K blocks (fp32 then walks two K blocks per step)."""
-    monkeypatch.setenv("LPG_FORCE_TILE", str(cfg))
+    tune(api.LPG_TUNE_TILE, cfg)
     rng = np.random.default_rng(100 + cfg)
     for (m, n, k) in [(300, 520, 200), (70, 40, 33), (2100, 2100, 96), (200, 330, 256)]:
         A = rng.uniform(-1, 1, (m, k)).astype(np.float32)

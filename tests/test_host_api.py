@@ -222,3 +222,36 @@ def test_chain_link_check_and_workspace():
     with pytest.raises(api.LpgError) as e:
         api.lpg_chain(stages, api.LPG_CHAIN_CANONICAL, None, 0)
     assert e.value.code == api.LPG_EWORKSPACE
+
+
+def test_tune_hooks_round_trip_and_reject_unknown_keys():
+    for key in range(7):
+        assert api.lpg_tune_get(key) == api.LPG_TUNE_AUTO
+    api.lpg_tune_set(api.LPG_TUNE_TILE, 3)
+    assert api.lpg_tune_get(api.LPG_TUNE_TILE) == 3
+    api.lpg_tune_set(api.LPG_TUNE_TILE, api.LPG_TUNE_AUTO)
+    assert api.lpg_tune_get(api.LPG_TUNE_TILE) == api.LPG_TUNE_AUTO
+    for bad in (-1, 7, 100):
+        with pytest.raises(api.LpgError) as e:
+            api.lpg_tune_set(bad, 1)
+        assert e.value.code == api.LPG_EINVAL
+
+
+def test_control_chain_of_odd_sizes_is_validated_before_launch():
+    """GEMM -> SCALE -> GEMM on 33 x 35 fp32: the control runs the elementwise stage on a tight
+    row-major copy whose size is not a multiple of 16 bytes.  The dry pass that sizes the workspace
+    validates that stage as well (fake, never dereferenced addresses), and accepts it."""
+    m, k, n = 33, 35, 35
+    a_d, b_d, c_d = desc(LPG_PACKED_A, LPG_F32, m, k), desc(LPG_PACKED_B, LPG_F32, k, n), desc(LPG_PACKED_A, LPG_F32, m, n)
+    A, B, C1, C2, C3 = (0x10000 * (i + 1) for i in range(5))
+    stages = [api.stage_gemm(1.0, A, a_d, B, b_d, 0.0, None, C1, c_d),
+              api.stage_elementwise(api.LPG_EW_SCALE, C1, None, 0.5, C2, c_d),
+              api.stage_gemm(1.0, C2, c_d, B, b_d, 0.0, None, C3, c_d)]
+    need = api.lpg_chain_workspace_bytes(stages, api.LPG_CHAIN_CANONICAL)
+    assert need >= 2 * m * n * 4
+    assert api.lpg_chain_workspace_bytes(stages, api.LPG_CHAIN_PROPAGATED) == 0
+    # a stage the control could not run (misaligned x1) is reported by the same dry pass
+    bad = list(stages)
+    bad[1] = api.stage_elementwise(api.LPG_EW_ADD, C1, C2 + 4, 0.5, C2, c_d)
+    with pytest.raises(api.LpgError):
+        api.lpg_chain_workspace_bytes(bad, api.LPG_CHAIN_CANONICAL)
