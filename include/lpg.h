@@ -341,6 +341,26 @@ int lpg_chain(const lpg_stage *stages, int n, int mode, void *workspace,
               size_t workspace_bytes, void *stream);
 
 /*
+ * lpg_chain_static - lpg_chain for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same stages, same modes, same kernels and same results as lpg_chain; the
+ * row-major copies of LPG_CHAIN_CANONICAL live in a static device array of the library
+ * (LPG_STATIC_SCRATCH_BYTES, one copy per GPU the library runs on, held until the process
+ * ends) instead of a caller's workspace.  The call allocates nothing and frees nothing.
+ *   A chain whose lpg_chain_workspace_bytes exceeds LPG_STATIC_SCRATCH_BYTES is refused with
+ *   LPG_EWORKSPACE before anything is launched.  LPG_CHAIN_PROPAGATED needs no scratch at all.
+ *   The device that is current at the call must be the stream's device; the address of that
+ *   device's copy of the array is looked up on the first call per device (the one call that
+ *   should not be made while a capture is in progress) and kept.
+ *   All calls on one GPU share that GPU's array, and nothing in it needs to start at zero
+ *   (every byte a stage reads there was written by an earlier stage of the same call), so
+ *   calls on one stream may follow each other freely, but calls that overlap in time on one
+ *   GPU (different streams, or graphs replayed concurrently) race on it.
+ */
+#define LPG_STATIC_SCRATCH_BYTES (64u << 20)
+int lpg_chain_static(const lpg_stage *stages, int n, int mode, void *stream);
+
+/*
  * Tuning and test hooks.  Every choice the library makes per launch (tile configuration, band
  * height of the tile walk, staging-ring variants, row-kernel variant) can be pinned for
  * measurements and for tests that must reach every variant; -1 (LPG_TUNE_AUTO) gives the choice

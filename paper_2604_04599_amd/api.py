@@ -24,6 +24,7 @@ LPG_ATTN_CAUSAL, LPG_ATTN_NO_SOFTMAX = 1, 2
 (LPG_TUNE_TILE, LPG_TUNE_BAND, LPG_TUNE_TWO_BLOCK_STEPS, LPG_TUNE_BF16_WHOLE_BLOCK_STEPS, LPG_TUNE_ROW_VARIANT,
  LPG_TUNE_ATTN_QUERY_GROUPS, LPG_TUNE_TRACE) = range(7)
 LPG_TUNE_AUTO = -1
+LPG_STATIC_SCRATCH_BYTES = 64 << 20
 
 ELEM_SIZE = {LPG_F32: 4, LPG_BF16: 2}
 
@@ -101,6 +102,8 @@ def lib():
         L.lpg_chain_workspace_bytes.restype = ctypes.c_size_t
         L.lpg_chain.argtypes = [sp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp]
         L.lpg_chain.restype = ctypes.c_int
+        L.lpg_chain_static.argtypes = [sp, ctypes.c_int, ctypes.c_int, vp]
+        L.lpg_chain_static.restype = ctypes.c_int
         L.lpg_tune_set.argtypes = [ctypes.c_int, ctypes.c_int]
         L.lpg_tune_set.restype = ctypes.c_int
         L.lpg_tune_get.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
@@ -113,7 +116,7 @@ def lib():
 
 EXPORTS = ("lpg_packed_bytes", "lpg_layout_offset", "lpg_pack", "lpg_unpack", "lpg_gemm_packed",
            "lpg_elementwise_packed", "lpg_softmax_packed", "lpg_attention_packed", "lpg_rmsnorm_packed", "lpg_rope_tables", "lpg_rope_packed",
-           "lpg_chain_workspace_bytes", "lpg_chain", "lpg_tune_set", "lpg_tune_get", "lpg_last_error",
+           "lpg_chain_workspace_bytes", "lpg_chain", "lpg_chain_static", "lpg_tune_set", "lpg_tune_get", "lpg_last_error",
            "lpg_version")
 
 
@@ -224,6 +227,11 @@ def lpg_chain_workspace_bytes(stages, mode):
 def lpg_chain(stages, mode=LPG_CHAIN_PROPAGATED, workspace=None, workspace_bytes=0, stream=None):
     arr = stages if isinstance(stages, ctypes.Array) else stage_array(stages)
     return _check(lib().lpg_chain(arr, len(arr), mode, _ptr(workspace), workspace_bytes, stream))
+
+
+def lpg_chain_static(stages, mode=LPG_CHAIN_PROPAGATED, stream=None):
+    arr = stages if isinstance(stages, ctypes.Array) else stage_array(stages)
+    return _check(lib().lpg_chain_static(arr, len(arr), mode, stream))
 
 
 def lpg_tune_set(key, value):

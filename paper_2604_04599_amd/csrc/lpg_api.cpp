@@ -1037,6 +1037,22 @@ int lpg_chain(const lpg_stage *stages, int n, int mode, void *workspace, size_t 
     return chain_canonical(stages, n, (char *)workspace, workspace_bytes, hs, false, nullptr);
 }
 
+int lpg_chain_static(const lpg_stage *stages, int n, int mode, void *stream)
+{
+    if (mode == LPG_CHAIN_PROPAGATED) return lpg_chain(stages, n, mode, nullptr, 0, stream);
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    hipError_t e = static_scratch(&ws, &ws_bytes);
+    if (e != hipSuccess) return fail(LPG_EHIP, "lpg_chain_static: %s", hipGetErrorString(e));
+    int rc = lpg_chain(stages, n, mode, ws, ws_bytes, stream);
+    if (rc == LPG_EWORKSPACE) {
+        char msg[sizeof(g_err)];
+        snprintf(msg, sizeof(msg), "%s", g_err);
+        return fail(LPG_EWORKSPACE, "lpg_chain_static: the chain's row-major copies do not fit the library's %zu-byte static scratch (%s)", ws_bytes, msg);
+    }
+    return rc;
+}
+
 int lpg_tune_set(int key, int value)
 {
     if (tune_set(key, value)) return fail(LPG_EINVAL, "lpg_tune_set: unknown key %d", key);

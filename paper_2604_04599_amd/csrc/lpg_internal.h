@@ -183,4 +183,8 @@ hipError_t launch_rope_tables(float *cos_t, float *sin_t, int64_t rows, int head
 hipError_t launch_rope(const RopeArgs &a, int dtype, bool packed, hipStream_t st);
 hipError_t launch_attention(const AttnArgs &a, int dtype, int head_dim, hipStream_t st);
 
+// The library's own device scratch (lpg_chain_static): address of the current device's copy and
+// its size.  Allocates nothing.
+hipError_t static_scratch(void **ptr, size_t *bytes);
+
 }  // namespace lpg

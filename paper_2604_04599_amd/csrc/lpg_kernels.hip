@@ -1,5 +1,5 @@
 // Device code of the GPU path for gfx950: pack / unpack / elementwise / row operations / RoPE /
-// fused attention, and the choice of the GEMM tile configuration.
+// fused attention, the choice of the GEMM tile configuration, and the library's static scratch.
 //
 // Packed layout (see include/lpg.h): blocks of 4 KiB = 32 free indices x KB
 // contraction indices, each made of four 1 KiB fragments; a fragment is the
@@ -13,7 +13,7 @@
 namespace lpg {
 
 // ---------------------------------------------------------------------------------
-// Process-wide state: tuning hooks, per-device facts.
+// Process-wide state: tuning hooks, per-device facts, the static scratch.
 
 static int g_tune[LPG_TUNE_KEYS] = {-1, -1, -1, -1, -1, -1, -1};
 
@@ -64,6 +64,32 @@ void mark_used_on_device(PerDeviceFlag &f)
 {
     const int dev = current_device();
     __atomic_fetch_or(&f.done[dev / 64], 1ull << (dev % 64), __ATOMIC_RELEASE);
+}
+
+// Device memory the library owns, for callers that may not allocate (lpg_chain_static): the
+// row-major copies of the canonical control chain.  Every GPU the library runs on holds its own
+// copy of this array, at its own address, until the process ends.  `scratch` is a host-side
+// stand-in here, never a device address: host code uses the address hipGetSymbolAddress gives.
+constexpr size_t kScratchBytes = (size_t)LPG_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+hipError_t static_scratch(void **ptr, size_t *bytes)
+{
+    static void *base[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = __atomic_load_n(&base[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        __atomic_store_n(&base[dev], p, __ATOMIC_RELEASE);
+    }
+    *ptr = p;
+    *bytes = kScratchBytes;
+    return hipSuccess;
 }
 
 // Launch limits of HIP: a request past them is reported, never narrowed.
