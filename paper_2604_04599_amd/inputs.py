@@ -12,8 +12,8 @@ Workloads (full sizes; every shape key can be overridden for small tests):
   attention      Q, K, V [heads x t x dh] ~ N(0,1)              heads=32 t=2048 dh=64
   deep_chain     C0 [n x n] ~ U[-1,1]; B_i [n x n] ~ U[-1,1]/sqrt(n)   n=4096 depth=8
   decoder_layer  X [t x hidden] ~ N(0,1); weights ~ N(0, std 0.02); all values
-                 made bf16-representable by clearing the low 16 bits of the fp32
-                 pattern           t=4096 hidden=2048 n_q=32 n_kv=8 ffn=8192
+                 rounded once to the nearest bf16-representable value (ties to
+                 even)            t=4096 hidden=2048 n_q=32 n_kv=8 ffn=8192
 Seeds are 1001..1005 in that order (numpy PCG64).
 
 A sixth workload outside the benchmark set, `llama_layer` (seed 1006), is the decoder
@@ -64,9 +64,11 @@ def _normal(rng, shape, std=1.0):
 
 
 def _bf16_representable(x):
-    """Clear the 16 low bits of each fp32 pattern (truncation, not rounding)."""
-    return (np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
-            & np.uint32(0xFFFF0000)).view(np.float32)
+    """Round each (finite) fp32 value to the nearest bf16-representable one, ties to even, on
+    the bit pattern; the result is still float32 (its 16 low bits are zero)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32)
 
 
 def make(name, seed=None, **over):

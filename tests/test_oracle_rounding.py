@@ -55,3 +55,19 @@ def test_round_arrays():
     assert np.array_equal(ref.round_bf16(r), r)
     f = ref.round_f32(np.array([0.1, 1.0 + 2.0 ** -30]))
     assert f[0] == float(np.float32(0.1)) and f[1] == 1.0
+
+
+def test_bf16_workload_inputs_are_rounded_to_nearest_even():
+    """The bf16 workloads draw fp32 values and round them once (nearest, ties to even) before
+    either side sees them: the generator's rounding equals the oracle's, ties included."""
+    from paper_2604_04599_amd import inputs
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(50000).astype(np.float32)
+    ties = (np.arange(0x3F80, 0x3F90, dtype=np.uint32) << 16 | 0x8000).view(np.float32)      # exact halves
+    x = np.concatenate([x, ties, -ties])
+    y = inputs._bf16_representable(x)
+    assert np.array_equal(y.astype(np.float64), ref.round_bf16(x.astype(np.float64)))
+    assert np.all(y.view(np.uint32) & 0xFFFF == 0)
+    inp, _ = inputs.make("decoder_layer", t=64, hidden=64, n_q=1, n_kv=1, ffn=64)
+    for v in inp.values():
+        assert np.all(v.view(np.uint32) & 0xFFFF == 0)
