@@ -368,14 +368,15 @@ int lpg_chain_static(const lpg_stage *stages, int n, int mode, void *stream);
  * Table I of the paper lists such parameters per architecture; these are this library's.
  */
 typedef enum {
-    LPG_TUNE_TILE = 0,                    /* GEMM tile configuration index 0..LPG_TILE_CONFIGS-1   */
+    LPG_TUNE_TILE = 0,                    /* GEMM tile configuration index 0..7                      */
     LPG_TUNE_BAND = 1,                    /* tile rows per band of the XCD-local tile walk          */
     LPG_TUNE_TWO_BLOCK_STEPS = 2,         /* 0: lone small tiles take one K block per step          */
     LPG_TUNE_BF16_WHOLE_BLOCK_STEPS = 3,  /* 0: bf16 4-wave tiles use the half-block ring           */
     LPG_TUNE_ROW_VARIANT = 4,             /* softmax / RMSNorm kernel variant 0..5                  */
     LPG_TUNE_ATTN_QUERY_GROUPS = 5,       /* fused attention: 1 or 2 query groups per wave          */
     LPG_TUNE_TRACE = 6,                   /* 1: print the tile configuration of every GEMM launch   */
-    LPG_TUNE_KEYS = 7
+    LPG_TUNE_STREAM_STORES = 7,           /* 0 / 1: GEMM epilogue stores plain / streaming (non-temporal)   */
+    LPG_TUNE_KEYS = 8
 } lpg_tune_key;
 #define LPG_TUNE_AUTO (-1)
 int lpg_tune_set(int key, int value);

@@ -22,7 +22,7 @@ LPG_STAGE_RMSNORM, LPG_STAGE_ROPE, LPG_STAGE_ATTENTION = 5, 6, 7
 LPG_CHAIN_PROPAGATED, LPG_CHAIN_CANONICAL = 0, 1
 LPG_ATTN_CAUSAL, LPG_ATTN_NO_SOFTMAX = 1, 2
 (LPG_TUNE_TILE, LPG_TUNE_BAND, LPG_TUNE_TWO_BLOCK_STEPS, LPG_TUNE_BF16_WHOLE_BLOCK_STEPS, LPG_TUNE_ROW_VARIANT,
- LPG_TUNE_ATTN_QUERY_GROUPS, LPG_TUNE_TRACE) = range(7)
+ LPG_TUNE_ATTN_QUERY_GROUPS, LPG_TUNE_TRACE, LPG_TUNE_STREAM_STORES) = range(8)
 LPG_TUNE_AUTO = -1
 LPG_STATIC_SCRATCH_BYTES = 64 << 20
 

@@ -320,6 +320,7 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     g.o_keep_l = g.o_keep_r = 0;
     g.o_foff = g.o_koff = 0;
     g.gm = 8;
+    g.o_stream = 0;
     g.L = (const char *)(l_is_a ? A : B) + L.origin;
     g.R = (const char *)(l_is_a ? B : A) + R.origin;
     g.l_canon = L.canon;

@@ -179,7 +179,9 @@ __device__ __forceinline__ void frag_vals(const char *ptr, float (&x)[16 / OUT::
     }
 }
 
-template <typename OUT, bool USE_C, int EPI>
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+// NT: streaming stores (the output is far larger than the caches and is not read again soon)
+template <typename OUT, bool USE_C, int EPI, bool NT = false>
 __device__ __forceinline__ void store_tile_plain(const GemmArgs &p, const f32x16 &acc, int grL, int grR, int lane, char *Ob,
                                                  const char *Cb, const char *Eb)
 {
@@ -207,13 +209,14 @@ __device__ __forceinline__ void store_tile_plain(const GemmArgs &p, const f32x16
 #pragma unroll
             for (int j = 0; j < PER; ++j) v[j] = silu_f(g[j]) * v[j];
         }
+        u32x4_t w;
         if constexpr (OUT::ES == 4) {
-            *(uint4 *)(Ob + off + fgi * kFragBytes) =
-                make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+            w = u32x4_t{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
         } else {
-            *(uint4 *)(Ob + off + fgi * kFragBytes) = make_uint4(bf16_pack2(v[0], v[1]), bf16_pack2(v[2], v[3]),
-                                                                  bf16_pack2(v[4], v[5]), bf16_pack2(v[6], v[7]));
+            w = u32x4_t{bf16_pack2(v[0], v[1]), bf16_pack2(v[2], v[3]), bf16_pack2(v[4], v[5]), bf16_pack2(v[6], v[7])};
         }
+        if constexpr (NT) __builtin_nontemporal_store(w, (u32x4_t *)(Ob + off + fgi * kFragBytes));
+        else *(u32x4_t *)(Ob + off + fgi * kFragBytes) = w;
     }
 }
 
@@ -231,6 +234,81 @@ __device__ __forceinline__ void store_tile_canon_plain(const GemmArgs &p, const 
         const float x = acc[e] * p.alpha;
         if constexpr (OUT::ES == 4) *(float *)dst = x;
         else *(uint16_t *)dst = (uint16_t)bf16_rne(x);
+    }
+}
+
+// virtual block id -> (batch, tile).  Hardware deals consecutive workgroups round-robin
+// to the 8 XCDs; ids congruent mod 8 get one contiguous range of tile ids, walked in
+// bands of GM tile-rows, so the tiles an XCD works on share L and R panels in its L2.
+template <int TLG, int TRG>
+__device__ __forceinline__ TileInfo decode_tile(const GemmArgs &p, uint32_t vb, uint32_t total, uint32_t ntile)
+{
+    const uint32_t per = total / 8, rem = total % 8, x = vb % 8, idx = vb / 8;
+    const uint32_t pid = (x < rem) ? x * (per + 1) + idx : rem * (per + 1) + (x - rem) * per + idx;
+    TileInfo t;
+    t.b = (int)(pid / ntile);
+    const int tp = (int)(pid % ntile);
+    const int GM = p.gm;
+    const int width = GM * p.tiles_r;
+    const int first_l = (tp / width) * GM;
+    const int gsz = min(p.tiles_l - first_l, GM);
+    const int tl = first_l + (tp % width) % gsz;
+    const int tr = (tp % width) / gsz;
+    t.gl0 = tl * TLG;
+    t.gr0 = tr * TRG;
+    t.nlg = min(TLG, p.FLg - t.gl0);
+    t.nrg = max(0, min(TRG, p.FRg - t.gr0));
+    // packed: first block of the tile; canonical: the operand's (slot's) first element
+    t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (p.l_canon ? 0 : (int64_t)t.gl0 * kBlockBytes);
+    t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (p.r_canon ? 0 : (int64_t)t.gr0 * kBlockBytes);
+    return t;
+}
+
+// The epilogue of one workgroup tile: every accumulator tile of the wave goes out through the
+// compact form that fits (tiles wholly inside the logical extents) or the general one.
+template <typename OUT, int TLG, int TRG, int WTL, int WTR>
+__device__ __forceinline__ void write_tiles(const GemmArgs &p, f32x16 (&acc)[WTL][WTR], const TileInfo &cur, int wl, int wr,
+                                            int lane, bool use_c, bool use_e)
+{
+    const int64_t oslot = (int64_t)cur.b * p.o_slot;
+    // compact forms for tiles wholly inside the logical extents; 0: general form
+    const bool interior = (cur.gl0 + TLG) * 32 <= p.FL && (cur.gr0 + TRG) * 32 <= p.FR;
+    int form = 0;
+    if (interior && !p.o_canon) {
+        if (p.epi == LPG_EPI_NONE) form = use_c ? 2 : 1;
+        else if (!use_c) form = (p.epi == LPG_EPI_SILU) ? 3 : (use_e ? 4 : 0);
+    } else if (p.o_canon == 1 && interior && !use_c && p.epi == LPG_EPI_NONE) {
+        form = 5;
+    }
+#define LPG_EPILOGUE_FORM(CALL)                                                                    \
+static_for<WTL * WTR>([&](auto I) {                                                            \
+    constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;                  \
+    const int grL = cur.gl0 + wl * WTL + a, grR = cur.gr0 + wr * WTR + q;                      \
+    CALL;                                                                                      \
+})
+    char *Oo = p.Out + oslot;
+    if (form == 1 && p.o_stream) {
+        LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_NONE, true>(p, acc[a][q], grL, grR, lane, Oo, nullptr, nullptr)));
+    } else if (form == 1) {
+        LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_NONE>(p, acc[a][q], grL, grR, lane, Oo, nullptr, nullptr)));
+    } else if (form == 2) {
+        LPG_EPILOGUE_FORM((store_tile_plain<OUT, true, LPG_EPI_NONE>(p, acc[a][q], grL, grR, lane, Oo, p.Cin + oslot, nullptr)));
+    } else if (form == 3) {
+        LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_SILU>(p, acc[a][q], grL, grR, lane, Oo, nullptr, nullptr)));
+    } else if (form == 4) {
+        LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_GATE_SILU>(p, acc[a][q], grL, grR, lane, Oo, nullptr, p.Epi + oslot)));
+    } else if (form == 5) {
+        LPG_EPILOGUE_FORM((store_tile_canon_plain<OUT>(p, acc[a][q], grL, grR, lane, Oo)));
+#undef LPG_EPILOGUE_FORM
+    } else {
+        static_for<WTL * WTR>([&](auto I) {
+            constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
+            const int grL = cur.gl0 + wl * WTL + a;
+            const int grR = cur.gr0 + wr * WTR + q;
+            if (grL < p.FLg && grR < p.FRg_out)
+                store_tile<OUT>(p, acc[a][q], grL, grR, lane, p.Out + oslot, p.Cin + oslot, p.Epi + oslot, use_c,
+                                use_e);
+        });
     }
 }
 
@@ -266,30 +344,7 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     if (blockIdx.x >= total) return;
     const uint32_t my_tiles = (total - blockIdx.x + G - 1) / G;
 
-    // virtual block id -> (batch, tile).  Hardware deals consecutive workgroups round-robin
-    // to the 8 XCDs; ids congruent mod 8 get one contiguous range of tile ids, walked in
-    // bands of GM tile-rows, so the tiles an XCD works on share L and R panels in its L2.
-    auto decode = [&](uint32_t vb) -> TileInfo {
-        const uint32_t per = total / 8, rem = total % 8, x = vb % 8, idx = vb / 8;
-        const uint32_t pid = (x < rem) ? x * (per + 1) + idx : rem * (per + 1) + (x - rem) * per + idx;
-        TileInfo t;
-        t.b = (int)(pid / ntile);
-        const int tp = (int)(pid % ntile);
-        const int GM = p.gm;
-        const int width = GM * p.tiles_r;
-        const int first_l = (tp / width) * GM;
-        const int gsz = min(p.tiles_l - first_l, GM);
-        const int tl = first_l + (tp % width) % gsz;
-        const int tr = (tp % width) / gsz;
-        t.gl0 = tl * TLG;
-        t.gr0 = tr * TRG;
-        t.nlg = min(TLG, p.FLg - t.gl0);
-        t.nrg = max(0, min(TRG, p.FRg - t.gr0));
-        // packed: first block of the tile; canonical: the operand's (slot's) first element
-        t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (p.l_canon ? 0 : (int64_t)t.gl0 * kBlockBytes);
-        t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (p.r_canon ? 0 : (int64_t)t.gr0 * kBlockBytes);
-        return t;
-    };
+    auto decode = [&](uint32_t vb) -> TileInfo { return decode_tile<TLG, TRG>(p, vb, total, ntile); };
 
     // ---- copy side.  Wave w copies fragments w, w + NW, ... of a stage; src[i] is this
     // lane's address of its i-th fragment at the step the copy cursor stands on.  Every wave
@@ -460,45 +515,7 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
         }
 
         // ---- epilogue
-        const TileInfo cur = decode(vb);
-        const int64_t oslot = (int64_t)cur.b * p.o_slot;
-        // compact forms for tiles wholly inside the logical extents; 0: general form
-        const bool interior = (cur.gl0 + TLG) * 32 <= p.FL && (cur.gr0 + TRG) * 32 <= p.FR;
-        int form = 0;
-        if (interior && !p.o_canon) {
-            if (p.epi == LPG_EPI_NONE) form = use_c ? 2 : 1;
-            else if (!use_c) form = (p.epi == LPG_EPI_SILU) ? 3 : (use_e ? 4 : 0);
-        } else if (p.o_canon == 1 && interior && !use_c && p.epi == LPG_EPI_NONE) {
-            form = 5;
-        }
-#define LPG_EPILOGUE_FORM(CALL)                                                                    \
-    static_for<WTL * WTR>([&](auto I) {                                                            \
-        constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;                  \
-        const int grL = cur.gl0 + wl * WTL + a, grR = cur.gr0 + wr * WTR + q;                      \
-        CALL;                                                                                      \
-    })
-        char *Oo = p.Out + oslot;
-        if (form == 1) {
-            LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_NONE>(p, acc[a][q], grL, grR, lane, Oo, nullptr, nullptr)));
-        } else if (form == 2) {
-            LPG_EPILOGUE_FORM((store_tile_plain<OUT, true, LPG_EPI_NONE>(p, acc[a][q], grL, grR, lane, Oo, p.Cin + oslot, nullptr)));
-        } else if (form == 3) {
-            LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_SILU>(p, acc[a][q], grL, grR, lane, Oo, nullptr, nullptr)));
-        } else if (form == 4) {
-            LPG_EPILOGUE_FORM((store_tile_plain<OUT, false, LPG_EPI_GATE_SILU>(p, acc[a][q], grL, grR, lane, Oo, nullptr, p.Epi + oslot)));
-        } else if (form == 5) {
-            LPG_EPILOGUE_FORM((store_tile_canon_plain<OUT>(p, acc[a][q], grL, grR, lane, Oo)));
-#undef LPG_EPILOGUE_FORM
-        } else {
-            static_for<WTL * WTR>([&](auto I) {
-                constexpr int a = decltype(I)::value / WTR, q = decltype(I)::value % WTR;
-                const int grL = cur.gl0 + wl * WTL + a;
-                const int grR = cur.gr0 + wr * WTR + q;
-                if (grL < p.FLg && grR < p.FRg_out)
-                    store_tile<OUT>(p, acc[a][q], grL, grR, lane, p.Out + oslot, p.Cin + oslot, p.Epi + oslot, use_c,
-                                    use_e);
-            });
-        }
+        write_tiles<OUT, TLG, TRG, WTL, WTR>(p, acc, decode(vb), wl, wr, lane, use_c, use_e);
     }
     wait_vmcnt<0>();  // no transfer into this workgroup's LDS may outlive the wave
 }
@@ -554,6 +571,14 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
         }
         const int force = tune_get(LPG_TUNE_BAND);
         a.gm = force > 0 ? force : best;
+    }
+    {
+        // An output larger than the memory-side cache that nothing reads back soon (attention scores)
+        // is written with streaming stores: 3-5 % on 32 heads of 2048^2 fp32 scores, nothing lost
+        // elsewhere.
+        const int force = tune_get(LPG_TUNE_STREAM_STORES);
+        const int64_t out_bytes = (int64_t)a.FL * a.FR * a.batch * OUT::ES;
+        a.o_stream = force < 0 ? out_bytes >= ((int64_t)256 << 20) : force > 0;
     }
     if constexpr (NS_LONE != NS) {
         if (total <= ncu) {

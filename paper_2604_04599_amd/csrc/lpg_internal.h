@@ -112,6 +112,7 @@ struct GemmArgs {
     // the origin, the view starts o_foff free indices and o_koff contraction indices into it
     int32_t o_foff, o_koff;
     int32_t gm;                      // tile rows per band of the tile walk (set by the launcher)
+    int32_t o_stream;                // plain packed output written with streaming (non-temporal) stores
 };
 
 struct EwArgs {

@@ -15,7 +15,7 @@ namespace lpg {
 // ---------------------------------------------------------------------------------
 // Process-wide state: tuning hooks, per-device facts, the static scratch.
 
-static int g_tune[LPG_TUNE_KEYS] = {-1, -1, -1, -1, -1, -1, -1};
+static int g_tune[LPG_TUNE_KEYS] = {-1, -1, -1, -1, -1, -1, -1, -1};
 
 int tune_get(int key) { return __atomic_load_n(&g_tune[key], __ATOMIC_RELAXED); }
 

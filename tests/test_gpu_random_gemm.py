@@ -40,9 +40,12 @@ def draw_case(seed):
     return c
 
 
+@pytest.mark.parametrize("streaming", [False, True])
 @pytest.mark.parametrize("seed", range(96))
-def test_random_gemm_case(seed):
+def test_random_gemm_case(seed, streaming, tune):
     c = draw_case(seed)
+    if streaming:
+        tune(api.LPG_TUNE_STREAM_STORES, 1)          # the epilogue's streaming-store form
     rng, in_dt, out_dt, kind = c["rng"], c["in_dt"], c["out_dt"], c["kind"]
     m, n, k, alpha, beta, epi = c["m"], c["n"], c["k"], c["alpha"], c["beta"], c["epi"]
     es_in, es = ES[in_dt], ES[out_dt]

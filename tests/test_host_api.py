@@ -225,13 +225,13 @@ def test_chain_link_check_and_workspace():
 
 
 def test_tune_hooks_round_trip_and_reject_unknown_keys():
-    for key in range(7):
+    for key in range(8):
         assert api.lpg_tune_get(key) == api.LPG_TUNE_AUTO
     api.lpg_tune_set(api.LPG_TUNE_TILE, 3)
     assert api.lpg_tune_get(api.LPG_TUNE_TILE) == 3
     api.lpg_tune_set(api.LPG_TUNE_TILE, api.LPG_TUNE_AUTO)
     assert api.lpg_tune_get(api.LPG_TUNE_TILE) == api.LPG_TUNE_AUTO
-    for bad in (-1, 7, 100):
+    for bad in (-1, 8, 100):
         with pytest.raises(api.LpgError) as e:
             api.lpg_tune_set(bad, 1)
         assert e.value.code == api.LPG_EINVAL
