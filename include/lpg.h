@@ -112,6 +112,23 @@ typedef enum {
  *                     slots share one parent).
  * batch_row_step,
  * batch_col_step      shift of the view origin per slot inside the parent.
+ * group_stride,
+ * kblock_stride       packed kinds: the paper's "block order" and "store stride" parameters
+ *                     (section III-C).  The packed parent is a grid of blocks, [K/KB] K blocks
+ *                     by [F/32] groups of the free dimension, each block 32 x KB elements
+ *                     (4 KiB) in the fragment order above.  group_stride = elements from one
+ *                     group's block to the next group's, kblock_stride = elements from one K
+ *                     block to the next; 0 = the default order, groups back to back inside a
+ *                     K block (group_stride = 32*KB) and K blocks back to back (kblock_stride
+ *                     = padded F * KB).  Other values change the order in which the blocks lie
+ *                     in memory (groups outermost: group_stride = padded K * 32, kblock_stride
+ *                     = 32*KB, which makes a row range of a left operand one contiguous run)
+ *                     or leave room between them (a stride larger than what the blocks need:
+ *                     the room is never read or written).  Both must be multiples of one block
+ *                     (32*KB elements) and must not make blocks overlap (LPG_EINVAL).  lpg_pack,
+ *                     lpg_unpack, lpg_gemm_packed (A, B, C, C_in, epi_arg), lpg_chain and
+ *                     lpg_layout_offset take them; the elementwise, row and attention entry
+ *                     points work on default-ordered buffers only (LPG_EUNSUPPORTED).
  */
 typedef struct lpg_desc {
     int32_t kind;
@@ -124,6 +141,7 @@ typedef struct lpg_desc {
     int32_t batch_div;
     int64_t batch_stride;
     int64_t batch_row_step, batch_col_step;
+    int64_t group_stride, kblock_stride;
 } lpg_desc;
 
 /* Elementwise operations on packed buffers (layout-oblivious; paper II-C, IV-A). */

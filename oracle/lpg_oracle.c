@@ -16,7 +16,8 @@
  *                   between the two attention GEMMs)
  *   orc_pack / orc_unpack            canonical <-> packed layout, by walking the
  *                   layout's nested dimensions outermost to innermost (the GPU
- *                   re-design of the dimension order of Eq. 3)
+ *                   re-design of the dimension order of Eq. 3); the _strided forms
+ *                   take the block order / store stride of section III-C
  *
  * The packed layout P(X; F, K) of a matrix with free dimension F (index f) and
  * contraction dimension K (index k), element size es in {4, 2} bytes:
@@ -159,14 +160,28 @@ static inline size_t canon_index(int64_t f, int64_t k, int64_t ld, int k_contig)
     return k_contig ? (size_t)(f * ld + k) : (size_t)(k * ld + f);
 }
 
+/* Where block (kb, g) of a packed parent starts, in elements.  The parent is a
+ * grid of blocks; gs / ks are the element distances from group to group and
+ * from K block to K block (the "block order" and "store stride" parameters of
+ * section III-C).  0, 0 selects the default order: the groups of a K block back
+ * to back, K blocks back to back. */
+static inline size_t block_start(int64_t kb, int64_t g, int64_t PFp, int64_t KB, int64_t gs, int64_t ks)
+{
+    if (gs == 0 && ks == 0) { gs = 32 * KB; ks = PFp * KB; }
+    else if (gs == 0) gs = 32 * KB;
+    else if (ks == 0) ks = 32 * KB;
+    return (size_t)(kb * ks + g * gs);
+}
+
 /* Pack the view [f0, f0+F) x [k0, k0+K) of a packed parent with extents
  * (PF, PK).  `canon` points at canonical element (f=0,k=0) OF THE VIEW.
  * Every block the view touches is written whole: positions whose (f,k) falls
  * outside the view's logical extent receive zero bytes.  f0 must be a multiple
- * of 32 and k0 of KB.  Elements are moved as raw es-byte patterns. */
-void orc_pack(const void *canon, int64_t ld, int k_contig, int es,
-              void *packed, int64_t PF, int64_t PK,
-              int64_t f0, int64_t k0, int64_t F, int64_t K)
+ * of 32 and k0 of KB.  Elements are moved as raw es-byte patterns.  gs, ks:
+ * block strides of the parent (see block_start). */
+void orc_pack_strided(const void *canon, int64_t ld, int k_contig, int es,
+                      void *packed, int64_t PF, int64_t PK,
+                      int64_t f0, int64_t k0, int64_t F, int64_t K, int64_t gs, int64_t ks)
 {
     const int64_t KV = 16 / es, KF = 2 * KV, KB = 4 * KF;
     const int64_t PFp = (PF + 31) / 32 * 32;
@@ -177,7 +192,7 @@ void orc_pack(const void *canon, int64_t ld, int k_contig, int es,
     for (int64_t kb = 0; kb < Kp / KB; ++kb)
         for (int64_t g = 0; g < Fp / 32; ++g) {
             /* position of block (kb, g) of the view inside the parent buffer */
-            size_t pos = (size_t)((k0 / KB + kb) * (PFp * KB) + (f0 / 32 + g) * (32 * KB));
+            size_t pos = block_start(k0 / KB + kb, f0 / 32 + g, PFp, KB, gs, ks);
             for (int64_t c = 0; c < 4; ++c)
                 for (int64_t h = 0; h < 2; ++h)
                     for (int64_t fl = 0; fl < 32; ++fl)
@@ -192,11 +207,18 @@ void orc_pack(const void *canon, int64_t ld, int k_contig, int es,
         }
 }
 
+void orc_pack(const void *canon, int64_t ld, int k_contig, int es,
+              void *packed, int64_t PF, int64_t PK,
+              int64_t f0, int64_t k0, int64_t F, int64_t K)
+{
+    orc_pack_strided(canon, ld, k_contig, es, packed, PF, PK, f0, k0, F, K, 0, 0);
+}
+
 /* Inverse of orc_pack: copies the view's logical elements back to canonical
  * order and ignores padding. */
-void orc_unpack(void *canon, int64_t ld, int k_contig, int es,
-                const void *packed, int64_t PF, int64_t PK,
-                int64_t f0, int64_t k0, int64_t F, int64_t K)
+void orc_unpack_strided(void *canon, int64_t ld, int k_contig, int es,
+                        const void *packed, int64_t PF, int64_t PK,
+                        int64_t f0, int64_t k0, int64_t F, int64_t K, int64_t gs, int64_t ks)
 {
     const int64_t KV = 16 / es, KF = 2 * KV, KB = 4 * KF;
     const int64_t PFp = (PF + 31) / 32 * 32;
@@ -206,7 +228,7 @@ void orc_unpack(void *canon, int64_t ld, int k_contig, int es,
     const unsigned char *src = (const unsigned char *)packed;
     for (int64_t kb = 0; kb < Kp / KB; ++kb)
         for (int64_t g = 0; g < Fp / 32; ++g) {
-            size_t pos = (size_t)((k0 / KB + kb) * (PFp * KB) + (f0 / 32 + g) * (32 * KB));
+            size_t pos = block_start(k0 / KB + kb, f0 / 32 + g, PFp, KB, gs, ks);
             for (int64_t c = 0; c < 4; ++c)
                 for (int64_t h = 0; h < 2; ++h)
                     for (int64_t fl = 0; fl < 32; ++fl)
@@ -217,4 +239,11 @@ void orc_unpack(void *canon, int64_t ld, int k_contig, int es,
                                 memcpy(dst + canon_index(f, k, ld, k_contig) * es, src + pos * es, es);
                         }
         }
+}
+
+void orc_unpack(void *canon, int64_t ld, int k_contig, int es,
+                const void *packed, int64_t PF, int64_t PK,
+                int64_t f0, int64_t k0, int64_t F, int64_t K)
+{
+    orc_unpack_strided(canon, ld, k_contig, es, packed, PF, PK, f0, k0, F, K, 0, 0);
 }

@@ -36,6 +36,8 @@ def lib():
         L.orc_silu_mul.argtypes = [vp, vp, vp, i64]
         L.orc_pack.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64]
         L.orc_unpack.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64]
+        L.orc_pack_strided.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64, i64, i64]
+        L.orc_unpack_strided.argtypes = [vp, i64, i32, i32, vp, i64, i64, i64, i64, i64, i64, i64, i64]
         L.orc_threads.restype = ctypes.c_int
         L.orc_softmax_rows.argtypes = [vp, vp, i64, i64, dbl, i32]
         _lib = L
@@ -178,15 +180,34 @@ def packed_elems(F, K, es):
     return fp * kp
 
 
-def packed_offset(f, k, PF, es):
+def block_strides(PF, es, group_stride=0, kblock_stride=0):
+    """(group stride, K-block stride) in elements of a packed parent with free extent PF: the given
+    ones ("block order" / "store stride", section III-C), or the defaults where 0: groups of a K
+    block back to back, K blocks back to back."""
+    _, _, kb = layout_consts(es)
+    pfp = (PF + 31) // 32 * 32
+    if not group_stride and not kblock_stride:
+        return 32 * kb, pfp * kb
+    return group_stride or 32 * kb, kblock_stride or 32 * kb
+
+
+def strided_elems(PF, PK, es, group_stride=0, kblock_stride=0):
+    """Elements a packed parent spans under the given block strides (room between blocks included)."""
+    _, _, kb = layout_consts(es)
+    fp, kp = padded_extents(PF, PK, es)
+    gs, ks = block_strides(PF, es, group_stride, kblock_stride)
+    return (fp // 32 - 1) * gs + (kp // kb - 1) * ks + 32 * kb
+
+
+def packed_offset(f, k, PF, es, group_stride=0, kblock_stride=0):
     """Closed-form element offset of logical (f, k) inside a packed parent whose
     free extent is PF.  Derived from the nested-dimension order by summing
     index * stride for each dimension; works on numpy integer arrays."""
     kv, kf, kb = layout_consts(es)
     f = np.asarray(f, dtype=np.int64)
     k = np.asarray(k, dtype=np.int64)
-    pfp = (PF + 31) // 32 * 32
-    blk = (k // kb) * (pfp * kb) + (f // 32) * (32 * kb)
+    gs, ks = block_strides(PF, es, group_stride, kblock_stride)
+    blk = (k // kb) * ks + (f // 32) * gs
     kin = k % kb
     c = kin // kf
     r = kin % kf              # position inside the fragment's k range
@@ -203,7 +224,7 @@ def _raw(a, es):
     return a.view(dt)
 
 
-def pack(canon, free_is_rows, es, parent=None, origin=(0, 0), out=None):
+def pack(canon, free_is_rows, es, parent=None, origin=(0, 0), out=None, group_stride=0, kblock_stride=0):
     """Pack a 2-D canonical row-major array of raw elements.
 
     free_is_rows=True gives the left-operand layout P(X; rows, cols); False
@@ -216,20 +237,20 @@ def pack(canon, free_is_rows, es, parent=None, origin=(0, 0), out=None):
     F, K = (rows, cols) if free_is_rows else (cols, rows)
     PF, PK = parent if parent is not None else (F, K)
     if out is None:
-        out = np.zeros(packed_elems(PF, PK, es), dtype=a.dtype)
-    lib().orc_pack(a.ctypes.data, cols, 1 if free_is_rows else 0, es, out.ctypes.data,
-                   PF, PK, origin[0], origin[1], F, K)
+        out = np.zeros(strided_elems(PF, PK, es, group_stride, kblock_stride), dtype=a.dtype)
+    lib().orc_pack_strided(a.ctypes.data, cols, 1 if free_is_rows else 0, es, out.ctypes.data,
+                           PF, PK, origin[0], origin[1], F, K, group_stride, kblock_stride)
     return out
 
 
-def unpack(packed, rows, cols, free_is_rows, es, parent=None, origin=(0, 0)):
+def unpack(packed, rows, cols, free_is_rows, es, parent=None, origin=(0, 0), group_stride=0, kblock_stride=0):
     """Inverse of pack(): returns a (rows, cols) raw array."""
     p = _raw(packed, es)
     F, K = (rows, cols) if free_is_rows else (cols, rows)
     PF, PK = parent if parent is not None else (F, K)
     out = np.zeros((rows, cols), dtype=p.dtype)
-    lib().orc_unpack(out.ctypes.data, cols, 1 if free_is_rows else 0, es, p.ctypes.data,
-                     PF, PK, origin[0], origin[1], F, K)
+    lib().orc_unpack_strided(out.ctypes.data, cols, 1 if free_is_rows else 0, es, p.ctypes.data,
+                             PF, PK, origin[0], origin[1], F, K, group_stride, kblock_stride)
     return out
 
 

@@ -38,6 +38,7 @@ class lpg_desc(ctypes.Structure):
         ("batch", ctypes.c_int32), ("batch_div", ctypes.c_int32),
         ("batch_stride", ctypes.c_int64),
         ("batch_row_step", ctypes.c_int64), ("batch_col_step", ctypes.c_int64),
+        ("group_stride", ctypes.c_int64), ("kblock_stride", ctypes.c_int64),
     ]
 
     def __repr__(self):
@@ -135,7 +136,7 @@ def _check(rc):
 
 
 def desc(kind, dtype, rows, cols, ld=0, parent=None, origin=(0, 0), batch=1, batch_div=1,
-         batch_stride=0, batch_step=(0, 0)):
+         batch_stride=0, batch_step=(0, 0), group_stride=0, kblock_stride=0):
     """Convenience constructor for lpg_desc."""
     d = lpg_desc()
     d.kind, d.dtype, d.rows, d.cols, d.ld = kind, dtype, rows, cols, ld
@@ -143,6 +144,7 @@ def desc(kind, dtype, rows, cols, ld=0, parent=None, origin=(0, 0), batch=1, bat
     d.row0, d.col0 = origin
     d.batch, d.batch_div, d.batch_stride = batch, batch_div, batch_stride
     d.batch_row_step, d.batch_col_step = batch_step
+    d.group_stride, d.kblock_stride = group_stride, kblock_stride
     return d
 
 

@@ -33,7 +33,8 @@ static int check_common(const lpg_desc *d, const char *what)
     if (d->rows < 0 || d->cols < 0) return fail(LPG_EINVAL, "%s: negative extent", what);
     if (d->rows > 0x7fffffff || d->cols > 0x7fffffff) return fail(LPG_EINVAL, "%s: extent over 2^31-1", what);
     if (d->batch < 0 || d->batch_div < 0) return fail(LPG_EINVAL, "%s: negative batch", what);
-    if (d->row0 < 0 || d->col0 < 0 || d->batch_stride < 0 || d->batch_row_step < 0 || d->batch_col_step < 0)
+    if (d->row0 < 0 || d->col0 < 0 || d->batch_stride < 0 || d->batch_row_step < 0 || d->batch_col_step < 0 ||
+        d->group_stride < 0 || d->kblock_stride < 0)
         return fail(LPG_EINVAL, "%s: negative origin, step or stride", what);
     if ((d->parent_rows == 0) != (d->parent_cols == 0))
         return fail(LPG_EINVAL, "%s: parent_rows and parent_cols must both be set or both be 0", what);
@@ -100,13 +101,27 @@ static int make_pview(const lpg_desc *d, const char *what, PView *v, unsigned in
         return fail(LPG_EALIGN, "%s: a free extent that is not a multiple of 32 must end at the parent's edge", what);
     if (v->keep_k && !(inner & kInnerK))
         return fail(LPG_EALIGN, "%s: a contraction extent that is not a multiple of %d must end at the parent's edge", what, (int)KB);
-    if (ns > 1 && v->bstride != 0 && v->bstride < v->PFp * v->PKp)
-        return fail(LPG_EINVAL, "%s: batch_stride smaller than one packed parent", what);
     if ((v->bstride * v->es) % 16)
         return fail(LPG_EALIGN, "%s: batch_stride must keep 16-byte alignment", what);
-    v->kb_stride = v->PFp * KB * v->es;
-    v->origin = (v->k0 / KB) * v->kb_stride + (v->f0 / 32) * (int64_t)kBlockBytes;
-    v->slot_step = v->bstride * v->es + (v->kstep / KB) * v->kb_stride + (v->fstep / 32) * (int64_t)kBlockBytes;
+    // block order / store stride: bytes from group to group and from K block to K block
+    const int64_t blk = 32 * KB;  // elements of one block
+    if (d->group_stride % blk || d->kblock_stride % blk)
+        return fail(LPG_EINVAL, "%s: group_stride and kblock_stride must be multiples of one block (%lld elements)", what, (long long)blk);
+    const int64_t ng = v->PFp / 32, nk = v->PKp / KB;
+    int64_t gs = d->group_stride, ks = d->kblock_stride;
+    if (!gs && !ks) { gs = blk; ks = ng * blk; }
+    else if (!gs) gs = blk;                 // kblock_stride alone: K blocks spread out, groups back to back
+    else if (!ks) ks = blk;                 // group_stride alone: groups outermost, K blocks back to back
+    const bool k_outer = ks >= ng * gs, f_outer = gs >= nk * ks;
+    if (!k_outer && !f_outer && ng > 1 && nk > 1)
+        return fail(LPG_EINVAL, "%s: group_stride %lld and kblock_stride %lld make blocks overlap", what, (long long)gs, (long long)ks);
+    v->default_order = gs == blk && ks == ng * blk;
+    v->g_stride = gs * v->es;
+    v->kb_stride = ks * v->es;
+    v->origin = (v->k0 / KB) * v->kb_stride + (v->f0 / 32) * v->g_stride;
+    v->slot_step = v->bstride * v->es + (v->kstep / KB) * v->kb_stride + (v->fstep / 32) * v->g_stride;
+    if (ns > 1 && v->bstride != 0 && v->bstride * v->es < (ng - 1) * v->g_stride + (nk - 1) * v->kb_stride + kBlockBytes)
+        return fail(LPG_EINVAL, "%s: batch_stride smaller than one packed parent", what);
     return LPG_OK;
 }
 
@@ -147,9 +162,17 @@ static size_t desc_bytes(const lpg_desc *d)
     const int64_t pcol = d->parent_cols ? d->parent_cols : d->cols;
     int64_t one;
     if (is_packed(d->kind)) {
+        PView pv;
+        if (make_pview(d, "desc", &pv, kInnerF | kInnerK | kOffGrid)) return 0;
         const bool tr = d->kind == LPG_PACKED_B;
         const int64_t PF = tr ? pcol : prow, PK = tr ? prow : pcol;
-        one = round_up(PF, 32) * round_up(PK, kb_of(d->dtype));
+        const int64_t KB = kb_of(d->dtype), blk = 32 * KB;
+        const int64_t ng = round_up(PF, 32) / 32, nk = round_up(PK, KB) / KB;
+        int64_t gs = d->group_stride, ks = d->kblock_stride;
+        if (!gs && !ks) { gs = blk; ks = ng * blk; }
+        else if (!gs) gs = blk;
+        else if (!ks) ks = blk;
+        one = (ng && nk) ? (ng - 1) * gs + (nk - 1) * ks + blk : 0;
     } else {
         const bool rm = d->kind == LPG_ROW_MAJOR;
         const int64_t tight = rm ? pcol : prow;
@@ -198,6 +221,7 @@ static int do_pack_unpack(bool pack, const void *canon, const lpg_desc *cd, cons
     a.sk = pv.transposed ? cv.row_stride : cv.col_stride;
     a.c_slot = cv.slot_step * cv.es;
     a.p_kbs = pv.kb_stride;
+    a.p_gs = pv.g_stride;
     a.p_slot = pv.slot_step;
     a.c_div = cv.bdiv;
     a.p_div = pv.bdiv;
@@ -229,6 +253,7 @@ struct Operand {
     int64_t origin, slot_step;  // bytes
     int64_t kb_stride;          // packed: bytes between K blocks
     int64_t ld_bytes;           // canonical: bytes between consecutive free indices
+    int64_t g_stride;           // packed: bytes between 32-groups
 };
 
 // is_a: the left operand (free = rows, must be PACKED_A or row-major); else the right operand
@@ -249,7 +274,7 @@ static int make_operand(const lpg_desc *d, const void *ptr, bool is_a, Operand *
         // ragged contraction extent inside a parent would add the neighbours into every sum
         rc = make_pview(d, what, &v, kInnerF);
         if (rc) return rc;
-        *o = Operand{false, v.dtype, v.F, v.K, v.batch, v.bdiv, v.origin, v.slot_step, v.kb_stride, 0};
+        *o = Operand{false, v.dtype, v.F, v.K, v.batch, v.bdiv, v.origin, v.slot_step, v.kb_stride, 0, v.g_stride};
         return LPG_OK;
     }
     if (d->kind != (is_a ? LPG_ROW_MAJOR : LPG_COL_MAJOR))
@@ -264,7 +289,7 @@ static int make_operand(const lpg_desc *d, const void *ptr, bool is_a, Operand *
     const int64_t ld = is_a ? v.row_stride : v.col_stride;
     if ((ld * 4) % 16 || (v.origin * 4) % 16 || (v.slot_step * 4) % 16)
         return fail(LPG_EALIGN, "%s: rows of a canonical operand must start on 16-byte boundaries", what);
-    *o = Operand{true, v.dtype, F, K, v.batch, v.bdiv, v.origin * 4, v.slot_step * 4, 0, ld * 4};
+    *o = Operand{true, v.dtype, F, K, v.batch, v.bdiv, v.origin * 4, v.slot_step * 4, 0, ld * 4, 0};
     return LPG_OK;
 }
 
@@ -329,6 +354,9 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     g.r_ld = R.ld_bytes;
     g.l_kbs = L.kb_stride;
     g.r_kbs = R.kb_stride;
+    g.l_gs = L.g_stride;
+    g.r_gs = R.g_stride;
+    g.o_gs = kBlockBytes;
     g.l_slot = L.batch == 1 ? 0 : L.slot_step;
     g.r_slot = R.batch == 1 ? 0 : R.slot_step;
     g.l_div = L.bdiv;
@@ -348,6 +376,7 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
         c_origin = cv.origin;
         g.o_canon = 0;
         g.o_kbs = cv.kb_stride;
+        g.o_gs = cv.g_stride;
         g.o_slot = cv.slot_step;
         g.o_sf = g.o_sk = 0;
         g.FRg_out = (int32_t)(round_up(R.F, kb_of(c_dtype)) / 32);
@@ -396,6 +425,11 @@ static int do_elementwise(int op, const void *x0, const void *x1, float s, void 
     if (is_canon(d->kind)) {
         const int64_t tight = d->kind == LPG_ROW_MAJOR ? d->cols : d->rows;
         if (d->ld && d->ld != tight) return fail(LPG_EUNSUPPORTED, "lpg_elementwise_packed: canonical buffers must be tight");
+    } else {
+        PView v;
+        rc = make_pview(d, "lpg_elementwise_packed", &v);
+        if (rc) return rc;
+        if (!v.default_order) return fail(LPG_EUNSUPPORTED, "lpg_elementwise_packed: packed buffers must have the default block order");
     }
     if (!x0 || !out) return fail(LPG_EINVAL, "lpg_elementwise_packed: NULL pointer");
     if (op != LPG_EW_SCALE && !x1) return fail(LPG_EINVAL, "lpg_elementwise_packed: op needs x1");
@@ -440,6 +474,7 @@ static int make_row_target(const char *what, const void *x, void *out, const lpg
         PView v;
         rc = make_pview(d, what, &v);
         if (rc) return rc;
+        if (!v.default_order) return fail(LPG_EUNSUPPORTED, "%s: packed buffers must have the default block order", what);
         if ((uintptr_t)x % 16 || (uintptr_t)out % 16) return fail(LPG_EALIGN, "%s: packed buffers must be 16-byte aligned", what);
         t->x = (const char *)x + v.origin;
         t->out = (char *)out + v.origin;
@@ -553,6 +588,8 @@ static int do_attention(const void *Q, const lpg_desc *q_d, const void *K, const
     if ((rc = make_pview(o_d, what, &o))) return rc;
     if (q_d->kind != LPG_PACKED_A || o_d->kind != LPG_PACKED_A)
         return fail(LPG_ELAYOUT, "%s: Q and O must be PACKED_A (queries x head_dim)", what);
+    if (!q.default_order || !k.default_order || !v.default_order || !o.default_order)
+        return fail(LPG_EUNSUPPORTED, "%s: packed buffers must have the default block order", what);
     if (q.dtype != k.dtype || q.dtype != v.dtype || q.dtype != o.dtype)
         return fail(LPG_EUNSUPPORTED, "%s: Q, K, V, O must share one dtype", what);
     const int64_t dh = q.K, tq = q.F, tk = k.F;
@@ -603,7 +640,7 @@ static int do_attention(const void *Q, const lpg_desc *q_d, const void *K, const
 // Packed geometry two descriptors must share to address the same bytes the same way.
 struct Geometry {
     int dtype;
-    int64_t PF, PK, bstride;
+    int64_t PF, PK, bstride, gs, ks;
 };
 static bool geometry_of(const lpg_desc *d, Geometry *g)
 {
@@ -615,6 +652,8 @@ static bool geometry_of(const lpg_desc *d, Geometry *g)
     g->PF = tr ? pcol : prow;
     g->PK = tr ? prow : pcol;
     g->bstride = d->batch_stride;
+    g->gs = d->group_stride;
+    g->ks = d->kblock_stride;
     return true;
 }
 
@@ -630,6 +669,7 @@ static lpg_desc canonical_twin(const lpg_desc *p)
     c.parent_rows = prow;
     c.parent_cols = pcol;
     c.batch_stride = p->batch_stride ? prow * pcol : 0;
+    c.group_stride = c.kblock_stride = 0;
     return c;
 }
 
@@ -745,7 +785,8 @@ static int check_links(const lpg_stage *st, int n)
                 Geometry gj;
                 if (!geometry_of(&st[j].out_d, &gj))
                     return fail(LPG_ELAYOUT, "lpg_chain: stage %d reads as packed a buffer stage %d wrote canonical", i, j);
-                if (gi.dtype != gj.dtype || gi.PF != gj.PF || gi.PK != gj.PK || gi.bstride != gj.bstride)
+                if (gi.dtype != gj.dtype || gi.PF != gj.PF || gi.PK != gj.PK || gi.bstride != gj.bstride || gi.gs != gj.gs ||
+                    gi.ks != gj.ks)
                     return fail(LPG_ELAYOUT,
                                 "lpg_chain: stage %d reads a buffer with packed geometry (free %lld, k %lld, dtype %d) "
                                 "but stage %d wrote it as (free %lld, k %lld, dtype %d)",
@@ -935,7 +976,7 @@ int lpg_layout_offset(const lpg_desc *d, int64_t b, int64_t row, int64_t col, in
     const int64_t KB = kb_of(v.dtype), KV = 16 / v.es, KF = 2 * KV;
     const int64_t kin = k % KB, c = kin / KF, r = kin % KF;
     const int64_t h = (r >> 2) & 1, vv = 4 * (r >> 3) + (r & 3);
-    const int64_t bytes = v.origin + slot * v.slot_step + (k / KB) * v.kb_stride + (f / 32) * (int64_t)kBlockBytes +
+    const int64_t bytes = v.origin + slot * v.slot_step + (k / KB) * v.kb_stride + (f / 32) * v.g_stride +
                           c * kFragBytes + h * 512 + (f % 32) * 16 + vv * v.es;
     *offset = bytes / v.es;
     return LPG_OK;

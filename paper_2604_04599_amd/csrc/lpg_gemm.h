@@ -60,7 +60,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc,
                 // parent's blocks, o_foff / o_koff further along than in an aligned view
                 const int fp = fl + p.o_foff, kp = fr + p.o_koff;
                 const int kin = kp % OUT::KB, r = kin % OUT::KF;
-                off = (int64_t)(kp / OUT::KB) * p.o_kbs + (int64_t)(fp >> 5) * kBlockBytes + (kin / OUT::KF) * kFragBytes +
+                off = (int64_t)(kp / OUT::KB) * p.o_kbs + (int64_t)(fp >> 5) * p.o_gs + (kin / OUT::KF) * kFragBytes +
                       (((r >> 2) & 1) * 32 + (fp & 31)) * 16 + (4 * (r >> 3) + (r & 3)) * OUT::ES;
             } else {
                 off = (int64_t)fl * p.o_sf + (int64_t)fr * p.o_sk;
@@ -83,9 +83,9 @@ __device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc,
     }
     int64_t obase;  // byte offset of this tile's first fragment inside out
     if constexpr (OUT::ES == 4)
-        obase = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
+        obase = (int64_t)grR * p.o_kbs + (int64_t)grL * p.o_gs + lane * 16;
     else
-        obase = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes + (grR & 1) * 2 * kFragBytes + lane * 16;
+        obase = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * p.o_gs + (grR & 1) * 2 * kFragBytes + lane * 16;
     constexpr int NF = (OUT::ES == 4) ? 4 : 2;  // fragments this tile spans
     constexpr int PER = 16 / NF;
     if (use_c || use_e) {
@@ -187,8 +187,8 @@ __device__ __forceinline__ void store_tile_plain(const GemmArgs &p, const f32x16
 {
     constexpr int NF = (OUT::ES == 4) ? 4 : 2, PER = 16 / NF;
     int64_t off;
-    if constexpr (OUT::ES == 4) off = (int64_t)grR * p.o_kbs + (int64_t)grL * kBlockBytes + lane * 16;
-    else off = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * kBlockBytes + (grR & 1) * 2 * kFragBytes + lane * 16;
+    if constexpr (OUT::ES == 4) off = (int64_t)grR * p.o_kbs + (int64_t)grL * p.o_gs + lane * 16;
+    else off = (int64_t)(grR >> 1) * p.o_kbs + (int64_t)grL * p.o_gs + (grR & 1) * 2 * kFragBytes + lane * 16;
 #pragma unroll
     for (int fgi = 0; fgi < NF; ++fgi) {
         float v[PER];
@@ -259,8 +259,8 @@ __device__ __forceinline__ TileInfo decode_tile(const GemmArgs &p, uint32_t vb, 
     t.nlg = min(TLG, p.FLg - t.gl0);
     t.nrg = max(0, min(TRG, p.FRg - t.gr0));
     // packed: first block of the tile; canonical: the operand's (slot's) first element
-    t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (p.l_canon ? 0 : (int64_t)t.gl0 * kBlockBytes);
-    t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (p.r_canon ? 0 : (int64_t)t.gr0 * kBlockBytes);
+    t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (p.l_canon ? 0 : (int64_t)t.gl0 * p.l_gs);
+    t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (p.r_canon ? 0 : (int64_t)t.gr0 * p.r_gs);
     return t;
 }
 
@@ -369,8 +369,8 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
                 const char *base = is_l ? t.Lp + (int64_t)row * p.l_ld : t.Rp + (int64_t)row * p.r_ld;
                 src[i] = base + c * (IN::KF * IN::ES) + (lane >> 5) * 16;
             } else {
-                const char *base = is_l ? t.Lp + min(grp, t.nlg - 1) * kBlockBytes
-                                        : t.Rp + max(0, min(grp - TLG, t.nrg - 1)) * kBlockBytes;
+                const char *base = is_l ? t.Lp + min(grp, t.nlg - 1) * p.l_gs
+                                        : t.Rp + max(0, min(grp - TLG, t.nrg - 1)) * p.r_gs;
                 // fragment c of the step: fragment c % 4 of the step's K block c / 4
                 src[i] = base + (c / kFragsPerBlock) * (is_l ? p.l_kbs : p.r_kbs) + (c % kFragsPerBlock) * kFragBytes + lane * 16;
             }

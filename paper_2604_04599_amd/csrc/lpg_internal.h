@@ -50,6 +50,8 @@ struct PView {
     int batch, bdiv;
     int64_t bstride;       // elements between parents of consecutive slots
     int64_t kb_stride;     // bytes between consecutive K blocks of the parent
+    int64_t g_stride;      // bytes between consecutive 32-groups of the free dimension
+    bool default_order;    // the strides are the default ones (groups back to back, K blocks back to back)
     int64_t origin;        // bytes from buffer start to slot 0's first block
     int64_t slot_step;     // bytes added per slot
     bool transposed;       // kind == PACKED_B (free = cols)
@@ -73,6 +75,7 @@ struct PackArgs {
     int64_t sf, sk;      // canonical strides (elements) along free / contraction index
     int64_t c_slot;      // canonical bytes per slot
     int64_t p_kbs;       // packed bytes between K blocks
+    int64_t p_gs;        // packed bytes between 32-groups
     int64_t p_slot;      // packed bytes per slot
     int32_t c_div, p_div;
     int32_t F, K;        // logical extents
@@ -91,6 +94,7 @@ struct GemmArgs {
     const char *Epi;     // may be null
     char *Out;
     int64_t l_kbs, r_kbs, o_kbs;     // bytes between K blocks (packed operands)
+    int64_t l_gs, r_gs, o_gs;        // bytes between 32-groups of the free dimension (packed operands)
     int64_t l_slot, r_slot, o_slot;  // bytes per slot
     // Canonical (row/column-major) operands read or written directly, without a pack or
     // unpack pass: the fused Initial / Ending kernels.  Inputs: fp32, contiguous along k;

@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs a)
     const int g = blockIdx.x, b = blockIdx.z;
     const int t = threadIdx.x;
     craw *canon = (craw *)(a.canon + (int64_t)(b / a.c_div) * a.c_slot);
-    char *pgroup = a.packed + (int64_t)(b / a.p_div) * a.p_slot + (int64_t)g * kBlockBytes;
+    char *pgroup = a.packed + (int64_t)(b / a.p_div) * a.p_slot + (int64_t)g * a.p_gs;
     const int kb_end = min(a.nkb, (int)(blockIdx.y + 1) * a.kpw);
 
     for (int kb = blockIdx.y * a.kpw; kb < kb_end; ++kb) {
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(256) void pack_offgrid_kernel(PackArgs a)
     const int g = blockIdx.x, kb = blockIdx.y, b = blockIdx.z;
     const int t = threadIdx.x;
     craw *canon = (craw *)(a.canon + (int64_t)(b / a.c_div) * a.c_slot);
-    praw *pvec = (praw *)(a.packed + (int64_t)(b / a.p_div) * a.p_slot + (int64_t)g * kBlockBytes +
+    praw *pvec = (praw *)(a.packed + (int64_t)(b / a.p_div) * a.p_slot + (int64_t)g * a.p_gs +
                           (int64_t)kb * a.p_kbs + t * 16);
     const int c = t >> 6, lane = t & 63, h = lane >> 5, fl = lane & 31;
     const int64_t f = (int64_t)g * 32 + fl - a.f_off;

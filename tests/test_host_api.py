@@ -31,8 +31,8 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_header(tmp_path):
     """The ctypes mirrors against what a C compiler makes of include/lpg.h: sizes and the
     offset of every field."""
-    # lpg_desc: 2 int32 + 7 int64 + 2 int32 + 3 int64
-    assert ctypes.sizeof(api.lpg_desc) == 8 + 7 * 8 + 8 + 3 * 8
+    # lpg_desc: 2 int32 + 7 int64 + 2 int32 + 5 int64
+    assert ctypes.sizeof(api.lpg_desc) == 8 + 7 * 8 + 8 + 5 * 8
     fields = {"lpg_desc": [n for n, _ in api.lpg_desc._fields_], "lpg_stage": [n for n, _ in api.lpg_stage._fields_]}
     src = ['#include <stdio.h>', '#include <stddef.h>', '#include "lpg.h"', 'int main(void) {']
     for st, names in fields.items():
@@ -255,3 +255,32 @@ def test_control_chain_of_odd_sizes_is_validated_before_launch():
     bad[1] = api.stage_elementwise(api.LPG_EW_ADD, C1, C2 + 4, 0.5, C2, c_d)
     with pytest.raises(api.LpgError):
         api.lpg_chain_workspace_bytes(bad, api.LPG_CHAIN_CANONICAL)
+
+
+@pytest.mark.parametrize("dtype,es", [(LPG_F32, 4), (LPG_BF16, 2)])
+def test_block_order_and_store_stride_in_the_host_index_function(dtype, es):
+    """group_stride / kblock_stride (section III-C): sizes and offsets equal the oracle's closed form for
+    groups-outermost order and for strides that leave room between blocks; overlapping or misaligned
+    strides are refused."""
+    kv, kf, kb = ref.layout_consts(es)
+    rows, cols = 100, 3 * kb + 5                   # 4 groups, 4 K blocks
+    blk = 32 * kb
+    cases = [(4 * blk, blk),                       # groups outermost, K blocks back to back
+             (4 * blk, 0),                         # the same, kblock_stride left to its default for that order
+             (2 * blk, 9 * blk),                   # K blocks outermost with room after every block and every K block
+             (0, 6 * blk)]                         # K blocks spread out, groups back to back
+    rng = np.random.default_rng(2)
+    for gs, ks in cases:
+        d = desc(LPG_PACKED_A, dtype, rows, cols, group_stride=gs, kblock_stride=ks)
+        assert api.lpg_packed_bytes(d) == ref.strided_elems(rows, cols, es, gs, ks) * es
+        dt = desc(LPG_PACKED_B, dtype, cols, rows, group_stride=gs, kblock_stride=ks)      # the same bytes as a right operand
+        for _ in range(100):
+            r, c = int(rng.integers(rows)), int(rng.integers(cols))
+            want = int(ref.packed_offset(r, c, rows, es, gs, ks))
+            assert api.lpg_layout_offset(d, 0, r, c) == want
+            assert api.lpg_layout_offset(dt, 0, c, r) == want
+    for gs, ks in [(blk + 8, 0), (2 * blk, 3 * blk), (blk, 2 * blk)]:      # not whole blocks; blocks overlap (4 x 4 grid)
+        with pytest.raises(api.LpgError) as e:
+            api.lpg_layout_offset(desc(LPG_PACKED_A, dtype, rows, cols, group_stride=gs, kblock_stride=ks), 0, 0, 0)
+        assert e.value.code == api.LPG_EINVAL
+    assert api.lpg_packed_bytes(desc(LPG_PACKED_A, dtype, rows, cols, group_stride=blk + 8)) == 0

@@ -131,3 +131,38 @@ def test_ragged_view_padding_is_zero():
     mask = np.ones(buf.size, dtype=bool)
     mask[off] = False
     assert not buf[mask].any()
+
+
+@pytest.mark.parametrize("es", [4, 2])
+def test_block_order_is_a_permutation_of_blocks_and_store_stride_leaves_room(es):
+    """Section III-C's two parameters on the oracle's pack: with groups outermost the buffer is the
+    default buffer with its block grid transposed (numpy reshape / transpose of whole 4 KiB blocks,
+    nothing of the layout's inner order involved); with room between blocks every block sits at
+    kb * ks + g * gs and the room keeps what it held; the closed form agrees; unpack inverts both."""
+    kv, kf, kb = ref.layout_consts(es)
+    dt = {4: np.uint32, 2: np.uint16}[es]
+    F, K = 70, 2 * kb + 9                       # 3 groups, 3 K blocks
+    ng, nk, blk = 3, 3, 32 * kb
+    x = (np.arange(F * K, dtype=np.uint64) * 2654435761 % (1 << (8 * es))).astype(dt).reshape(F, K)
+    base = ref.pack(x, True, es)
+    assert base.size == ng * nk * blk
+    # groups outermost
+    got = ref.pack(x, True, es, group_stride=nk * blk, kblock_stride=blk)
+    assert np.array_equal(got, base.reshape(nk, ng, blk).transpose(1, 0, 2).reshape(-1))
+    assert np.array_equal(ref.unpack(got, F, K, True, es, group_stride=nk * blk, kblock_stride=blk), x)
+    # room after every block and after every K block
+    gs, ks = 2 * blk, 7 * blk
+    poison = np.full(ref.strided_elems(F, K, es, gs, ks), 0xABCD, dtype=dt)
+    got = ref.pack(x, True, es, out=poison.copy(), group_stride=gs, kblock_stride=ks)
+    touched = np.zeros(got.size, dtype=bool)
+    for kbi in range(nk):
+        for g in range(ng):
+            at = kbi * ks + g * gs
+            assert np.array_equal(got[at:at + blk], base[(kbi * ng + g) * blk:(kbi * ng + g + 1) * blk])
+            touched[at:at + blk] = True
+    assert np.all(got[~touched] == 0xABCD)
+    assert np.array_equal(ref.unpack(got, F, K, True, es, group_stride=gs, kblock_stride=ks), x)
+    f, k = np.meshgrid(np.arange(F), np.arange(K), indexing="ij")
+    assert np.array_equal(got[ref.packed_offset(f, k, F, es, gs, ks)], x)
+    # a right operand under the same strides: the bytes of the transposed left operand
+    assert np.array_equal(ref.pack(np.ascontiguousarray(x.T), False, es, out=poison.copy(), group_stride=gs, kblock_stride=ks), got)
