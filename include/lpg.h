@@ -77,19 +77,15 @@ typedef enum {
  * parent_rows/cols    extent of the parent this view lives in (0,0 = the view is
  *                     the whole parent).  For packed kinds the parent fixes the
  *                     padded geometry (block strides).
- * row0, col0          origin of the view inside the parent.  Packed kinds: read
- *                     views (A and B of lpg_gemm_packed, the row, elementwise and
- *                     attention entry points) and batched views with a per-slot
- *                     origin step need the free-dimension origin to be a multiple
- *                     of 32 and the contraction-dimension origin a multiple of KB
- *                     (LPG_EALIGN otherwise).  A view extent that is not such a
- *                     multiple either ends at the parent's edge (its padding is then
- *                     the parent's own zero padding; every entry point takes this)
- *                     or ends inside the parent, sharing its last block with the
- *                     parent's other elements; that second form is taken by A and
- *                     B of lpg_gemm_packed in their free dimension only (a ragged
- *                     contraction extent inside a parent would add the neighbours
- *                     to every sum: LPG_EALIGN).
+ * row0, col0          origin of the view inside the parent.  Packed kinds: the row,
+ *                     elementwise and attention entry points and batched views with a
+ *                     per-slot origin step need the free-dimension origin to be a
+ *                     multiple of 32 and the contraction-dimension origin a multiple of
+ *                     KB (LPG_EALIGN otherwise), and a view extent that is not such a
+ *                     multiple must end at the parent's edge (its padding is then the
+ *                     parent's own zero padding).  A and B of lpg_gemm_packed take any
+ *                     origin and any extent inside the parent: what lies outside the
+ *                     view never enters a sum.
  *                     WRITTEN views - the destination of lpg_pack, the source of
  *                     lpg_unpack, and C / C_in / epi_arg of lpg_gemm_packed - may
  *                     have any origin and any extent inside the parent: the call
@@ -201,11 +197,20 @@ int lpg_unpack(const void *src, const lpg_desc *src_d, void *dst, const lpg_desc
  *   Batches: c_d.batch matrices; A, B use slot b / batch_div of their descriptors.
  *   Padding of C_out is written as zeros (C as a view inside a parent: see lpg_desc).
  * The same call is also the paper's Initial and Ending kernels (III-A.1, III-A.3):
- *   Initial: a_d may be LPG_ROW_MAJOR and/or b_d LPG_COL_MAJOR (the canonical order
- *   that is contiguous along the contraction index).  The kernel then gathers MFMA
- *   fragments straight from the canonical matrix, no pack pass.  fp32 only, the
- *   contraction extent a multiple of 32, base/ld/origin keeping rows 16-byte
- *   aligned; anything else is reported (LPG_EUNSUPPORTED / LPG_EALIGN): pack it.
+ *   Initial: a_d and / or b_d may be LPG_ROW_MAJOR or LPG_COL_MAJOR, fp32 or bf16, with any
+ *   leading dimension, origin and element alignment, and the contraction extent may be any
+ *   length: the kernel builds the MFMA fragments from the canonical matrix itself, no pack
+ *   pass.  The product multiplies in the dtype of the packed operand; with two canonical
+ *   operands in bf16 if either of them or the result is bf16, else in fp32; an fp32 canonical
+ *   operand of a bf16 product is rounded to nearest even as it is read, as lpg_pack would
+ *   have rounded it.  (A bf16 canonical operand beside an fp32 packed one: LPG_EUNSUPPORTED.)
+ *   An fp32 operand that is contiguous along the contraction index, 16-byte aligned and a
+ *   multiple of 32 long is copied verbatim by the main kernel (full speed); every other form
+ *   is gathered element by element by the general kernel.
+ *   Packed inputs may be views with any origin and any extent inside their parent (lpg_desc):
+ *   the main kernel takes any free-dimension origin at full speed; a contraction-dimension
+ *   origin off the KB grid, or a contraction extent that ends inside the parent, goes through
+ *   the general kernel.
  *   Ending: c_d may be LPG_ROW_MAJOR or LPG_COL_MAJOR (any dtype pair above, any
  *   ld): C_out, and C_in / epi_arg if used, are then canonical, elements outside the
  *   logical extent are left untouched, and no unpack pass is needed.

@@ -246,50 +246,64 @@ static int do_pack_unpack(bool pack, const void *canon, const lpg_desc *cd, cons
 
 // An input of the product in (free, contraction) terms, packed or canonical.
 struct Operand {
-    bool canon;
-    int dtype;
+    bool canon;                 // canonical (row- or column-major) rather than packed
+    bool copyable_f32;          // canonical: fp32, contiguous along k, K a multiple of 32, 16-byte aligned rows
+    bool copyable_packed;       // packed: origin on the K-block grid, contraction extent whole or ending at the parent's edge
+    int dtype;                  // of the stored elements
     int64_t F, K;
     int batch, bdiv;
     int64_t origin, slot_step;  // bytes
     int64_t kb_stride;          // packed: bytes between K blocks
     int64_t ld_bytes;           // canonical: bytes between consecutive free indices
     int64_t g_stride;           // packed: bytes between 32-groups
+    int f_off;                  // packed: rows between the view's origin and the 32-grid
+    GatherOperand go;           // the same operand for the general (gathering) kernel
 };
 
-// is_a: the left operand (free = rows, must be PACKED_A or row-major); else the right operand
-// (free = cols, PACKED_B or column-major).  Canonical inputs are the fused Initial kernel:
-// fp32 only, contiguous along the contraction index, K a multiple of 32, 16-byte aligned rows.
+// is_a: the left operand (free = rows; PACKED_A or canonical); else the right operand (free =
+// cols; PACKED_B or canonical).  What the main kernel can copy verbatim is marked copyable;
+// every other operand is read by the general kernel (the Initial kernel for any layout).
 static int make_operand(const lpg_desc *d, const void *ptr, bool is_a, Operand *o)
 {
     const char *what = is_a ? "lpg_gemm_packed A" : "lpg_gemm_packed B";
     int rc = check_common(d, what);
     if (rc) return rc;
     if (!ptr) return fail(LPG_EINVAL, "%s: NULL pointer", what);
-    if ((uintptr_t)ptr % 16) return fail(LPG_EALIGN, "%s: buffer must be 16-byte aligned", what);
+    *o = Operand{};
     if (is_packed(d->kind)) {
+        if ((uintptr_t)ptr % 16) return fail(LPG_EALIGN, "%s: packed buffers must be 16-byte aligned", what);
         if (d->kind != (is_a ? LPG_PACKED_A : LPG_PACKED_B))
             return fail(LPG_ELAYOUT, "%s: must be %s", what, is_a ? "LPG_PACKED_A" : "LPG_PACKED_B");
         PView v;
-        // rows past a ragged free extent only feed output elements that are never stored; a
-        // ragged contraction extent inside a parent would add the neighbours into every sum
-        rc = make_pview(d, what, &v, kInnerF);
+        rc = make_pview(d, what, &v, kInnerF | kInnerK | kOffGrid);
         if (rc) return rc;
-        *o = Operand{false, v.dtype, v.F, v.K, v.batch, v.bdiv, v.origin, v.slot_step, v.kb_stride, 0, v.g_stride};
+        // a contraction extent that ends inside the parent's last touched block would add the
+        // neighbours to every sum if that block were copied whole
+        const bool k_tail_inside = v.K % kb_of(v.dtype) && v.k0 + v.K != v.PK;
+        o->canon = false;
+        o->copyable_packed = v.k_off == 0 && !k_tail_inside;
+        o->dtype = v.dtype;
+        o->F = v.F; o->K = v.K; o->batch = v.batch; o->bdiv = v.bdiv;
+        o->origin = v.origin; o->slot_step = v.slot_step; o->kb_stride = v.kb_stride; o->g_stride = v.g_stride;
+        o->f_off = v.f_off;
+        o->go = GatherOperand{(const char *)ptr + v.origin, v.batch == 1 ? 0 : v.slot_step, 0, 0, v.kb_stride, v.g_stride,
+                              v.bdiv, 1, v.es, v.f_off, v.k_off, (int32_t)v.F, (int32_t)v.K};
         return LPG_OK;
     }
-    if (d->kind != (is_a ? LPG_ROW_MAJOR : LPG_COL_MAJOR))
-        return fail(LPG_ELAYOUT, "%s: a canonical operand must be contiguous along the contraction index (%s)", what,
-                    is_a ? "row-major" : "column-major");
     CView v;
     rc = make_cview(d, what, &v);
     if (rc) return rc;
-    if (v.dtype != LPG_F32) return fail(LPG_EUNSUPPORTED, "%s: canonical operands are read directly only in fp32; pack it", what);
+    if ((uintptr_t)ptr % v.es) return fail(LPG_EALIGN, "%s: buffer not element aligned", what);
     const int64_t K = is_a ? d->cols : d->rows, F = is_a ? d->rows : d->cols;
-    if (K % 32) return fail(LPG_EUNSUPPORTED, "%s: a canonical operand needs a contraction extent that is a multiple of 32; pack it", what);
-    const int64_t ld = is_a ? v.row_stride : v.col_stride;
-    if ((ld * 4) % 16 || (v.origin * 4) % 16 || (v.slot_step * 4) % 16)
-        return fail(LPG_EALIGN, "%s: rows of a canonical operand must start on 16-byte boundaries", what);
-    *o = Operand{true, v.dtype, F, K, v.batch, v.bdiv, v.origin * 4, v.slot_step * 4, 0, ld * 4, 0};
+    const int64_t sf = is_a ? v.row_stride : v.col_stride, sk = is_a ? v.col_stride : v.row_stride;  // elements
+    o->canon = true;
+    o->copyable_f32 = v.dtype == LPG_F32 && sk == 1 && K % 32 == 0 && (uintptr_t)ptr % 16 == 0 && (sf * 4) % 16 == 0 &&
+                      (v.origin * 4) % 16 == 0 && (v.slot_step * 4) % 16 == 0;
+    o->dtype = v.dtype;
+    o->F = F; o->K = K; o->batch = v.batch; o->bdiv = v.bdiv;
+    o->origin = v.origin * v.es; o->slot_step = v.slot_step * v.es; o->ld_bytes = sf * v.es;
+    o->go = GatherOperand{(const char *)ptr + v.origin * v.es, v.batch == 1 ? 0 : v.slot_step * v.es, sf * v.es, sk * v.es, 0, 0,
+                          v.bdiv, 0, v.es, 0, 0, (int32_t)F, (int32_t)K};
     return LPG_OK;
 }
 
@@ -316,9 +330,24 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     if (c_d->rows != a_d->rows || c_d->cols != b_d->cols)
         return fail(LPG_EINVAL, "lpg_gemm_packed: C is %lldx%lld but A*B is %lldx%lld", (long long)c_d->rows,
                     (long long)c_d->cols, (long long)a_d->rows, (long long)b_d->cols);
-    if (ao.dtype != bo.dtype) return fail(LPG_EUNSUPPORTED, "lpg_gemm_packed: A and B dtypes differ");
-    if (ao.dtype == LPG_F32 && c_dtype != LPG_F32)
+    // The type the MFMAs multiply: that of the packed operands; an fp32 canonical operand beside a
+    // bf16 one is rounded to bf16 as it is read (as lpg_pack would have done).
+    int in_dtype;
+    if (!ao.canon && !bo.canon) {
+        if (ao.dtype != bo.dtype) return fail(LPG_EUNSUPPORTED, "lpg_gemm_packed: A and B dtypes differ");
+        in_dtype = ao.dtype;
+    } else if (ao.canon && bo.canon) {
+        // two canonical operands: bf16 if either is, or if the result is to be stored as bf16
+        in_dtype = (ao.dtype == LPG_BF16 || bo.dtype == LPG_BF16 || c_dtype == LPG_BF16) ? LPG_BF16 : LPG_F32;
+    } else {
+        in_dtype = ao.canon ? bo.dtype : ao.dtype;
+        if (in_dtype == LPG_F32 && (ao.canon ? ao.dtype : bo.dtype) != LPG_F32)
+            return fail(LPG_EUNSUPPORTED, "lpg_gemm_packed: a bf16 canonical operand beside an fp32 packed one");
+    }
+    if (in_dtype == LPG_F32 && c_dtype != LPG_F32)
         return fail(LPG_EUNSUPPORTED, "lpg_gemm_packed: f32 inputs need an f32 output");
+    auto copyable = [&](const Operand &o) { return o.canon ? (o.copyable_f32 && in_dtype == LPG_F32) : o.copyable_packed; };
+    const bool general = !(copyable(ao) && copyable(bo));
     if (epi < LPG_EPI_NONE || epi > LPG_EPI_GATE_SILU) return fail(LPG_EINVAL, "lpg_gemm_packed: bad epilogue op %d", epi);
     if (epi == LPG_EPI_GATE_SILU && !epi_arg) return fail(LPG_EINVAL, "lpg_gemm_packed: LPG_EPI_GATE_SILU needs epi_arg");
     if (beta != 0.0f && !C_in) return fail(LPG_EINVAL, "lpg_gemm_packed: beta != 0 needs C_in");
@@ -356,6 +385,8 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     g.r_kbs = R.kb_stride;
     g.l_gs = L.g_stride;
     g.r_gs = R.g_stride;
+    g.l_foff = L.f_off;
+    g.r_foff = R.f_off;
     g.o_gs = kBlockBytes;
     g.l_slot = L.batch == 1 ? 0 : L.slot_step;
     g.r_slot = R.batch == 1 ? 0 : R.slot_step;
@@ -398,15 +429,26 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     g.FR = (int32_t)R.F;
     g.FLg = (int32_t)((L.F + 31) / 32);
     g.FRg = (int32_t)((R.F + 31) / 32);
-    g.nkb = (int32_t)((ao.K + kb_of(ao.dtype) - 1) / kb_of(ao.dtype));
+    g.nkb = (int32_t)((ao.K + kb_of(in_dtype) - 1) / kb_of(in_dtype));
     g.tiles_l = g.tiles_r = 0;
     g.batch = nb;
     g.epi = epi;
     g.alpha = alpha;
     g.beta = beta;
     if (g.FL == 0 || g.FR == 0) return LPG_OK;
+    if (general) {
+        GatherArgs ga;
+        ga.g = g;
+        ga.g.L = ga.g.R = nullptr;
+        ga.g.l_canon = ga.g.r_canon = 1;
+        ga.l = L.go;
+        ga.r = R.go;
+        hipError_t e = launch_gemm_gather(ga, in_dtype, c_dtype, st);
+        if (e != hipSuccess) return fail(LPG_EHIP, "lpg_gemm_packed: %s", hipGetErrorString(e));
+        return LPG_OK;
+    }
     // the tuning hook LPG_TUNE_TILE pins the tile configuration (-1 = automatic)
-    hipError_t e = launch_gemm(g, ao.dtype, c_dtype, tune_get(LPG_TUNE_TILE), st);
+    hipError_t e = launch_gemm(g, in_dtype, c_dtype, tune_get(LPG_TUNE_TILE), st);
     if (e != hipSuccess) return fail(LPG_EHIP, "lpg_gemm_packed: %s", hipGetErrorString(e));
     return LPG_OK;
 }

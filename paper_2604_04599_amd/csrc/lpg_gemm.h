@@ -67,8 +67,8 @@ __device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc,
             }
             float x = v[e];
             if (use_c) {
-                if constexpr (OUT::ES == 4) x += p.beta * *(const float *)(Cb + off);
-                else x += p.beta * bf16_to_f32(*(const uint16_t *)(Cb + off));
+                if constexpr (OUT::ES == 4) x = __builtin_fmaf(p.beta, *(const float *)(Cb + off), x);
+                else x = __builtin_fmaf(p.beta, bf16_to_f32(*(const uint16_t *)(Cb + off)), x);
             }
             float gte = 0.0f;
             if (use_e) {
@@ -113,7 +113,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs &p, const f32x16 &acc,
 #pragma unroll
             for (int j = 0; j < PER; ++j) {
                 float x = v[fgi * PER + j];
-                if (use_c) x += p.beta * cv[j];
+                if (use_c) x = __builtin_fmaf(p.beta, cv[j], x);
                 v[fgi * PER + j] = epi_apply(p.epi, x, use_e ? ev[j] : 0.0f);
             }
         }
@@ -198,7 +198,7 @@ __device__ __forceinline__ void store_tile_plain(const GemmArgs &p, const f32x16
             float c[PER];
             frag_vals<OUT>(Cb + off + fgi * kFragBytes, c);
 #pragma unroll
-            for (int j = 0; j < PER; ++j) v[j] += p.beta * c[j];
+            for (int j = 0; j < PER; ++j) v[j] = __builtin_fmaf(p.beta, c[j], v[j]);
         }
         if constexpr (EPI == LPG_EPI_SILU) {
 #pragma unroll
@@ -265,7 +265,9 @@ __device__ __forceinline__ TileInfo decode_tile(const GemmArgs &p, uint32_t vb, 
 }
 
 // The epilogue of one workgroup tile: every accumulator tile of the wave goes out through the
-// compact form that fits (tiles wholly inside the logical extents) or the general one.
+// compact form that fits (tiles wholly inside the logical extents) or the general one.  All forms
+// round alike (v = alpha * acc, then one fused multiply-add with beta * C_in), so an element's
+// value does not depend on the tile configuration that happened to compute it.
 template <typename OUT, int TLG, int TRG, int WTL, int WTR>
 __device__ __forceinline__ void write_tiles(const GemmArgs &p, f32x16 (&acc)[WTL][WTR], const TileInfo &cur, int wl, int wr,
                                             int lane, bool use_c, bool use_e)
@@ -369,10 +371,21 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
                 const char *base = is_l ? t.Lp + (int64_t)row * p.l_ld : t.Rp + (int64_t)row * p.r_ld;
                 src[i] = base + c * (IN::KF * IN::ES) + (lane >> 5) * 16;
             } else {
-                const char *base = is_l ? t.Lp + min(grp, t.nlg - 1) * p.l_gs
-                                        : t.Rp + max(0, min(grp - TLG, t.nrg - 1)) * p.r_gs;
+                // A view whose free-dimension origin is foff rows off the 32-grid: view row v of a
+                // group is parent row v + foff, i.e. lane slot (v + foff) % 32 of this block or of the
+                // next one.  The transfer takes a source address per lane, so the shift costs nothing:
+                // each lane fetches its 16 bytes from where they are and drops them at lane * 16.
+                // Rows past the view's last row come from the last block the view touches (never used).
+                const int foff = is_l ? p.l_foff : p.r_foff;
+                const int row = (lane & 31) + foff;
+                const int g = is_l ? min(grp, t.nlg - 1) : max(0, min(grp - TLG, t.nrg - 1));
+                const int g0 = is_l ? t.gl0 : t.gr0;
+                const int gmax = (foff + (is_l ? p.FL : p.FR) - 1) >> 5;   // last block of the view, from its first
+                const int gsrc = min(g0 + g + (row >> 5), gmax) - g0;
+                const char *base = is_l ? t.Lp + (int64_t)gsrc * p.l_gs : t.Rp + (int64_t)gsrc * p.r_gs;
                 // fragment c of the step: fragment c % 4 of the step's K block c / 4
-                src[i] = base + (c / kFragsPerBlock) * (is_l ? p.l_kbs : p.r_kbs) + (c % kFragsPerBlock) * kFragBytes + lane * 16;
+                src[i] = base + (c / kFragsPerBlock) * (is_l ? p.l_kbs : p.r_kbs) + (c % kFragsPerBlock) * kFragBytes +
+                         ((lane >> 5) * 32 + (row & 31)) * 16;
             }
         }
     };
@@ -615,6 +628,178 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
     return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS>(a, grid, st);
 }
 
+
+// ---------------------------------------------------------------------------------
+// The general GEMM kernel: the Initial kernel of section III-A.1 for ANY operand.  The main kernel
+// copies fragments verbatim (packed operands on the block grid, k-contiguous fp32 canonical ones);
+// everything else - canonical matrices contiguous along the free index (a row-major weight B[k x n]),
+// bf16 canonical matrices, fp32 canonical matrices feeding a bf16 product (rounded to nearest even on
+// the way, exactly as lpg_pack would), contractions of any length (the tail reads as zero), views of
+// packed parents with any origin and any extent - goes through registers here: every thread builds
+// the 16-byte lane vectors of the operand image element by element (vector loads where the source is
+// contiguous along k and aligned), writes them to the LDS, and the multiply side and the epilogue
+// are the main kernel's.  One K block per step, two LDS stages, 128 x 128 tiles, 4 waves of 2 x 2.
+// The per-accumulator order of the sums is the main kernel's, so results are bit-identical to
+// lpg_pack followed by the packed product.
+
+// element (f, k) of an operand as the raw pattern of the type the GEMM multiplies; zero outside
+template <typename IN>
+__device__ __forceinline__ typename IN::raw gather_elem(const GatherOperand &o, const char *base, int f, int k)
+{
+    typedef typename IN::raw raw;
+    if (f >= o.F || k >= o.K) return (raw)0;
+    if (o.packed) {
+        const int fp = f + o.foff, kp = k + o.koff;
+        const int kin = kp % IN::KB, r = kin % IN::KF;
+        const int64_t off = (int64_t)(kp / IN::KB) * o.kbs + (int64_t)(fp >> 5) * o.gs + (kin / IN::KF) * kFragBytes +
+                            (((r >> 2) & 1) * 32 + (fp & 31)) * 16 + (4 * (r >> 3) + (r & 3)) * IN::ES;
+        return *(const raw *)(base + off);
+    }
+    const char *ptr = base + (int64_t)f * o.sf + (int64_t)k * o.sk;
+    if (o.es == 4) {
+        const uint32_t u = *(const uint32_t *)ptr;
+        if constexpr (IN::ES == 4) return u;
+        else return (raw)bf16_rne(__uint_as_float(u));
+    }
+    if constexpr (IN::ES == 2) return *(const uint16_t *)ptr;
+    else return (raw)0;  // refused on the host: an fp32 product never takes bf16 canonical operands
+}
+
+// The 16 bytes lane (fl, h) holds of fragment c of K block kb of 32-group g: elements
+// k = KB*kb + KF*c + 8*(v/4) + 4*h + v%4, v < KV, of free index 32*g + fl.
+template <typename IN>
+__device__ __forceinline__ uint4 gather_vector(const GatherOperand &o, const char *base, int g, int kb, int c, int lane)
+{
+    const int f = g * 32 + (lane & 31), h = lane >> 5;
+    const int k0 = kb * IN::KB + c * IN::KF + 4 * h;
+    typename IN::raw e[IN::KV];
+    // runs of four consecutive k: one (fp32) or two, eight apart (bf16)
+    constexpr int RUNS = IN::KV / 4;
+    const bool contiguous = !o.packed && o.sk == o.es && f < o.F;
+#pragma unroll
+    for (int u = 0; u < RUNS; ++u) {
+        const int k = k0 + 8 * u;
+        const char *ptr = base + (int64_t)f * o.sf + (int64_t)k * o.sk;
+        if (contiguous && k + 4 <= o.K && o.es == 4 && ((uintptr_t)ptr & 15) == 0) {
+            const uint4 q = *(const uint4 *)ptr;
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (IN::ES == 4) e[4 * u + j] = w[j];
+                else e[4 * u + j] = (typename IN::raw)bf16_rne(__uint_as_float(w[j]));
+            }
+        } else if (IN::ES == 2 && contiguous && k + 4 <= o.K && o.es == 2 && ((uintptr_t)ptr & 7) == 0) {
+            const uint2 q = *(const uint2 *)ptr;
+            e[4 * u + 0] = (typename IN::raw)(q.x & 0xffff);
+            e[4 * u + 1] = (typename IN::raw)(q.x >> 16);
+            e[4 * u + 2] = (typename IN::raw)(q.y & 0xffff);
+            e[4 * u + 3] = (typename IN::raw)(q.y >> 16);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e[4 * u + j] = gather_elem<IN>(o, base, f, k + j);
+        }
+    }
+    if constexpr (IN::ES == 4) return make_uint4(e[0], e[1], e[2], e[3]);
+    else return make_uint4((uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16),
+                           (uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16));
+}
+
+template <typename IN, typename OUT>
+__global__ __launch_bounds__(256) void gemm_gather_kernel(GatherArgs ga)
+{
+    constexpr int TLG = 4, TRG = 4, WL = 2, NW = 4, WTL = 2, WTR = 2;   // 2 x 2 waves of 2 x 2 tiles
+    constexpr int FS = kFragsPerBlock;                 // one K block per step
+    constexpr int NFRAG = (TLG + TRG) * FS, FPW = NFRAG / NW;
+    constexpr int STAGE = NFRAG * kFragBytes;
+    const GemmArgs &p = ga.g;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wl = wave % WL, wr = wave / WL;
+    const uint32_t ntile = (uint32_t)(p.tiles_l * p.tiles_r);
+    const uint32_t total = ntile * (uint32_t)p.batch;
+    const bool use_c = (p.beta != 0.0f) && p.Cin;
+    const bool use_e = (p.epi == LPG_EPI_GATE_SILU) && p.Epi;
+
+    for (uint32_t vb = blockIdx.x; vb < total; vb += gridDim.x) {
+        const TileInfo t = decode_tile<TLG, TRG>(p, vb, total, ntile);
+        const char *lbase = ga.l.base + (int64_t)(t.b / ga.l.div) * ga.l.slot;
+        const char *rbase = ga.r.base + (int64_t)(t.b / ga.r.div) * ga.r.slot;
+        // wave w builds fragments w, w + NW, ... of a stage: fragment x = grp * FS + c
+        uint4 staged[FPW];
+        auto fetch = [&](int kb) {
+#pragma unroll
+            for (int i = 0; i < FPW; ++i) {
+                const int x = i * NW + wave, grp = x / FS, c = x % FS;
+                staged[i] = grp < TLG ? gather_vector<IN>(ga.l, lbase, t.gl0 + grp, kb, c, lane)
+                                      : gather_vector<IN>(ga.r, rbase, t.gr0 + grp - TLG, kb, c, lane);
+            }
+        };
+        auto deposit = [&](int stage) {
+#pragma unroll
+            for (int i = 0; i < FPW; ++i)
+                *(uint4 *)(smem + stage * STAGE + (i * NW + wave) * kFragBytes + lane * 16) = staged[i];
+        };
+        f32x16 acc[WTL][WTR];
+#pragma unroll
+        for (int a = 0; a < WTL; ++a)
+#pragma unroll
+            for (int q = 0; q < WTR; ++q)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[a][q][e] = 0.0f;
+
+        if (p.nkb > 0) {
+            fetch(0);
+            __syncthreads();   // the previous tile's last stage has been read by everyone
+            deposit(0);
+            __syncthreads();
+        }
+        for (int s = 0; s < p.nkb; ++s) {
+            const bool more = s + 1 < p.nkb;
+            if (more) fetch(s + 1);     // in flight while this step is multiplied
+            const char *sL = smem + (s & 1) * STAGE + (wl * WTL) * (FS * kFragBytes) + lane * 16;
+            const char *sR = smem + (s & 1) * STAGE + (TLG + wr * WTR) * (FS * kFragBytes) + lane * 16;
+            constexpr int J = mma_depth<IN>();
+#pragma unroll
+            for (int c = 0; c < FS; ++c) {
+                uint4 lf[WTL], rf[WTR];
+#pragma unroll
+                for (int a = 0; a < WTL; ++a) lf[a] = *(const uint4 *)(sL + a * (FS * kFragBytes) + c * kFragBytes);
+#pragma unroll
+                for (int q = 0; q < WTR; ++q) rf[q] = *(const uint4 *)(sR + q * (FS * kFragBytes) + c * kFragBytes);
+#pragma unroll
+                for (int j = 0; j < J; ++j)
+#pragma unroll
+                    for (int a = 0; a < WTL; ++a)
+#pragma unroll
+                        for (int q = 0; q < WTR; ++q) mma_part<IN>(acc[a][q], rf[q], lf[a], j);
+            }
+            if (more) deposit((s + 1) & 1);   // that stage was last read in step s - 1
+            __syncthreads();
+        }
+        write_tiles<OUT, TLG, TRG, WTL, WTR>(p, acc, t, wl, wr, lane, use_c, use_e);
+    }
+}
+
+template <typename IN, typename OUT>
+static hipError_t launch_gemm_gather_dtype(GatherArgs ga, hipStream_t st)
+{
+    GemmArgs &a = ga.g;
+    constexpr int TLG = 4, TRG = 4;
+    a.tiles_l = (a.FLg + TLG - 1) / TLG;
+    a.tiles_r = (a.FRg_out + TRG - 1) / TRG;
+    const int64_t total = (int64_t)a.tiles_l * a.tiles_r * a.batch;
+    if (total <= 0) return hipSuccess;
+    if (total > 0x7fffffff) return hipErrorInvalidValue;
+    a.gm = 8;
+    a.o_stream = 0;
+    constexpr size_t lds = 2 * (size_t)(TLG + TRG) * kFragsPerBlock * kFragBytes;   // 64 KiB
+    int64_t grid = (int64_t)device_info().ncu * 2;
+    if (grid > total) grid = total;
+    hipLaunchKernelGGL((gemm_gather_kernel<IN, OUT>), dim3((unsigned)grid), dim3(256), lds, st, ga);
+    return hipGetLastError();
+}
 
 template <typename IN, typename OUT>
 static hipError_t launch_gemm_dtype(const GemmArgs &a, int cfg, hipStream_t st)

@@ -104,6 +104,7 @@ struct GemmArgs {
     int64_t l_ld, r_ld;
     int64_t o_sf, o_sk;
     int32_t l_div, r_div;
+    int32_t l_foff, r_foff;          // packed inputs: rows between the view's origin and the 32-grid (read views)
     int32_t FL, FR;                  // logical extents of out: free dim, contraction dim
     int32_t FLg, FRg;                // 32-groups present in L and R
     int32_t FRg_out;                 // 32-groups of out's contraction dim incl. block padding
@@ -117,6 +118,25 @@ struct GemmArgs {
     int32_t o_foff, o_koff;
     int32_t gm;                      // tile rows per band of the tile walk (set by the launcher)
     int32_t o_stream;                // plain packed output written with streaming (non-temporal) stores
+};
+
+// One input of the general (gathering) GEMM kernel: any canonical matrix (any strides, fp32 or
+// bf16 elements) or any view of a packed parent, read element by element.
+struct GatherOperand {
+    const char *base;     // canonical: element (0, 0) of slot 0's view; packed: the block that holds the view's origin
+    int64_t slot;         // bytes per slot
+    int64_t sf, sk;       // canonical: byte strides along the free and the contraction index
+    int64_t kbs, gs;      // packed: bytes between K blocks / between 32-groups
+    int32_t div;          // matrix b uses slot b / div
+    int32_t packed;       // 0: canonical, 1: view of a packed parent
+    int32_t es;           // bytes of a source element (4: fp32, converted if the GEMM multiplies bf16; 2: bf16)
+    int32_t foff, koff;   // packed: the origin's distance from the 32 / KB grid
+    int32_t F, K;         // logical extents; what lies outside reads as zero
+};
+
+struct GatherArgs {
+    GemmArgs g;           // output side, extents, alpha / beta / epilogue, tile walk (L, R and their strides unused)
+    GatherOperand l, r;   // the operand on lanes (out's free dimension) and the one on registers
 };
 
 struct EwArgs {
@@ -180,6 +200,11 @@ hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, int cfg, 
 hipError_t launch_gemm_f32(const GemmArgs &a, int cfg, hipStream_t st);
 hipError_t launch_gemm_bf16(const GemmArgs &a, int cfg, hipStream_t st);
 hipError_t launch_gemm_bf16_f32(const GemmArgs &a, int cfg, hipStream_t st);
+// The general kernel: operands gathered element by element (any layout, view, conversion).
+hipError_t launch_gemm_gather(const GatherArgs &a, int in_dtype, int out_dtype, hipStream_t st);
+hipError_t launch_gemm_gather_f32(const GatherArgs &a, hipStream_t st);
+hipError_t launch_gemm_gather_bf16(const GatherArgs &a, hipStream_t st);
+hipError_t launch_gemm_gather_bf16_f32(const GatherArgs &a, hipStream_t st);
 int choose_gemm_config(const GemmArgs &a, int in_dtype);
 hipError_t launch_elementwise(const EwArgs &a, int dtype, hipStream_t st);
 hipError_t launch_row_op(const RowArgs &a, int op, int dtype, bool packed, hipStream_t st);

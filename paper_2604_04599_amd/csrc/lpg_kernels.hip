@@ -1259,4 +1259,12 @@ hipError_t launch_gemm(const GemmArgs &a, int in_dtype, int out_dtype, int cfg, 
     return hipErrorInvalidValue;
 }
 
+hipError_t launch_gemm_gather(const GatherArgs &a, int in_dtype, int out_dtype, hipStream_t st)
+{
+    if (in_dtype == LPG_F32 && out_dtype == LPG_F32) return launch_gemm_gather_f32(a, st);
+    if (in_dtype == LPG_BF16 && out_dtype == LPG_BF16) return launch_gemm_gather_bf16(a, st);
+    if (in_dtype == LPG_BF16 && out_dtype == LPG_F32) return launch_gemm_gather_bf16_f32(a, st);
+    return hipErrorInvalidValue;
+}
+
 }  // namespace lpg

@@ -318,18 +318,3 @@ def test_fused_boundaries_with_heads():
     S = host(ts, np.float32, (nh, t, t)).astype(np.float64)
     for h in range(nh):
         assert ref.rel_frobenius(S[h], ref.gemm(Q[h], K[h].T.copy(), alpha=0.125)) <= F32_TOL
-
-
-def test_canonical_operand_restrictions_are_reported():
-    fake = 1 << 20
-    pb = desc(LPG_PACKED_B, LPG_F32, 64, 64)
-    pc = desc(LPG_PACKED_A, LPG_F32, 64, 64)
-    def err(a_d, b_d=pb, c_d=pc):
-        with pytest.raises(api.LpgError) as e:
-            api.lpg_gemm_packed(1.0, fake, a_d, 2 * fake, b_d, 0.0, None, 3 * fake, c_d)
-        return e.value.code
-    assert err(desc(api.LPG_COL_MAJOR, LPG_F32, 64, 64)) == api.LPG_ELAYOUT            # A must be k-contiguous
-    assert err(desc(LPG_ROW_MAJOR, LPG_BF16, 64, 64), desc(LPG_PACKED_B, LPG_BF16, 64, 64),
-               desc(LPG_PACKED_A, LPG_BF16, 64, 64)) == api.LPG_EUNSUPPORTED             # bf16 must be packed
-    assert err(desc(LPG_ROW_MAJOR, LPG_F32, 64, 40), desc(LPG_PACKED_B, LPG_F32, 40, 64)) == api.LPG_EUNSUPPORTED
-    assert err(desc(LPG_ROW_MAJOR, LPG_F32, 64, 64, ld=66)) == api.LPG_EALIGN

@@ -114,24 +114,12 @@ def test_descriptor_errors_are_caught_on_the_host():
                 desc(LPG_PACKED_A, LPG_BF16, 64, 64)) == api.LPG_EUNSUPPORTED
     assert _err(api.lpg_gemm_packed, 1.0, fake, pa, fake, pb, 1.0, None, 2 * fake, pa) == api.LPG_EINVAL
     assert _err(api.lpg_gemm_packed, 1.0, fake, pa, 2 * fake, pb, 0.0, None, fake, pa) == api.LPG_EINVAL
-    # views: an origin off the 32 / KB grid is for written views only (pack destination, unpack
-    # source, GEMM C); inputs of a product, row operations and stepped batches refuse it
+    # views: the row, elementwise and attention entry points and stepped batches need origins on the
+    # 32 / KB grid; a product takes any view of a packed parent as an input (checked below without a launch)
     bad = desc(LPG_PACKED_A, LPG_F32, 32, 64, parent=(64, 64), origin=(16, 0))
-    assert _err(api.lpg_gemm_packed, 1.0, fake, bad, fake, pb, 0.0, None, 2 * fake,
-                desc(LPG_PACKED_A, LPG_F32, 32, 64)) == api.LPG_EALIGN
-    bad_k = desc(LPG_PACKED_B, LPG_F32, 64, 64, parent=(64, 96), origin=(0, 8))
-    assert _err(api.lpg_gemm_packed, 1.0, fake, pa, fake, bad_k, 0.0, None, 2 * fake, pa) == api.LPG_EALIGN
     assert _err(api.lpg_softmax_packed, fake, fake, bad, 1.0, False) == api.LPG_EALIGN
     assert _err(api.lpg_pack, fake, desc(LPG_ROW_MAJOR, LPG_F32, 32, 32, batch=2, batch_stride=1024), fake,
                 desc(LPG_PACKED_A, LPG_F32, 32, 32, parent=(128, 64), origin=(8, 0), batch=2, batch_step=(40, 0))) == api.LPG_EALIGN
-    # a ragged extent that ends inside the parent: refused where neighbours would be read into
-    # a sum (contraction extent of a GEMM input) and by the row, elementwise, attention calls
-    inner_k = desc(LPG_PACKED_A, LPG_F32, 64, 20, parent=(64, 64), origin=(0, 0))
-    assert _err(api.lpg_gemm_packed, 1.0, fake, inner_k, fake, desc(LPG_PACKED_B, LPG_F32, 20, 64), 0.0, None,
-                2 * fake, pa) == api.LPG_EALIGN
-    inner_kb = desc(LPG_PACKED_B, LPG_F32, 20, 64, parent=(64, 64), origin=(0, 0))
-    assert _err(api.lpg_gemm_packed, 1.0, fake, desc(LPG_PACKED_A, LPG_F32, 64, 20), fake, inner_kb, 0.0, None,
-                2 * fake, pa) == api.LPG_EALIGN
     inner_f = desc(LPG_PACKED_A, LPG_F32, 20, 32, parent=(64, 64), origin=(0, 0))
     assert _err(api.lpg_softmax_packed, fake, fake, inner_f, 1.0, False) == api.LPG_EALIGN
     assert _err(api.lpg_rmsnorm_packed, fake, fake, fake, inner_f, 1e-5) == api.LPG_EALIGN
@@ -284,3 +272,31 @@ def test_block_order_and_store_stride_in_the_host_index_function(dtype, es):
             api.lpg_layout_offset(desc(LPG_PACKED_A, dtype, rows, cols, group_stride=gs, kblock_stride=ks), 0, 0, 0)
         assert e.value.code == api.LPG_EINVAL
     assert api.lpg_packed_bytes(desc(LPG_PACKED_A, dtype, rows, cols, group_stride=blk + 8)) == 0
+
+
+def _gemm_validates(a_d, b_d, c_d):
+    """Host validation of one product without a launch: the dry pass that sizes the control chain's workspace."""
+    A, B, C = 0x10000, 0x20000, 0x30000
+    return api.lpg_chain_workspace_bytes([api.stage_gemm(1.0, A, a_d, B, b_d, 0.0, None, C, c_d)], api.LPG_CHAIN_CANONICAL)
+
+
+def test_a_product_takes_any_operand_form():
+    """What the Initial kernel accepts (section III-A.1: it packs whatever the caller has): packed views with any
+    origin and extent, canonical matrices of either order and either dtype, contractions of any length."""
+    pa, pb = desc(LPG_PACKED_A, LPG_F32, 64, 64), desc(LPG_PACKED_B, LPG_F32, 64, 64)
+    shifted = desc(LPG_PACKED_A, LPG_F32, 32, 64, parent=(64, 64), origin=(16, 0))
+    assert _gemm_validates(shifted, pb, desc(LPG_PACKED_A, LPG_F32, 32, 64)) == 0
+    off_k = desc(LPG_PACKED_A, LPG_F32, 64, 40, parent=(64, 96), origin=(0, 8))
+    assert _gemm_validates(off_k, desc(LPG_PACKED_B, LPG_F32, 40, 64), pa) == 0
+    inner_k = desc(LPG_PACKED_A, LPG_F32, 64, 20, parent=(64, 64))
+    assert _gemm_validates(inner_k, desc(LPG_PACKED_B, LPG_F32, 20, 64), pa) == 0
+    for a_d, b_d in [(desc(LPG_COL_MAJOR, LPG_F32, 64, 50), desc(LPG_ROW_MAJOR, LPG_F32, 50, 64)),       # neither contiguous along k
+                     (desc(LPG_ROW_MAJOR, LPG_BF16, 64, 50), desc(LPG_COL_MAJOR, LPG_F32, 50, 64)),     # bf16 beside fp32: a bf16 product
+                     (desc(LPG_ROW_MAJOR, LPG_F32, 64, 50, ld=51), desc(LPG_PACKED_B, LPG_BF16, 50, 64))]:
+        out_dt = LPG_BF16 if LPG_BF16 in (a_d.dtype, b_d.dtype) else LPG_F32
+        assert _gemm_validates(a_d, b_d, desc(LPG_PACKED_A, out_dt, 64, 64)) == 0
+    # still refused: a bf16 canonical operand beside an fp32 packed one; fp32 operands with a bf16 result
+    with pytest.raises(api.LpgError):
+        _gemm_validates(desc(LPG_ROW_MAJOR, LPG_BF16, 64, 64), pb, pa)
+    with pytest.raises(api.LpgError):
+        _gemm_validates(pa, pb, desc(LPG_PACKED_A, LPG_BF16, 64, 64))
