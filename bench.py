@@ -331,8 +331,8 @@ def _time_calls(fn, reps, min_seconds=0.03):
 def sweep(reps):
     """Synthetic size sweep (the paper's single-GEMM and DNN-chain size lists are not available):
     (1) one GEMM M x K x N (fp32, then bf16 operands) with a pre-packed weight, as the Initial kernel (row-major A in,
-    packed C out), the Intermediate kernel (packed in, packed out), the Ending kernel (packed in,
-    row-major out) and as a BLAS-style call (pack A + GEMM + unpack C; the Initial kernel exists for fp32 only); (2) three-GEMM chains of
+    packed C out; also with a row-major weight), the Intermediate kernel (packed in, packed out), the Ending kernel (packed in,
+    row-major out) and as a BLAS-style call (pack A + GEMM + unpack C); (2) three-GEMM chains of
     unequal widths, propagated against the canonical control.  One JSON line per case."""
     import torch
     from paper_2604_04599_amd import api, chains
@@ -351,9 +351,13 @@ def sweep(reps):
             api.lpg_pack(w, w_rm, pw, w_p, st)
             flops = 2.0 * m * k * n
             res = {"sweep": "gemm_" + tag, "m": m, "k": k, "n": n}
-            if k % 32 == 0 and dtype == LPG_F32:
-                res["initial_tflops"] = round(flops / _time_calls(
-                    lambda: api.lpg_gemm_packed(1.0, a, a_rm, pw, w_p, 0.0, None, pc, c_p, stream=st), reps) / 1e12, 2)
+            # Initial kernel: row-major fp32 A read by the GEMM itself (fp32 with K a multiple of 32: copied
+            # verbatim by the main kernel; otherwise, and for a bf16 product, gathered by the general kernel)
+            res["initial_tflops"] = round(flops / _time_calls(
+                lambda: api.lpg_gemm_packed(1.0, a, a_rm, pw, w_p, 0.0, None, pc, c_p, stream=st), reps) / 1e12, 2)
+            # ... and with the weight row-major as well (contiguous along n): the general kernel for both
+            res["initial_row_major_weight_tflops"] = round(flops / _time_calls(
+                lambda: api.lpg_gemm_packed(1.0, a, a_rm, w, w_rm, 0.0, None, pc, c_p, stream=st), reps) / 1e12, 2)
             res["intermediate_tflops"] = round(flops / _time_calls(
                 lambda: api.lpg_gemm_packed(1.0, pa, a_p, pw, w_p, 0.0, None, pc, c_p, stream=st), reps) / 1e12, 2)
             res["ending_tflops"] = round(flops / _time_calls(

@@ -287,7 +287,8 @@ static int make_operand(const lpg_desc *d, const void *ptr, bool is_a, Operand *
         o->origin = v.origin; o->slot_step = v.slot_step; o->kb_stride = v.kb_stride; o->g_stride = v.g_stride;
         o->f_off = v.f_off;
         o->go = GatherOperand{(const char *)ptr + v.origin, v.batch == 1 ? 0 : v.slot_step, 0, 0, v.kb_stride, v.g_stride,
-                              v.bdiv, 1, v.es, v.f_off, v.k_off, (int32_t)v.F, (int32_t)v.K};
+                              v.bdiv, 1, 3 /* element by element through the packed position */, v.es, v.f_off, v.k_off,
+                              (int32_t)v.F, (int32_t)v.K};
         return LPG_OK;
     }
     CView v;
@@ -302,8 +303,14 @@ static int make_operand(const lpg_desc *d, const void *ptr, bool is_a, Operand *
     o->dtype = v.dtype;
     o->F = F; o->K = K; o->batch = v.batch; o->bdiv = v.bdiv;
     o->origin = v.origin * v.es; o->slot_step = v.slot_step * v.es; o->ld_bytes = sf * v.es;
+    // vector loads where rows are contiguous along k, start on 16-byte (fp32) / 8-byte (bf16) boundaries and the
+    // contraction extent is a multiple of 4 (a run of four k is then inside or outside as a whole)
+    const int64_t vec = v.es == 4 ? 16 : 8;
+    const bool vec_ok = sk == 1 && K % 4 == 0 && ((uintptr_t)ptr + v.origin * v.es) % vec == 0 && (sf * v.es) % vec == 0 &&
+                        (v.slot_step * v.es) % vec == 0;
+    const int mode = vec_ok ? (v.es == 4 ? 1 : 2) : 0;
     o->go = GatherOperand{(const char *)ptr + v.origin * v.es, v.batch == 1 ? 0 : v.slot_step * v.es, sf * v.es, sk * v.es, 0, 0,
-                          v.bdiv, 0, v.es, 0, 0, (int32_t)F, (int32_t)K};
+                          v.bdiv, 0, mode, v.es, 0, 0, (int32_t)F, (int32_t)K};
     return LPG_OK;
 }
 

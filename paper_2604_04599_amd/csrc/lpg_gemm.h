@@ -635,73 +635,109 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
 // everything else - canonical matrices contiguous along the free index (a row-major weight B[k x n]),
 // bf16 canonical matrices, fp32 canonical matrices feeding a bf16 product (rounded to nearest even on
 // the way, exactly as lpg_pack would), contractions of any length (the tail reads as zero), views of
-// packed parents with any origin and any extent - goes through registers here: every thread builds
-// the 16-byte lane vectors of the operand image element by element (vector loads where the source is
-// contiguous along k and aligned), writes them to the LDS, and the multiply side and the epilogue
-// are the main kernel's.  One K block per step, two LDS stages, 128 x 128 tiles, 4 waves of 2 x 2.
+// packed parents with any origin and any extent - goes through registers here: every thread fetches
+// the elements of its lane vectors of the next K block (vector loads where the source is contiguous
+// along k and aligned) while the current block is multiplied, then converts them, writes the vectors
+// to the LDS, and the multiply side and the epilogue are the main kernel's.  One K block per step, two LDS stages, 128 x 128 tiles, 4 waves of 2 x 2.
 // The per-accumulator order of the sums is the main kernel's, so results are bit-identical to
 // lpg_pack followed by the packed product.
 
-// element (f, k) of an operand as the raw pattern of the type the GEMM multiplies; zero outside
-template <typename IN>
-__device__ __forceinline__ typename IN::raw gather_elem(const GatherOperand &o, const char *base, int f, int k)
-{
-    typedef typename IN::raw raw;
-    if (f >= o.F || k >= o.K) return (raw)0;
-    if (o.packed) {
-        const int fp = f + o.foff, kp = k + o.koff;
-        const int kin = kp % IN::KB, r = kin % IN::KF;
-        const int64_t off = (int64_t)(kp / IN::KB) * o.kbs + (int64_t)(fp >> 5) * o.gs + (kin / IN::KF) * kFragBytes +
-                            (((r >> 2) & 1) * 32 + (fp & 31)) * 16 + (4 * (r >> 3) + (r & 3)) * IN::ES;
-        return *(const raw *)(base + off);
-    }
-    const char *ptr = base + (int64_t)f * o.sf + (int64_t)k * o.sk;
-    if (o.es == 4) {
-        const uint32_t u = *(const uint32_t *)ptr;
-        if constexpr (IN::ES == 4) return u;
-        else return (raw)bf16_rne(__uint_as_float(u));
-    }
-    if constexpr (IN::ES == 2) return *(const uint16_t *)ptr;
-    else return (raw)0;  // refused on the host: an fp32 product never takes bf16 canonical operands
-}
+// How an operand's lane vectors are fetched (GatherOperand::mode, chosen on the host).  All loads of a
+// K block are issued first and land in raw registers while the current block is multiplied; they are
+// converted and packed into lane vectors only when they go to the LDS.
+enum { kGatherElem = 0,     // canonical, element by element (lanes run along the free index)
+       kGatherVec32 = 1,    // canonical fp32, contiguous along k, 16-byte aligned rows, K a multiple of 4
+       kGatherVec16 = 2,    // canonical bf16, contiguous along k, 8-byte aligned rows, K a multiple of 4
+       kGatherPacked = 3 }; // view of a packed parent, element by element through the closed-form position
 
-// The 16 bytes lane (fl, h) holds of fragment c of K block kb of 32-group g: elements
-// k = KB*kb + KF*c + 8*(v/4) + 4*h + v%4, v < KV, of free index 32*g + fl.
+// One lane vector as fetched: KV dwords.  Element modes: one element per dword (fp32 bits, or a bf16
+// pattern in the low half).  kGatherVec32: the dwords of the 16-byte loads.  kGatherVec16: dwords
+// 2u, 2u+1 hold run u's four bf16 values.
 template <typename IN>
-__device__ __forceinline__ uint4 gather_vector(const GatherOperand &o, const char *base, int g, int kb, int c, int lane)
+struct RawVector {
+    uint32_t w[IN::KV];
+};
+
+// Lane (fl, h) of fragment c of K block kb of 32-group g holds k = KB*kb + KF*c + 8*u + 4*h + j
+// (u < KV/4 runs of j < 4 consecutive k) of free index 32*g + fl.
+template <typename IN>
+__device__ __forceinline__ void gather_fetch(RawVector<IN> &raw, const GatherOperand &o, const char *base, int g, int kb, int c,
+                                             int lane)
 {
     const int f = g * 32 + (lane & 31), h = lane >> 5;
     const int k0 = kb * IN::KB + c * IN::KF + 4 * h;
-    typename IN::raw e[IN::KV];
-    // runs of four consecutive k: one (fp32) or two, eight apart (bf16)
     constexpr int RUNS = IN::KV / 4;
-    const bool contiguous = !o.packed && o.sk == o.es && f < o.F;
+    const bool row_in = f < o.F;
 #pragma unroll
-    for (int u = 0; u < RUNS; ++u) {
-        const int k = k0 + 8 * u;
-        const char *ptr = base + (int64_t)f * o.sf + (int64_t)k * o.sk;
-        if (contiguous && k + 4 <= o.K && o.es == 4 && ((uintptr_t)ptr & 15) == 0) {
-            const uint4 q = *(const uint4 *)ptr;
-            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    for (int v = 0; v < IN::KV; ++v) raw.w[v] = 0;
+    if (o.mode == kGatherVec32) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if constexpr (IN::ES == 4) e[4 * u + j] = w[j];
-                else e[4 * u + j] = (typename IN::raw)bf16_rne(__uint_as_float(w[j]));
+        for (int u = 0; u < RUNS; ++u) {
+            const int k = k0 + 8 * u;
+            if (row_in && k < o.K) {   // K is a multiple of 4: the run is inside or outside as a whole
+                const uint4 q = *(const uint4 *)(base + (int64_t)f * o.sf + (int64_t)k * 4);
+                raw.w[4 * u] = q.x; raw.w[4 * u + 1] = q.y; raw.w[4 * u + 2] = q.z; raw.w[4 * u + 3] = q.w;
             }
-        } else if (IN::ES == 2 && contiguous && k + 4 <= o.K && o.es == 2 && ((uintptr_t)ptr & 7) == 0) {
-            const uint2 q = *(const uint2 *)ptr;
-            e[4 * u + 0] = (typename IN::raw)(q.x & 0xffff);
-            e[4 * u + 1] = (typename IN::raw)(q.x >> 16);
-            e[4 * u + 2] = (typename IN::raw)(q.y & 0xffff);
-            e[4 * u + 3] = (typename IN::raw)(q.y >> 16);
-        } else {
+        }
+    } else if (o.mode == kGatherVec16) {
+        if constexpr (IN::ES == 2) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) e[4 * u + j] = gather_elem<IN>(o, base, f, k + j);
+            for (int u = 0; u < RUNS; ++u) {
+                const int k = k0 + 8 * u;
+                if (row_in && k < o.K) {
+                    const uint2 q = *(const uint2 *)(base + (int64_t)f * o.sf + (int64_t)k * 2);
+                    raw.w[2 * u] = q.x; raw.w[2 * u + 1] = q.y;
+                }
+            }
+        }
+    } else if (o.mode == kGatherPacked) {
+#pragma unroll
+        for (int v = 0; v < IN::KV; ++v) {
+            const int k = k0 + 8 * (v >> 2) + (v & 3);
+            if (row_in && k < o.K) {
+                const int fp = f + o.foff, kp = k + o.koff;
+                const int kin = kp % IN::KB, r = kin % IN::KF;
+                const int64_t off = (int64_t)(kp / IN::KB) * o.kbs + (int64_t)(fp >> 5) * o.gs + (kin / IN::KF) * kFragBytes +
+                                    (((r >> 2) & 1) * 32 + (fp & 31)) * 16 + (4 * (r >> 3) + (r & 3)) * IN::ES;
+                raw.w[v] = *(const typename IN::raw *)(base + off);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < IN::KV; ++v) {
+            const int k = k0 + 8 * (v >> 2) + (v & 3);
+            if (row_in && k < o.K) {
+                const char *ptr = base + (int64_t)f * o.sf + (int64_t)k * o.sk;
+                raw.w[v] = o.es == 4 ? *(const uint32_t *)ptr : (uint32_t) * (const uint16_t *)ptr;
+            }
         }
     }
-    if constexpr (IN::ES == 4) return make_uint4(e[0], e[1], e[2], e[3]);
-    else return make_uint4((uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16),
-                           (uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16));
+}
+
+// raw registers -> the 16-byte lane vector of the type the GEMM multiplies (fp32 sources of a bf16
+// product are rounded to nearest even here, exactly as lpg_pack rounds)
+template <typename IN>
+__device__ __forceinline__ uint4 gather_finish(const RawVector<IN> &raw, const GatherOperand &o)
+{
+    if constexpr (IN::ES == 4) {
+        return make_uint4(raw.w[0], raw.w[1], raw.w[2], raw.w[3]);   // fp32 sources only (checked on the host)
+    } else {
+        uint32_t e[8];
+        if (o.mode == kGatherVec16) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                e[4 * u] = raw.w[2 * u] & 0xffff; e[4 * u + 1] = raw.w[2 * u] >> 16;
+                e[4 * u + 2] = raw.w[2 * u + 1] & 0xffff; e[4 * u + 3] = raw.w[2 * u + 1] >> 16;
+            }
+        } else if (o.mode != kGatherPacked && o.es == 4) {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) e[v] = bf16_rne(__uint_as_float(raw.w[v]));
+        } else {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) e[v] = raw.w[v] & 0xffff;
+        }
+        return make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
 }
 
 template <typename IN, typename OUT>
@@ -709,8 +745,9 @@ __global__ __launch_bounds__(256) void gemm_gather_kernel(GatherArgs ga)
 {
     constexpr int TLG = 4, TRG = 4, WL = 2, NW = 4, WTL = 2, WTR = 2;   // 2 x 2 waves of 2 x 2 tiles
     constexpr int FS = kFragsPerBlock;                 // one K block per step
-    constexpr int NFRAG = (TLG + TRG) * FS, FPW = NFRAG / NW;
+    constexpr int NFRAG = (TLG + TRG) * FS;
     constexpr int STAGE = NFRAG * kFragBytes;
+    static_assert(FS == NW, "wave w builds fragment w of every 32-group");
     const GemmArgs &p = ga.g;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -726,20 +763,20 @@ __global__ __launch_bounds__(256) void gemm_gather_kernel(GatherArgs ga)
         const TileInfo t = decode_tile<TLG, TRG>(p, vb, total, ntile);
         const char *lbase = ga.l.base + (int64_t)(t.b / ga.l.div) * ga.l.slot;
         const char *rbase = ga.r.base + (int64_t)(t.b / ga.r.div) * ga.r.slot;
-        // wave w builds fragments w, w + NW, ... of a stage: fragment x = grp * FS + c
-        uint4 staged[FPW];
+        // wave w builds fragment c = w of every 32-group of the stage: groups 0 .. TLG-1 of L, then R's
+        RawVector<IN> rawl[TLG], rawr[TRG];
         auto fetch = [&](int kb) {
 #pragma unroll
-            for (int i = 0; i < FPW; ++i) {
-                const int x = i * NW + wave, grp = x / FS, c = x % FS;
-                staged[i] = grp < TLG ? gather_vector<IN>(ga.l, lbase, t.gl0 + grp, kb, c, lane)
-                                      : gather_vector<IN>(ga.r, rbase, t.gr0 + grp - TLG, kb, c, lane);
-            }
+            for (int i = 0; i < TLG; ++i) gather_fetch<IN>(rawl[i], ga.l, lbase, t.gl0 + i, kb, wave, lane);
+#pragma unroll
+            for (int i = 0; i < TRG; ++i) gather_fetch<IN>(rawr[i], ga.r, rbase, t.gr0 + i, kb, wave, lane);
         };
         auto deposit = [&](int stage) {
+            char *dst = smem + stage * STAGE + wave * kFragBytes + lane * 16;
 #pragma unroll
-            for (int i = 0; i < FPW; ++i)
-                *(uint4 *)(smem + stage * STAGE + (i * NW + wave) * kFragBytes + lane * 16) = staged[i];
+            for (int i = 0; i < TLG; ++i) *(uint4 *)(dst + i * (FS * kFragBytes)) = gather_finish<IN>(rawl[i], ga.l);
+#pragma unroll
+            for (int i = 0; i < TRG; ++i) *(uint4 *)(dst + (TLG + i) * (FS * kFragBytes)) = gather_finish<IN>(rawr[i], ga.r);
         };
         f32x16 acc[WTL][WTR];
 #pragma unroll

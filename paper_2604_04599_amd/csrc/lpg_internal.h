@@ -129,6 +129,7 @@ struct GatherOperand {
     int64_t kbs, gs;      // packed: bytes between K blocks / between 32-groups
     int32_t div;          // matrix b uses slot b / div
     int32_t packed;       // 0: canonical, 1: view of a packed parent
+    int32_t mode;         // how its lane vectors are fetched (kGather* in lpg_gemm.h), chosen on the host
     int32_t es;           // bytes of a source element (4: fp32, converted if the GEMM multiplies bf16; 2: bf16)
     int32_t foff, koff;   // packed: the origin's distance from the 32 / KB grid
     int32_t F, K;         // logical extents; what lies outside reads as zero
