@@ -52,8 +52,10 @@ static inline int nslots(const lpg_desc *d) { return (nbatch(d) + bdiv(d) - 1) /
 // last block is then shared with neighbouring elements of the parent, keep_f / keep_k are set,
 // and a writer must leave those neighbours alone.  kOffGrid: the caller also takes an origin
 // that is not a multiple of 32 / KB (f_off / k_off are then non-zero, the origin points at the
-// block that holds the first element, and nothing outside the view may be written).
-enum { kInnerF = 1, kInnerK = 2, kOffGrid = 4 };
+// block that holds the first element, and nothing outside the view may be written).  kRaggedSteps:
+// the caller only reads, so the views of a stepped batch may have ragged extents (a writer's ragged
+// view would spill its padding into the next slot's elements).
+enum { kInnerF = 1, kInnerK = 2, kOffGrid = 4, kRaggedSteps = 8 };
 static int make_pview(const lpg_desc *d, const char *what, PView *v, unsigned inner = 0)
 {
     int rc = check_common(d, what);
@@ -91,9 +93,9 @@ static int make_pview(const lpg_desc *d, const char *what, PView *v, unsigned in
     if (f_last + v->F > v->PF || k_last + v->K > v->PK)
         return fail(LPG_EINVAL, "%s: view exceeds its parent", what);
     // a ragged extent may only sit at the parent's edge, where its padding is the parent's
-    if (v->F % 32 && (ns > 1 ? v->fstep != 0 : false))
+    if (!(inner & kRaggedSteps) && v->F % 32 && (ns > 1 ? v->fstep != 0 : false))
         return fail(LPG_EALIGN, "%s: stepped views need a free extent that is a multiple of 32", what);
-    if (v->K % KB && (ns > 1 ? v->kstep != 0 : false))
+    if (!(inner & kRaggedSteps) && v->K % KB && (ns > 1 ? v->kstep != 0 : false))
         return fail(LPG_EALIGN, "%s: stepped views need a contraction extent that is a multiple of %d", what, (int)KB);
     v->keep_f = !off_grid && v->F % 32 && v->f0 + v->F != v->PF;
     v->keep_k = !off_grid && v->K % KB && v->k0 + v->K != v->PK;
@@ -275,7 +277,7 @@ static int make_operand(const lpg_desc *d, const void *ptr, bool is_a, Operand *
         if (d->kind != (is_a ? LPG_PACKED_A : LPG_PACKED_B))
             return fail(LPG_ELAYOUT, "%s: must be %s", what, is_a ? "LPG_PACKED_A" : "LPG_PACKED_B");
         PView v;
-        rc = make_pview(d, what, &v, kInnerF | kInnerK | kOffGrid);
+        rc = make_pview(d, what, &v, kInnerF | kInnerK | kOffGrid | kRaggedSteps);
         if (rc) return rc;
         // a contraction extent that ends inside the parent's last touched block would add the
         // neighbours to every sum if that block were copied whole

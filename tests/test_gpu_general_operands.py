@@ -142,3 +142,75 @@ def test_row_major_weight_and_fp32_activations_of_a_bf16_layer(dtype):
     for b in range(nb):
         got = f64(ref.unpack(raw[b * per:(b + 1) * per], m, n, True, ES[dtype]), dtype)
         assert ref.rel_frobenius(got, ref.gemm(X[b], W)) <= (1e-5 if dtype == LPG_F32 else 1e-2)
+
+
+@pytest.mark.parametrize("dtype", [LPG_F32, LPG_BF16])
+@pytest.mark.parametrize("shift", [(5, 0), (0, 16), (37, 24), (31, 0)])
+def test_shifted_head_views_with_shared_key_value_slots(shift, dtype):
+    """Batched read views whose origin is off the grid: query heads as column slices of a packed parent
+    starting `shift[0]` tokens into it (free-dimension shift: main kernel, per-lane source addresses) and,
+    for shift[1] != 0, `shift[1]` columns into a head (contraction-dimension shift: general kernel); keys
+    shared by pairs of query heads through batch_div; block strides on the key parent."""
+    rng = np.random.default_rng(sum(shift) + dtype)
+    es = ES[dtype]
+    kb = ref.layout_consts(es)[2]
+    nh, t, dh, tk = 4, 70, kb, 150
+    f0, k0 = shift
+    dk = dh - k0                                           # contraction extent of the sliced heads
+    Qp = f64(raw_of(rng.standard_normal((f0 + t + 9, nh * dh)), dtype), dtype)       # parent of Q: tokens x (heads*dh)
+    Kp = f64(raw_of(rng.standard_normal((tk, (nh // 2) * dh)), dtype), dtype)        # parent of K: keys x (kv heads*dh)
+    blk = 32 * kb
+    ng, nk = (tk + 31) // 32, (nh // 2)
+    gs, ks = (nk + 1) * blk, blk                           # groups outermost with room after each group
+    qd = desc(LPG_PACKED_A, dtype, t, dk, parent=Qp.shape, origin=(f0, k0), batch=nh, batch_step=(0, dh))
+    # K_g^T as the right operand: rows [g*dh + k0, g*dh + dh) of K^T, the same bytes as K's left-operand image
+    ktd = desc(LPG_PACKED_B, dtype, dk, tk, parent=(Kp.shape[1], Kp.shape[0]), origin=(k0, 0), batch=nh, batch_div=2,
+               batch_step=(dh, 0), group_stride=gs, kblock_stride=ks)
+    sd = desc(LPG_PACKED_A, LPG_F32, t, tk, batch=nh, batch_stride=ref.packed_elems(t, tk, 4))
+    qbuf = dev_bytes(ref.pack(raw_of(Qp, dtype), True, es))
+    kbuf = dev_bytes(ref.pack(raw_of(Kp, dtype), True, es, group_stride=gs, kblock_stride=ks))
+    out = dev_empty(api.lpg_packed_bytes(sd), fill=0xFF)
+    api.lpg_gemm_packed(0.125, qbuf, qd, kbuf, ktd, 0.0, None, out, sd, 0, None, stream())
+    raw = host(out, np.uint32)
+    per = ref.packed_elems(t, tk, 4)
+    for h in range(nh):
+        g = h // 2
+        q = Qp[f0:f0 + t, h * dh + k0:(h + 1) * dh]
+        k = Kp[:, g * dh + k0:(g + 1) * dh]
+        got = ref.unpack(raw[h * per:(h + 1) * per], t, tk, True, 4).view(np.float32).astype(np.float64)
+        assert ref.rel_frobenius(got, ref.gemm(q, np.ascontiguousarray(k.T), alpha=0.125)) <= 1e-5, h
+
+
+def test_a_chain_may_start_from_any_canonical_operands_and_match_the_packed_chain():
+    """X (row-major fp32) times a row-major weight, then a packed weight, in a bf16 chain: the first
+    stage is the general Initial kernel; propagated and canonical modes agree bit for bit, and both equal
+    the chain that packs X and W1 first."""
+    rng = np.random.default_rng(8)
+    m, d, h = 200, 130, 96
+    X = f64(raw_of(rng.standard_normal((m, d)), LPG_BF16), LPG_BF16)
+    W1 = f64(raw_of(rng.standard_normal((d, h)) / np.sqrt(d), LPG_BF16), LPG_BF16)
+    W2 = f64(raw_of(rng.standard_normal((h, d)) / np.sqrt(h), LPG_BF16), LPG_BF16)
+    xs, w1s = dev_bytes(X.astype(np.float32)), dev_bytes(W1.astype(np.float32))
+    pw2 = dev_bytes(ref.pack(raw_of(W2, LPG_BF16), False, 2))
+    hd, yd = desc(LPG_PACKED_A, LPG_BF16, m, h), desc(LPG_PACKED_A, LPG_F32, m, d)
+    ph, py = dev_empty(api.lpg_packed_bytes(hd), fill=0xFF), dev_empty(api.lpg_packed_bytes(yd), fill=0xFF)
+    y = dev_empty(m * d * 4, fill=0xFF)
+    rm_x, rm_w, rm_y = desc(LPG_ROW_MAJOR, LPG_F32, m, d), desc(LPG_ROW_MAJOR, LPG_F32, d, h), desc(LPG_ROW_MAJOR, LPG_F32, m, d)
+    stages = [api.stage_gemm(1.0, xs, rm_x, w1s, rm_w, 0.0, None, ph, hd),
+              api.stage_gemm(1.0, ph, hd, pw2, desc(LPG_PACKED_B, LPG_BF16, h, d), 0.0, None, py, yd),
+              api.stage_unpack(py, yd, y, rm_y)]
+    api.lpg_chain(stages, api.LPG_CHAIN_PROPAGATED, None, 0, stream())
+    prop = host(y, np.float32, (m, d)).copy()
+    Hq = ref.round_bf16(ref.gemm(X, W1))
+    assert ref.rel_frobenius(prop, ref.gemm(Hq, W2)) <= 5e-3
+    need = api.lpg_chain_workspace_bytes(stages, api.LPG_CHAIN_CANONICAL)
+    ws = dev_empty(need)
+    y.fill_(0xFF)
+    api.lpg_chain(stages, api.LPG_CHAIN_CANONICAL, ws, need, stream())
+    assert np.array_equal(host(y, np.uint32, (m, d)), prop.view(np.uint32))
+    # the same chain entered through lpg_pack
+    px, pw1 = dev_bytes(ref.pack(raw_of(X, LPG_BF16), True, 2)), dev_bytes(ref.pack(raw_of(W1, LPG_BF16), False, 2))
+    y.fill_(0xFF)
+    packed_stages = [api.stage_gemm(1.0, px, desc(LPG_PACKED_A, LPG_BF16, m, d), pw1, desc(LPG_PACKED_B, LPG_BF16, d, h), 0.0, None, ph, hd)] + stages[1:]
+    api.lpg_chain(packed_stages, api.LPG_CHAIN_PROPAGATED, None, 0, stream())
+    assert np.array_equal(host(y, np.uint32, (m, d)), prop.view(np.uint32))
