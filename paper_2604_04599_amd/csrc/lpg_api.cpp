@@ -382,7 +382,6 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     GemmArgs g;
     g.o_keep_l = g.o_keep_r = 0;
     g.o_foff = g.o_koff = 0;
-    g.gm = 8;
     g.o_stream = 0;
     g.L = (const char *)(l_is_a ? A : B) + L.origin;
     g.R = (const char *)(l_is_a ? B : A) + R.origin;
@@ -439,7 +438,7 @@ static int do_gemm(float alpha, const void *A, const lpg_desc *a_d, const void *
     g.FLg = (int32_t)((L.F + 31) / 32);
     g.FRg = (int32_t)((R.F + 31) / 32);
     g.nkb = (int32_t)((ao.K + kb_of(in_dtype) - 1) / kb_of(in_dtype));
-    g.tiles_l = g.tiles_r = 0;
+    g.walk = TileWalk{};
     g.batch = nb;
     g.epi = epi;
     g.alpha = alpha;

@@ -246,21 +246,15 @@ __device__ __forceinline__ TileInfo decode_tile(const GemmArgs &p, uint32_t vb, 
     const uint32_t per = total / 8, rem = total % 8, x = vb % 8, idx = vb / 8;
     const uint32_t pid = (x < rem) ? x * (per + 1) + idx : rem * (per + 1) + (x - rem) * per + idx;
     TileInfo t;
-    t.b = (int)(pid / ntile);
-    const int tp = (int)(pid % ntile);
-    const int GM = p.gm;
-    const int width = GM * p.tiles_r;
-    const int first_l = (tp / width) * GM;
-    const int gsz = min(p.tiles_l - first_l, GM);
-    const int tl = first_l + (tp % width) % gsz;
-    const int tr = (tp % width) / gsz;
+    int tl, tr;
+    tile_at(p.walk, pid, t.b, tl, tr);
     t.gl0 = tl * TLG;
     t.gr0 = tr * TRG;
     t.nlg = min(TLG, p.FLg - t.gl0);
     t.nrg = max(0, min(TRG, p.FRg - t.gr0));
     // packed: first block of the tile; canonical: the operand's (slot's) first element
-    t.Lp = p.L + (int64_t)(t.b / p.l_div) * p.l_slot + (p.l_canon ? 0 : (int64_t)t.gl0 * p.l_gs);
-    t.Rp = p.R + (int64_t)(t.b / p.r_div) * p.r_slot + (p.r_canon ? 0 : (int64_t)t.gr0 * p.r_gs);
+    t.Lp = p.L + (int64_t)div_by((uint32_t)t.b, p.by_ldiv) * p.l_slot + (p.l_canon ? 0 : (int64_t)t.gl0 * p.l_gs);
+    t.Rp = p.R + (int64_t)div_by((uint32_t)t.b, p.by_rdiv) * p.r_slot + (p.r_canon ? 0 : (int64_t)t.gr0 * p.r_gs);
     return t;
 }
 
@@ -339,7 +333,7 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wl = wave % WL, wr = wave / WL;
 
-    const uint32_t ntile = (uint32_t)(p.tiles_l * p.tiles_r);
+    const uint32_t ntile = (uint32_t)(p.walk.tiles_l * p.walk.tiles_r);
     const uint32_t total = ntile * (uint32_t)p.batch;
     const uint32_t G = gridDim.x;
     const int spt = FS > kFragsPerBlock ? p.nkb / BPS : p.nkb * (kFragsPerBlock / FS);  // steps per tile (launcher: BPS divides nkb)
@@ -354,38 +348,47 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     // across waves: a group the tile does not have is replaced by the tile's last existing
     // group (its data is never used), which keeps every address inside the operand.
     const char *src[FPW];
+    // The two operands as the fragment fetch sees them (lpg_addr.h).  A source address is a
+    // wave-uniform part (which group, K block and fragment: scalar arithmetic) plus a part
+    // that depends on the lane alone and is the same for all fragments of an operand.
+    const FragOperand opL = {p.l_canon, p.l_foff, p.FL, p.l_gs, p.l_kbs, p.l_ld, IN::KF * IN::ES};
+    const FragOperand opR = {p.r_canon, p.r_foff, p.FR, p.r_gs, p.r_kbs, p.r_ld, IN::KF * IN::ES};
     auto aim = [&](const TileInfo &t) {
+        // per-lane parts, once per tile and operand
+        const int64_t laneL = p.l_canon ? frag_lane_canon(opL, lane) : (int64_t)frag_lane_packed(opL, lane);
+        const int64_t laneR = p.r_canon ? frag_lane_canon(opR, lane) : (int64_t)frag_lane_packed(opR, lane);
+        const bool hiL = frag_lane_hi(opL, lane) != 0, hiR = frag_lane_hi(opR, lane) != 0;
 #pragma unroll
         for (int i = 0; i < FPW; ++i) {
             const int fid = i * NW + wave;
-            const int grp = fid / FS, c = fid % FS;
+            const int c = fid % FS;
             const bool is_l = i < FPW_L;
-            if (is_l ? p.l_canon : p.r_canon) {
-                // Initial kernel: gather the fragment straight from the canonical matrix.  Lane
-                // (fl, h) of fragment c needs k = KF*c + 4*h .. +3 of free index fl: 16
-                // contiguous bytes of a k-contiguous fp32 row, which the transfer drops at
-                // lane*16 of the stage, i.e. in fragment order.  Rows past the end are
-                // replaced by the last row (never used).
-                const int g0 = is_l ? t.gl0 + grp : t.gr0 + grp - TLG;
-                const int row = min(g0 * 32 + (lane & 31), (is_l ? p.FL : p.FR) - 1);
-                const char *base = is_l ? t.Lp + (int64_t)row * p.l_ld : t.Rp + (int64_t)row * p.r_ld;
-                src[i] = base + c * (IN::KF * IN::ES) + (lane >> 5) * 16;
+            const int grp = is_l ? fid / FS : fid / FS - TLG;  // group of the tile, in its operand
+            const FragOperand &o = is_l ? opL : opR;
+            const int g0 = is_l ? t.gl0 : t.gr0, ng = is_l ? t.nlg : t.nrg;
+            const char *base = is_l ? t.Lp : t.Rp;
+            const int64_t lane_part = is_l ? laneL : laneR;
+            if (o.canon) {
+                // Initial kernel: the fragment comes straight from the canonical matrix.  Lane
+                // (fl, h) of fragment c needs k = KF*c + 4*h .. +3 of free index fl: 16 contiguous
+                // bytes of a k-contiguous fp32 row, which the transfer drops at lane*16 of the
+                // stage, i.e. in fragment order.  A group that ends past the operand's last row
+                // takes the per-lane form, which replaces the missing rows by the last one.
+                if (frag_group_inside(o, g0, grp)) src[i] = base + frag_uniform_canon(o, g0, grp, c) + lane_part;
+                else src[i] = base + frag_offset_reference(o, g0, ng, grp, c, lane);
             } else {
                 // A view whose free-dimension origin is foff rows off the 32-grid: view row v of a
-                // group is parent row v + foff, i.e. lane slot (v + foff) % 32 of this block or of the
-                // next one.  The transfer takes a source address per lane, so the shift costs nothing:
-                // each lane fetches its 16 bytes from where they are and drops them at lane * 16.
-                // Rows past the view's last row come from the last block the view touches (never used).
-                const int foff = is_l ? p.l_foff : p.r_foff;
-                const int row = (lane & 31) + foff;
-                const int g = is_l ? min(grp, t.nlg - 1) : max(0, min(grp - TLG, t.nrg - 1));
-                const int g0 = is_l ? t.gl0 : t.gr0;
-                const int gmax = (foff + (is_l ? p.FL : p.FR) - 1) >> 5;   // last block of the view, from its first
-                const int gsrc = min(g0 + g + (row >> 5), gmax) - g0;
-                const char *base = is_l ? t.Lp + (int64_t)gsrc * p.l_gs : t.Rp + (int64_t)gsrc * p.r_gs;
-                // fragment c of the step: fragment c % 4 of the step's K block c / 4
-                src[i] = base + (c / kFragsPerBlock) * (is_l ? p.l_kbs : p.r_kbs) + (c % kFragsPerBlock) * kFragBytes +
-                         ((lane >> 5) * 32 + (row & 31)) * 16;
+                // group is parent row v + foff, i.e. lane slot (v + foff) % 32 of this block or of
+                // the next one.  The transfer takes a source address per lane, so the shift costs
+                // one select per fragment: each lane fetches its 16 bytes from where they are and
+                // drops them at lane * 16.
+                const int64_t u0 = frag_uniform_packed(o, g0, ng, grp, c, 0);
+                if (o.foff == 0) {
+                    src[i] = base + u0 + lane_part;
+                } else {
+                    const int64_t u1 = frag_uniform_packed(o, g0, ng, grp, c, 1);
+                    src[i] = base + ((is_l ? hiL : hiR) ? u1 : u0) + lane_part;
+                }
             }
         }
     };
@@ -560,9 +563,9 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
 {
     constexpr bool BF = IN::ES == 2;
     constexpr int NS = ring_ns(BF, TLG, TRG, WL * WR), NS_LONE = BF ? NS : ring_ns_lone(TLG, TRG);
-    a.tiles_l = (a.FLg + TLG - 1) / TLG;
-    a.tiles_r = (a.FRg_out + TRG - 1) / TRG;
-    const int64_t total = (int64_t)a.tiles_l * a.tiles_r * a.batch;
+    a.walk.tiles_l = (a.FLg + TLG - 1) / TLG;
+    a.walk.tiles_r = (a.FRg_out + TRG - 1) / TRG;
+    const int64_t total = (int64_t)a.walk.tiles_l * a.walk.tiles_r * a.batch;
     if (total <= 0) return hipSuccess;
     if (total > 0x7fffffff) return hipErrorInvalidValue;  // the kernel counts tiles in 32 bits
     const TileCfg c = {TLG, TRG, WL, WR};
@@ -577,13 +580,15 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
         int best = 8;
         int64_t best_cost = -1;
         for (int gm : {8, 4, 2, 16}) {
-            const int64_t rows = gm < a.tiles_l ? gm : a.tiles_l;
-            const int64_t cols = (range + rows - 1) / rows < a.tiles_r ? (range + rows - 1) / rows : a.tiles_r;
+            const int64_t rows = gm < a.walk.tiles_l ? gm : a.walk.tiles_l;
+            const int64_t cols = (range + rows - 1) / rows < a.walk.tiles_r ? (range + rows - 1) / rows : a.walk.tiles_r;
             const int64_t cost = rows * TLG + cols * TRG;
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = gm; }
         }
         const int force = tune_get(LPG_TUNE_BAND);
-        a.gm = force > 0 ? force : best;
+        a.walk = tile_walk_setup(a.walk.tiles_l, a.walk.tiles_r, force > 0 ? force : best);
+        a.by_ldiv = div_setup((uint32_t)(a.l_div > 0 ? a.l_div : 1));
+        a.by_rdiv = div_setup((uint32_t)(a.r_div > 0 ? a.r_div : 1));
     }
     {
         // An output larger than the memory-side cache that nothing reads back soon (attention scores)
@@ -754,7 +759,7 @@ __global__ __launch_bounds__(256) void gemm_gather_kernel(GatherArgs ga)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wl = wave % WL, wr = wave / WL;
-    const uint32_t ntile = (uint32_t)(p.tiles_l * p.tiles_r);
+    const uint32_t ntile = (uint32_t)(p.walk.tiles_l * p.walk.tiles_r);
     const uint32_t total = ntile * (uint32_t)p.batch;
     const bool use_c = (p.beta != 0.0f) && p.Cin;
     const bool use_e = (p.epi == LPG_EPI_GATE_SILU) && p.Epi;
@@ -824,12 +829,14 @@ static hipError_t launch_gemm_gather_dtype(GatherArgs ga, hipStream_t st)
 {
     GemmArgs &a = ga.g;
     constexpr int TLG = 4, TRG = 4;
-    a.tiles_l = (a.FLg + TLG - 1) / TLG;
-    a.tiles_r = (a.FRg_out + TRG - 1) / TRG;
-    const int64_t total = (int64_t)a.tiles_l * a.tiles_r * a.batch;
+    a.walk.tiles_l = (a.FLg + TLG - 1) / TLG;
+    a.walk.tiles_r = (a.FRg_out + TRG - 1) / TRG;
+    const int64_t total = (int64_t)a.walk.tiles_l * a.walk.tiles_r * a.batch;
     if (total <= 0) return hipSuccess;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
-    a.gm = 8;
+    a.walk = tile_walk_setup(a.walk.tiles_l, a.walk.tiles_r, 8);
+    a.by_ldiv = div_setup((uint32_t)(a.l_div > 0 ? a.l_div : 1));
+    a.by_rdiv = div_setup((uint32_t)(a.r_div > 0 ? a.r_div : 1));
     a.o_stream = 0;
     constexpr size_t lds = 2 * (size_t)(TLG + TRG) * kFragsPerBlock * kFragBytes;   // 64 KiB
     int64_t grid = (int64_t)device_info().ncu * 2;

@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include "../../include/lpg.h"
+#include "lpg_addr.h"
 
 namespace lpg {
 
@@ -109,14 +110,15 @@ struct GemmArgs {
     int32_t FLg, FRg;                // 32-groups present in L and R
     int32_t FRg_out;                 // 32-groups of out's contraction dim incl. block padding
     int32_t nkb;                     // contraction blocks of the product
-    int32_t tiles_l, tiles_r, batch;
+    int32_t batch;
     int32_t epi;
     float alpha, beta;
     int32_t o_keep_l, o_keep_r;      // packed out: leave elements past FL / past FR untouched
     // o_canon == 2: packed out whose origin is off the 32 / KB grid; Out points at the block holding
     // the origin, the view starts o_foff free indices and o_koff contraction indices into it
     int32_t o_foff, o_koff;
-    int32_t gm;                      // tile rows per band of the tile walk (set by the launcher)
+    TileWalk walk;                   // order in which the launch's tiles are walked (set by the launcher)
+    DivBy by_ldiv, by_rdiv;          // division by l_div / r_div (set by the launcher)
     int32_t o_stream;                // plain packed output written with streaming (non-temporal) stores
 };
 
