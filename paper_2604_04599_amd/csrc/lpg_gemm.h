@@ -312,9 +312,10 @@ static_for<WTL * WTR>([&](auto I) {                                             
 // last fragment of the current step is multiplied, so no LDS latency is exposed after the
 // barrier; the barrier of a step then also publishes the step after it.
 template <typename IN, typename OUT, int TLG, int TRG, int WL, int WR, int FS, int NS, bool XPF>
-__global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
+__global__ __launch_bounds__(WL *WR * 64, 2) void gemm_kernel(GemmArgs p)
 {
     static_assert(!XPF || NS >= 3, "cross-step prefetch needs a landed stage beyond the current one");
+    constexpr int DEPTH = NS - 1;  // steps the copy side runs ahead of the multiply side
     constexpr int NW = WL * WR;
     constexpr int WTL = TLG / WL, WTR = TRG / WR;
     constexpr int NFRAG = (TLG + TRG) * FS;  // fragments per stage
@@ -340,7 +341,7 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     if (blockIdx.x >= total) return;
     const uint32_t my_tiles = (total - blockIdx.x + G - 1) / G;
 
-    auto decode = [&](uint32_t vb) -> TileInfo { return decode_tile<TLG, TRG>(p, vb, total, ntile); };
+    auto decode = [&](uint32_t vb) __attribute__((always_inline)) -> TileInfo { return decode_tile<TLG, TRG>(p, vb, total, ntile); };
 
     // ---- copy side.  Wave w copies fragments w, w + NW, ... of a stage; src[i] is this
     // lane's address of its i-th fragment at the step the copy cursor stands on.  Every wave
@@ -353,44 +354,45 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     // that depends on the lane alone and is the same for all fragments of an operand.
     const FragOperand opL = {p.l_canon, p.l_foff, p.FL, p.l_gs, p.l_kbs, p.l_ld, IN::KF * IN::ES};
     const FragOperand opR = {p.r_canon, p.r_foff, p.FR, p.r_gs, p.r_kbs, p.r_ld, IN::KF * IN::ES};
-    auto aim = [&](const TileInfo &t) {
+    auto aim = [&](const TileInfo &t) __attribute__((always_inline)) {
         // per-lane parts, once per tile and operand
         const int64_t laneL = p.l_canon ? frag_lane_canon(opL, lane) : (int64_t)frag_lane_packed(opL, lane);
         const int64_t laneR = p.r_canon ? frag_lane_canon(opR, lane) : (int64_t)frag_lane_packed(opR, lane);
         const bool hiL = frag_lane_hi(opL, lane) != 0, hiR = frag_lane_hi(opR, lane) != 0;
-#pragma unroll
-        for (int i = 0; i < FPW; ++i) {
+        static_for<FPW>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            constexpr bool is_l = i < FPW_L;
             const int fid = i * NW + wave;
             const int c = fid % FS;
-            const bool is_l = i < FPW_L;
             const int grp = is_l ? fid / FS : fid / FS - TLG;  // group of the tile, in its operand
-            const FragOperand &o = is_l ? opL : opR;
             const int g0 = is_l ? t.gl0 : t.gr0, ng = is_l ? t.nlg : t.nrg;
             const char *base = is_l ? t.Lp : t.Rp;
             const int64_t lane_part = is_l ? laneL : laneR;
-            if (o.canon) {
+            const bool canon = is_l ? p.l_canon != 0 : p.r_canon != 0;
+            const int foff = is_l ? p.l_foff : p.r_foff;
+            if (canon) {
                 // Initial kernel: the fragment comes straight from the canonical matrix.  Lane
                 // (fl, h) of fragment c needs k = KF*c + 4*h .. +3 of free index fl: 16 contiguous
                 // bytes of a k-contiguous fp32 row, which the transfer drops at lane*16 of the
                 // stage, i.e. in fragment order.  A group that ends past the operand's last row
                 // takes the per-lane form, which replaces the missing rows by the last one.
-                if (frag_group_inside(o, g0, grp)) src[i] = base + frag_uniform_canon(o, g0, grp, c) + lane_part;
-                else src[i] = base + frag_offset_reference(o, g0, ng, grp, c, lane);
+                if (frag_group_inside(is_l ? opL : opR, g0, grp)) src[i] = base + frag_uniform_canon(is_l ? opL : opR, g0, grp, c) + lane_part;
+                else src[i] = base + frag_offset_reference(is_l ? opL : opR, g0, ng, grp, c, lane);
             } else {
                 // A view whose free-dimension origin is foff rows off the 32-grid: view row v of a
                 // group is parent row v + foff, i.e. lane slot (v + foff) % 32 of this block or of
                 // the next one.  The transfer takes a source address per lane, so the shift costs
                 // one select per fragment: each lane fetches its 16 bytes from where they are and
                 // drops them at lane * 16.
-                const int64_t u0 = frag_uniform_packed(o, g0, ng, grp, c, 0);
-                if (o.foff == 0) {
+                const int64_t u0 = frag_uniform_packed(is_l ? opL : opR, g0, ng, grp, c, 0);
+                if (foff == 0) {
                     src[i] = base + u0 + lane_part;
                 } else {
-                    const int64_t u1 = frag_uniform_packed(o, g0, ng, grp, c, 1);
+                    const int64_t u1 = frag_uniform_packed(is_l ? opL : opR, g0, ng, grp, c, 1);
                     src[i] = base + ((is_l ? hiL : hiR) ? u1 : u0) + lane_part;
                 }
             }
-        }
+        });
     };
     uint32_t c_tiles_left = my_tiles;  // tiles the copy cursor still has to start or finish
     uint32_t c_vb = blockIdx.x;
@@ -399,43 +401,48 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
     int pending = 0;                   // steps copied (or in flight) and not yet multiplied
     bool c_live = spt > 0;
     // fragment i of the step the copy cursor stands on -> ring stage c_st
-    auto copy_issue = [&](int i) {
-        lds_dma16(src[i], sbase + c_st * STAGE + (i * NW + wave) * kFragBytes);
+    auto copy_issue = [&](int i) __attribute__((always_inline)) {
+        // (the ring stage is the same for all lanes; said explicitly, because the compiler does not always see it)
+        lds_dma16(src[i], __builtin_amdgcn_readfirstlane(sbase + c_st * STAGE + (i * NW + wave) * kFragBytes));
     };
-    // move the copy cursor one step on
-    auto copy_advance = [&]() {
+    // Address increments of a step inside a tile, fixed for the launch.  Whole K blocks per step:
+    // one increment; half blocks: from the first half of a block to its second half (d*_in), and
+    // from there to the first half of the next block (d*_out).  Canonical rows are contiguous along k.
+    const int64_t dl_in = p.l_canon ? FS * IN::KF * IN::ES : (FS >= kFragsPerBlock ? BPS * p.l_kbs : (int64_t)FS * kFragBytes);
+    const int64_t dr_in = p.r_canon ? FS * IN::KF * IN::ES : (FS >= kFragsPerBlock ? BPS * p.r_kbs : (int64_t)FS * kFragBytes);
+    const int64_t dl_out = (p.l_canon || FS >= kFragsPerBlock) ? dl_in : p.l_kbs - (kFragsPerBlock - FS) * kFragBytes;
+    const int64_t dr_out = (p.r_canon || FS >= kFragsPerBlock) ? dr_in : p.r_kbs - (kFragsPerBlock - FS) * kFragBytes;
+    // Move the copy cursor one step on: inside its tile (FPW additions), or on to its next tile
+    // (tile decode, fresh addresses).
+    auto advance_in_tile = [&]() __attribute__((always_inline)) {
         c_st = (c_st + 1 == NS) ? 0 : c_st + 1;
         ++pending;
-        if (++c_s == spt) {  // next tile
-            c_s = 0;
-            c_vb += G;
-            if (--c_tiles_left == 0) c_live = false;
-            else aim(decode(c_vb));
-        } else {             // next step of the same tile
-            int64_t dl, dr;
-            if (FS >= kFragsPerBlock) {       // whole K blocks per step
-                dl = BPS * p.l_kbs;
-                dr = BPS * p.r_kbs;
-            } else if ((c_s & 1) == 0) {      // first fragments of the next K block
-                dl = p.l_kbs - (kFragsPerBlock - FS) * kFragBytes;
-                dr = p.r_kbs - (kFragsPerBlock - FS) * kFragBytes;
-            } else {                          // second half of the same K block
-                dl = dr = FS * kFragBytes;
-            }
-            if (p.l_canon) dl = FS * IN::KF * IN::ES;  // canonical rows are contiguous along k
-            if (p.r_canon) dr = FS * IN::KF * IN::ES;
+        ++c_s;
+        const bool leaving = (c_s & 1) == 0;  // (half-block steps) the step just copied was a block's second half
+        const int64_t dl = leaving ? dl_out : dl_in, dr = leaving ? dr_out : dr_in;
 #pragma unroll
-            for (int i = 0; i < FPW; ++i) src[i] += (i < FPW_L) ? dl : dr;
-        }
+        for (int i = 0; i < FPW; ++i) src[i] += (i < FPW_L) ? dl : dr;
     };
-    auto copy_step = [&]() {
+    auto advance_to_next_tile = [&]() __attribute__((always_inline)) {
+        c_st = (c_st + 1 == NS) ? 0 : c_st + 1;
+        ++pending;
+        c_s = 0;
+        c_vb += G;
+        if (--c_tiles_left == 0) c_live = false;
+        else aim(decode(c_vb));
+    };
+    auto copy_advance = [&]() __attribute__((always_inline)) {
+        if (c_s + 1 == spt) advance_to_next_tile();
+        else advance_in_tile();
+    };
+    auto copy_step = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < FPW; ++i) copy_issue(i);
         copy_advance();
     };
     aim(decode(c_vb));
 #pragma unroll
-    for (int j = 0; j < NS - 1; ++j)
+    for (int j = 0; j < DEPTH; ++j)
         if (c_live) copy_step();
 
     const bool use_c = (p.beta != 0.0f) && p.Cin;
@@ -466,7 +473,9 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[a][q][e] = 0.0f;
 
-        for (int s = 0; s < spt; ++s) {
+        // One step of the tile.  ADV says where the copy cursor goes after it: 0 = wherever it must
+        // (the general case), 1 = on inside its tile, 2 = to its next tile.
+        auto step = [&](const int ADV) __attribute__((always_inline)) {
             // Wait until this wave's transfers of the step that must be readable have landed
             // (XPF: the step after the current one; otherwise the current one); later steps
             // stay in flight (transfers complete in issue order).
@@ -527,7 +536,23 @@ __global__ __launch_bounds__(WL *WR * 64) void gemm_kernel(GemmArgs p)
             }
             st = stn;
             --pending;
-            if (c_live) copy_advance();
+            if (c_live) {
+                if (ADV == 0) copy_advance();
+                else if (ADV == 1) advance_in_tile();
+                else advance_to_next_tile();
+            }
+        };
+        if (spt > DEPTH) {
+            // The copy cursor runs DEPTH steps ahead, so with more than DEPTH steps per tile it leaves
+            // this tile exactly once, after step spt - DEPTH - 1.  That step stands alone between two
+            // loops whose own cursor movement is a handful of additions: the tile decode and the
+            // fresh addresses are then not part of any loop body.
+            int s = 0;
+            for (; s < spt - DEPTH - 1; ++s) step(1);
+            step(2);
+            for (++s; s < spt; ++s) step(1);
+        } else {
+            for (int s = 0; s < spt; ++s) step(0);
         }
 
         // ---- epilogue
@@ -628,6 +653,12 @@ static hipError_t launch_gemm_cfg(GemmArgs a, hipStream_t st)
         // in four stages with it: half the barriers in the same LDS; measured 2-8 % faster on
         // 2048^3, 4096 x 2048 x 2048, 16384 x 1024 x 1024 and ragged shapes.  The tuning hook
         // LPG_TUNE_BF16_WHOLE_BLOCK_STEPS = 0 restores the half-block ring.
+        if (tune_get(LPG_TUNE_BF16_WHOLE_BLOCK_STEPS) != 0) return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, 2, 4>(a, grid, st);
+    }
+    if constexpr (BF && TLG == 8 && TRG == 8) {
+        // bf16, 256 x 256 (eight waves, the whole compute unit): whole K blocks in two stages of
+        // 64 KiB as well, half as many barriers as the ring of five half-block stages: 2-3 % on the
+        // gate / up projections (4096 x 2048 x 8192).  LPG_TUNE_BF16_WHOLE_BLOCK_STEPS = 0: the ring.
         if (tune_get(LPG_TUNE_BF16_WHOLE_BLOCK_STEPS) != 0) return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, 2, 4>(a, grid, st);
     }
     return launch_gemm_ring<IN, OUT, TLG, TRG, WL, WR, NS>(a, grid, st);
