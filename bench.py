@@ -537,7 +537,7 @@ def main():
     t_gemm, gemm_flops, gemm_bytes = time_gemm_launches(ch, max(3, min(args.steps, 40)))
     achieved = gemm_flops / t_gemm / 1e12
     traffic, traffic_src = profile_traffic("gemm_kernel")
-    roofline = {"bound": "mfma", "kernel": "gemm_kernel<F32,F32,256x128 tile> (every GEMM of the chain)",
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel<F32,F32,256x256 tile, 8 waves> (every GEMM of the chain)",
                 "achieved": round(achieved, 2), "peak": PEAK_TFLOPS["f32"], "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_TFLOPS["f32"], 4), "avg_launch_us": round(t_gemm * 1e6, 2),
                 "flops_per_launch": gemm_flops, "traffic": traffic, "algorithmic_bytes": gemm_bytes,
