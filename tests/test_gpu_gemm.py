@@ -231,6 +231,45 @@ def test_every_tile_configuration(cfg, tune):
     assert np.array_equal(got, ref.gemm(A, B))
 
 
+_LONG_K_CASES = {}
+
+
+def _long_k_case(key):
+    """Inputs and oracle results of the long-contraction cases, computed once per process."""
+    if key not in _LONG_K_CASES:
+        m, n, k = key
+        rng = np.random.default_rng(m + 3 * n + 7 * k)
+        A = rng.integers(-3, 4, (m, k)).astype(np.float32)     # small integers: every product and sum is exact in
+        B = rng.integers(-3, 4, (k, n)).astype(np.float32)     # fp32 and in bf16 inputs with fp32 accumulation
+        _LONG_K_CASES[key] = (A, B, ref.gemm(A, B))
+    return _LONG_K_CASES[key]
+
+
+@pytest.mark.parametrize("rings", [(0, 0), (1, 1)])
+@pytest.mark.parametrize("cfg", range(8))
+def test_long_contractions_in_every_ring_variant(cfg, rings, tune):
+    """Contractions long enough that the copy cursor of every staging ring (up to four steps ahead) switches
+    tile in the middle of a tile's step loop, in every tile configuration and with the whole-block / two-block
+    step variants on and off: one shape of few tiles (the deeper rings of lone workgroups), one of more tiles
+    than persistent workgroups (every workgroup walks several tiles, so the peeled tile-switch step runs with a
+    live cursor), both ragged.  Integer inputs, so the result is exact in both dtypes and must equal the oracle
+    bit for bit."""
+    tune(api.LPG_TUNE_TILE, cfg)
+    tune(api.LPG_TUNE_BF16_WHOLE_BLOCK_STEPS, rings[0])
+    tune(api.LPG_TUNE_TWO_BLOCK_STEPS, rings[1])
+    many = (4200, 4136, 330) if cfg in (4, 5, 6) else (2100, 2070, 330)
+    for key in ((300, 520, 1100), many):
+        A, B, want = _long_k_case(key)
+        got, raw, _ = run_gemm(A, B, LPG_F32, LPG_F32, LPG_PACKED_A)
+        assert np.array_equal(got, want), (cfg, rings, key, "f32")
+        assert np.array_equal(raw, ref.pack(got.astype(np.float32), True, 4))
+        got, _, _ = run_gemm(A, B, LPG_BF16, LPG_F32, LPG_PACKED_B)
+        assert np.array_equal(got, want), (cfg, rings, key, "bf16 -> f32")
+    A, B, want = _long_k_case((300, 520, 1100))
+    got, _, _ = run_gemm(A, B, LPG_BF16, LPG_BF16, LPG_PACKED_A)
+    assert np.array_equal(got, ref.round_bf16(want)), (cfg, rings, "bf16")
+
+
 # ---- fused boundary kernels: canonical operands read / written by the GEMM itself
 
 def _canon_dev(a, ld):
