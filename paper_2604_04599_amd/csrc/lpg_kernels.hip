@@ -1227,14 +1227,15 @@ int choose_gemm_config(const GemmArgs &a, int in_dtype)
     const bool bf16 = in_dtype == LPG_BF16;
     // A contraction of at most 256 (attention scores, whatever the head_dim) with at least two
     // tiles per compute unit makes the launch a stream of epilogues bound by the stores; the
-    // cost model has no term for that.  Measured on
-    // 32 heads of 2048^2 / 4096^2 scores: two workgroups per compute unit, so that one stores
-    // while the other multiplies, with 128 x 256 tiles in bf16 (255 us against 276-365 us for
-    // the others) and 128 x 128 in fp32 (187 against 195-219).
+    // cost model has no term for that.  Measured on 32 heads of 2048^2 / 4096^2 scores: two
+    // workgroups per compute unit, so that one stores while the other multiplies, with 256 x 128
+    // tiles in bf16 (192-205 us on 4096^2 against 201-215 for 128 x 256 and 197-222 for the
+    // others) and 128 x 128 in fp32 (174-185 against 180-199).
     {
-        const TileCfg &c = kCfgs[bf16 ? 5 : 3];
+        const int pick = bf16 ? 4 : 3;
+        const TileCfg &c = kCfgs[pick];
         const int64_t tiles = (int64_t)((a.FLg + c.tlg - 1) / c.tlg) * ((a.FRg_out + c.trg - 1) / c.trg) * a.batch;
-        if (a.nkb * (bf16 ? 64 : 32) <= 256 && tiles >= 512) return bf16 ? 5 : 3;
+        if (a.nkb * (bf16 ? 64 : 32) <= 256 && tiles >= 512) return pick;
     }
     int best = 3;
     double best_cost = 1e300;
