@@ -258,6 +258,18 @@ def measure(name, shape_over=None, options=None, with_stages=False, extras=True)
             ach = chains.build(name, inp, shape, flash=True, **options)
             res["fused_attention_ms"] = round(time_for(ach, api.LPG_CHAIN_PROPAGATED, 0.2)[0] * 1e3, 4)
             del ach
+        if name == "two_gemm":
+            # the launch-bound chain replayed from a HIP graph (one graph launch per step)
+            replay = ch.capture()
+            for _ in range(20):
+                replay()
+            torch.cuda.synchronize()
+            reps = 2000
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                replay()
+            torch.cuda.synchronize()
+            res["graph_replay_ms_per_step"] = round((time.perf_counter() - t0) / reps * 1e3, 4)
         torch.cuda.empty_cache()
     return res, ch, inp, shape
 
