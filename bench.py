@@ -258,6 +258,11 @@ def measure(name, shape_over=None, options=None, with_stages=False, extras=True)
             ach = chains.build(name, inp, shape, flash=True, **options)
             res["fused_attention_ms"] = round(time_for(ach, api.LPG_CHAIN_PROPAGATED, 0.2)[0] * 1e3, 4)
             del ach
+        if (name == "llama_layer" and not options) or (name == "attention" and options.get("causal") and not options.get("flash")):
+            # the three attention stages cut into four blocks of query rows that stop at the causal diagonal
+            bch = chains.build(name, inp, shape, causal_blocks=4, **options)
+            res["causal_row_blocks_ms"] = round(time_for(bch, api.LPG_CHAIN_PROPAGATED, 0.2)[0] * 1e3, 4)
+            del bch
         if name == "two_gemm":
             # the launch-bound chain replayed from a HIP graph (one graph launch per step)
             replay = ch.capture()

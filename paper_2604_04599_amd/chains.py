@@ -198,11 +198,13 @@ def build_mlp(inp, shape, fused=False):
     return ch
 
 
-def build_attention(inp, shape, fused=False, softmax=False, causal=False, flash=False):
+def build_attention(inp, shape, fused=False, softmax=False, causal=False, flash=False, causal_blocks=1):
     """softmax=False: O = (Q K^T / sqrt(dh)) V, the two chained GEMMs alone.  softmax=True: the
     scale moves into a softmax stage (optionally causally masked) that runs in place on the
     packed scores between the two GEMMs.  flash=True: one lpg_attention_packed stage replaces the
-    two or three stages (with or without the softmax), and the scores are never stored."""
+    two or three stages (with or without the softmax), and the scores are never stored.
+    causal_blocks = n > 1 (with softmax and causal): the three stages run per block of t/n query
+    rows on views that end at the last key those rows may see (build_llama_layer has the same)."""
     nh, t, dh = shape["heads"], shape["t"], shape["dh"]
     scale = 1.0 / float(np.sqrt(dh))
     alpha = 1.0 if softmax else scale
@@ -237,6 +239,22 @@ def build_attention(inp, shape, fused=False, softmax=False, causal=False, flash=
     ch.add(api.stage_pack(v, rm, pv, vd))
     if flash:
         ch.add(api.stage_attention(pq, qd, pk, ktd, pv, vd, po, od, scale, causal, softmax=softmax))
+        ch.add(api.stage_unpack(po, od, out, rm))
+        return ch
+    if causal_blocks > 1:
+        rb = t // causal_blocks
+        if not (softmax and causal) or t % causal_blocks or rb % 32:
+            raise ValueError("causal_blocks needs the causal softmax stage and blocks of a multiple of 32 rows")
+        for i in range(causal_blocks):
+            r0, kc = i * rb, (i + 1) * rb              # query rows [r0, r0 + rb) see keys [0, kc)
+            q_i = desc(LPG_PACKED_A, LPG_F32, rb, dh, parent=(t, dh), origin=(r0, 0), batch=nh, batch_stride=qd.batch_stride)
+            kt_i = desc(LPG_PACKED_B, LPG_F32, dh, kc, parent=(dh, t), batch=nh, batch_stride=ktd.batch_stride)
+            s_i = desc(LPG_PACKED_A, LPG_F32, rb, kc, parent=(t, t), origin=(r0, 0), batch=nh, batch_stride=sd.batch_stride)
+            v_i = desc(LPG_PACKED_B, LPG_F32, kc, dh, parent=(t, dh), batch=nh, batch_stride=vd.batch_stride)
+            o_i = desc(LPG_PACKED_A, LPG_F32, rb, dh, parent=(t, dh), origin=(r0, 0), batch=nh, batch_stride=od.batch_stride)
+            ch.add(api.stage_gemm(alpha, pq, q_i, pk, kt_i, 0.0, None, ps, s_i))
+            ch.add(api.stage_softmax(ps, ps, s_i, scale, True))
+            ch.add(api.stage_gemm(1.0, ps, s_i, pv, v_i, 0.0, None, po, o_i))
         ch.add(api.stage_unpack(po, od, out, rm))
         return ch
     ch.add(api.stage_gemm(alpha, pq, qd, pk, ktd, 0.0, None, ps, sd))
@@ -378,12 +396,15 @@ def build_linear_chain(x, weights, dtype=LPG_F32, fused=False):
     return ch
 
 
-def build_llama_layer(inp, shape, fused=False, flash=False):
+def build_llama_layer(inp, shape, fused=False, flash=False, causal_blocks=1):
     """The decoder layer with every step between its GEMMs on the packed layout: RMSNorm, Q/K/V
     projections, RoPE on Q and K, causal softmax attention with grouped keys/values, output
     projection + residual, RMSNorm, gated MLP + residual.  bf16 intermediates, fp32 math.
     fused=True folds SiLU(gate)*up into the up projection's epilogue; flash=True runs the attention
-    block as one lpg_attention_packed stage (no score matrix)."""
+    block as one lpg_attention_packed stage (no score matrix).  causal_blocks = n > 1 cuts the
+    three attention stages into n blocks of t/n query rows, each a view of the same packed
+    buffers that ends at the last key its rows may see: the blocks of S above the causal diagonal
+    are then neither computed, nor normalised, nor multiplied (they only ever held zeros)."""
     t, hid, nq, nkv, ffn = shape["t"], shape["hidden"], shape["n_q"], shape["n_kv"], shape["ffn"]
     eps, base = 1.0 / shape["inv_eps"], float(shape["rope_base"])
     dh = hid // nq
@@ -430,6 +451,21 @@ def build_llama_layer(inp, shape, fused=False, flash=False):
     o_view = desc(LPG_PACKED_A, B, t, dh, parent=(t, hid), batch=nq, batch_step=(0, dh))
     if flash:
         ch.add(api.stage_attention(pq, q_view, pk, kt_view, pv, v_view, po, o_view, 1.0 / float(np.sqrt(dh)), True))
+    elif causal_blocks > 1:
+        rb = t // causal_blocks
+        if t % causal_blocks or rb % 64:
+            raise ValueError("causal_blocks must cut the rows into multiples of 64")
+        selems = _packed_elems(B, t, t)
+        for i in range(causal_blocks):
+            r0, kc = i * rb, (i + 1) * rb              # query rows [r0, r0 + rb) see keys [0, kc)
+            q_i = desc(LPG_PACKED_A, B, rb, dh, parent=(t, hid), origin=(r0, 0), batch=nq, batch_step=(0, dh))
+            kt_i = desc(LPG_PACKED_B, B, dh, kc, parent=(kvw, t), batch=nq, batch_div=rep, batch_step=(dh, 0))
+            s_i = desc(LPG_PACKED_A, B, rb, kc, parent=(t, t), origin=(r0, 0), batch=nq, batch_stride=selems)
+            v_i = desc(LPG_PACKED_B, B, kc, dh, parent=(t, kvw), batch=nq, batch_div=rep, batch_step=(0, dh))
+            o_i = desc(LPG_PACKED_A, B, rb, dh, parent=(t, hid), origin=(r0, 0), batch=nq, batch_step=(0, dh))
+            ch.add(api.stage_gemm(1.0, pq, q_i, pk, kt_i, 0.0, None, ps, s_i))
+            ch.add(api.stage_softmax(ps, ps, s_i, 1.0 / float(np.sqrt(dh)), True))
+            ch.add(api.stage_gemm(1.0, ps, s_i, pv, v_i, 0.0, None, po, o_i))
     else:
         ch.add(api.stage_gemm(1.0, pq, q_view, pk, kt_view, 0.0, None, ps, sd))
         ch.add(api.stage_softmax(ps, ps, sd, 1.0 / float(np.sqrt(dh)), True))

@@ -194,13 +194,46 @@ def test_llama_layer_small_both_modes():
     assert ref.rel_frobenius(fch.output("Y"), y) <= 1e-2
 
 
-def test_llama_layer_full_size_sampled_rows():
+@pytest.mark.parametrize("blocks", [1, 4])
+def test_llama_layer_full_size_sampled_rows(blocks):
     inp, shape = inputs.make("llama_layer")
-    ch = chains.build("llama_layer", inp, shape)
+    ch = chains.build("llama_layer", inp, shape, causal_blocks=blocks)
     ch.run(LPG_CHAIN_PROPAGATED)
     y = ch.output("Y").copy()
     rows = spread_rows(shape["t"], 11)
     _check_llama(inp, shape, ch, y, rows)
+
+
+@pytest.mark.parametrize("blocks", [2, 4])
+def test_llama_layer_causal_row_blocks(blocks):
+    """The attention stages cut into blocks of query rows, each a view that ends at the last key
+    its rows may see: same layer output and same probabilities below the diagonal as the uncut
+    chain, in both modes, and the blocks of S above the block diagonal are never touched."""
+    inp, shape = inputs.make("llama_layer", t=256, hidden=256, n_q=4, n_kv=2, ffn=320)
+    whole = chains.build("llama_layer", inp, shape)
+    whole.run(LPG_CHAIN_PROPAGATED)
+    y_whole, p_whole = whole.output("Y").copy(), whole.fetch("S")
+    ch = chains.build("llama_layer", inp, shape, causal_blocks=blocks)
+    assert len(ch.stages) == len(whole.stages) + 3 * (blocks - 1)
+    ch.bufs["S"][0].fill_(0xA5)                      # bf16 pattern 0xA5A5 = -7.2e-17 wherever nothing is written
+    ch.run(LPG_CHAIN_PROPAGATED)
+    y = ch.output("Y").copy()
+    _check_llama(inp, shape, ch, y, None)
+    assert ref.rel_frobenius(y, y_whole) <= 5e-3
+    p = ch.fetch("S")
+    rb = shape["t"] // blocks
+    untouched = np.float32(np.frombuffer(np.array([0xA5A50000], dtype=np.uint32).tobytes(), dtype=np.float32)[0])
+    for i in range(blocks):
+        r, kc = slice(i * rb, (i + 1) * rb), (i + 1) * rb
+        assert ref.rel_frobenius(p[:, r, :kc], p_whole[:, r, :kc]) <= 5e-3
+        assert np.all(np.triu(p[:, r, :kc], i * rb + 1) == 0.0)       # masked inside the block's own columns
+        assert np.all(p[:, r, kc:] == untouched)                      # never computed, never written
+    ch.bufs["S"][0].fill_(0xA5)
+    ch.outputs["Y"].fill_(float("nan"))
+    ch.run(LPG_CHAIN_CANONICAL)
+    canon = ch.output("Y").copy()
+    assert ref.rel_frobenius(canon, y) <= 1e-2
+    assert np.all(ch.fetch("S")[:, :rb, rb:] == untouched)
 
 
 @pytest.mark.parametrize("seed", range(48))

@@ -137,9 +137,35 @@ def test_attention_chain_with_softmax(causal, fused):
         assert ref.rel_frobenius(canon[h], want["O"][h]) <= 3e-5
 
 
-def test_attention_chain_with_softmax_full_size_sampled_heads():
+@pytest.mark.parametrize("blocks", [2, 6])
+def test_attention_chain_in_causal_row_blocks(blocks):
+    """The three stages per block of query rows, on views that end at the causal diagonal: the
+    oracle's O in both modes, the oracle's probabilities inside the blocks, and nothing written
+    above the block diagonal."""
+    inp, shape = inputs.make("attention", heads=3, t=192, dh=64)
+    ch = chains.build("attention", inp, shape, softmax=True, causal=True, causal_blocks=blocks)
+    ch.bufs["S"][0].view(torch.float32).fill_(-77.0)
+    ch.run(LPG_CHAIN_PROPAGATED)
+    prop = ch.output("O").copy()
+    p = ch.fetch("S")
+    ch.outputs["O"].fill_(float("nan"))
+    ch.run(LPG_CHAIN_CANONICAL)
+    canon = ch.output("O").copy()
+    want = workloads.attention(inp, softmax=True, causal=True, keep_s=True)
+    rb = shape["t"] // blocks
+    for h in range(shape["heads"]):
+        for i in range(blocks):
+            r, kc = slice(i * rb, (i + 1) * rb), (i + 1) * rb
+            assert ref.rel_frobenius(p[h][r, :kc], want["S"][h][r, :kc]) <= 2e-5
+            assert np.all(p[h][r, kc:] == -77.0)
+        assert ref.rel_frobenius(prop[h], want["O"][h]) <= 3e-5
+        assert ref.rel_frobenius(canon[h], want["O"][h]) <= 3e-5
+
+
+@pytest.mark.parametrize("blocks", [1, 4])
+def test_attention_chain_with_softmax_full_size_sampled_heads(blocks):
     inp, shape = inputs.make("attention")
-    ch = chains.build("attention", inp, shape, softmax=True, causal=True)
+    ch = chains.build("attention", inp, shape, softmax=True, causal=True, causal_blocks=blocks)
     ch.run(LPG_CHAIN_PROPAGATED)
     prop = ch.output("O").copy()
     heads = [0, 17, 31]
