@@ -226,8 +226,8 @@ def measure(name, shape_over=None, options=None, with_stages=False, extras=True)
     (mp, ap, np_), (mc, ac, nc) = both[api.LPG_CHAIN_PROPAGATED], both[api.LPG_CHAIN_CANONICAL]
     tf = flops / mp / 1e12
     nbytes = sum(stage_bytes(s) for s in ch.stages)
-    res = {"dtype": dt, "gemm_gflop": round(flops / 1e9, 2), "ms": round(mp * 1e3, 4), "ms_mean": round(ap * 1e3, 4),
-           "steps_timed": np_, "tflops": round(tf, 2), "pct_mfma_peak": round(100 * tf / PEAK_TFLOPS[dt], 2),
+    res = {"dtype": dt, "gemm_gflop": round(flops / 1e9, 2), "ms": round(mp * 1e3, 4),
+           "tflops": round(tf, 2), "pct_mfma_peak": round(100 * tf / PEAK_TFLOPS[dt], 2),
            "canonical_ms": round(mc * 1e3, 4), "speedup_vs_canonical": round(mc / mp, 3),
            "hbm_frac": round(nbytes / mp / 1e9 / HBM_PEAK_GBPS, 3)}
     if dt == "bf16":
@@ -559,10 +559,9 @@ def main():
                 "frac": round(achieved / PEAK_TFLOPS["f32"], 4), "avg_launch_us": round(t_gemm * 1e6, 2),
                 "flops_per_launch": gemm_flops, "traffic": traffic, "algorithmic_bytes": gemm_bytes,
                 "traffic_over_algorithmic": round(traffic / gemm_bytes, 2) if traffic else None,
-                "traffic_unit": "L2-miss bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel's "
-                                "reading; re-fetches by the eight L2s are mostly served by the memory-side cache), "
-                                f"from {traffic_src}, not measured in this run" if traffic else None}
-    head = {"dtype": "f32", "gemm_gflop": round(flops / 1e9, 2), "ms": round(mp * 1e3, 4), "ms_mean": round(apm * 1e3, 4),
+                "traffic_unit": "L2-miss bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated on a copy "
+                                f"kernel), from {traffic_src}, not measured in this run" if traffic else None}
+    head = {"dtype": "f32", "gemm_gflop": round(flops / 1e9, 2), "ms": round(mp * 1e3, 4),
             "steps_timed": np_, "tflops": round(flops / mp / 1e12, 2),
             "pct_mfma_peak": round(100 * flops / mp / 1e12 / PEAK_TFLOPS["f32"], 2),
             "canonical_ms": round(mc * 1e3, 4), "speedup_vs_canonical": round(mc / mp, 3),
