@@ -415,7 +415,7 @@ def main():
     ap.add_argument("--stages", action="store_true", help="add the per-stage lists to every workload's record")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default=None,
-                    help="profiling aid: run just this workload (a workload name, attention_softmax_causal, "
+                    help="profiling aid: run just this workload (a workload name, attention_softmax_causal, llama_layer_causal_row_blocks, "
                          "llama_layer or llama_layer_fused_attention) --steps times in --mode and print its line")
     ap.add_argument("--mode", default="both", choices=["both", "propagated", "canonical"],
                     help="with --only: which chain mode(s) to run")
@@ -527,10 +527,17 @@ def main():
             name, options = "attention", {"softmax": True, "causal": True}
         elif name == "llama_layer_fused_attention":
             name, options = "llama_layer", {"flash": True}
+        elif name == "llama_layer_causal_row_blocks":
+            name, options = "llama_layer", {"causal_blocks": 4}
         inp, shape = inputs.make(name)
         ch = chains.build(name, inp, shape, **options)
         res = {"workload": args.only, "steps": args.steps}
         flops = inputs.gemm_flops(name, shape)
+        if options.get("causal_blocks"):
+            # only the GEMM flops that are executed: n blocks of query rows do (n + 1) / 2n of the two attention GEMMs
+            n = options["causal_blocks"]
+            dh = shape["hidden"] // shape["n_q"]
+            flops -= shape["n_q"] * 4.0 * shape["t"] * shape["t"] * dh * (1.0 - (n + 1) / (2.0 * n))
         if args.mode in ("both", "propagated"):
             t = time_chain(ch, api.LPG_CHAIN_PROPAGATED, args.steps, args.warmup)
             res.update({"ms_per_step": round(t * 1e3, 4), "tflops": round(flops / t / 1e12, 2)})
